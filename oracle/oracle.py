@@ -1,0 +1,197 @@
+"""ctypes front end of the plain CPU oracle (``asyncmesh_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY: imported by the tests, by the smoke check and by the benchmark's CPU
+baseline leg.  The product path never imports this module, and this module imports nothing of
+the product.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import subprocess
+from pathlib import Path
+
+import numpy as np
+
+_HERE = Path(__file__).resolve().parent
+_SRC = _HERE / "asyncmesh_oracle.c"
+_LIB = _HERE / "libasyncmesh_oracle.so"
+
+OPT_SGD, OPT_ADAMW, OPT_NADAMW = 0, 1, 2
+CORR_NONE, CORR_EMA = 0, 1
+
+
+def build(force: bool = False) -> Path:
+    """Compile the oracle with gcc (OpenMP over coordinates, no fast-math, no FMA contraction)."""
+    if force or not _LIB.exists() or _LIB.stat().st_mtime < _SRC.stat().st_mtime:
+        cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
+               "-Wall", "-Wextra", "-o", str(_LIB), str(_SRC), "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+class _Config(C.Structure):
+    _fields_ = [
+        ("n", C.c_uint64), ("mu0", C.c_uint64),
+        ("replicas", C.c_uint32), ("delay", C.c_uint32), ("avg_interval", C.c_uint32),
+        ("optimizer", C.c_uint32),
+        ("fraction", C.c_double), ("seed", C.c_uint64),
+        ("beta1", C.c_double), ("beta2", C.c_double), ("eps", C.c_double), ("weight_decay", C.c_double),
+        ("gamma", C.c_double),
+        ("lookahead", C.c_uint32), ("correction", C.c_uint32),
+        ("fwd_bf16", C.c_uint32), ("grad_bf16", C.c_uint32),
+        ("momentum_decay", C.c_double),
+    ]
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build()
+        L = C.CDLL(str(_LIB))
+        L.amo_philox4x32_10.argtypes = [C.POINTER(C.c_uint32), C.POINTER(C.c_uint32), C.POINTER(C.c_uint32)]
+        L.amo_threshold.argtypes = [C.c_double]; L.amo_threshold.restype = C.c_uint64
+        L.amo_member.argtypes = [C.c_uint64, C.c_uint64, C.c_uint64, C.c_uint64]; L.amo_member.restype = C.c_int
+        L.amo_subset.argtypes = [C.c_uint64, C.c_uint64, C.c_uint64, C.c_uint64, C.c_double, C.c_void_p, C.c_uint64]
+        L.amo_subset.restype = C.c_uint64
+        L.amo_bf16_to_float.argtypes = [C.c_uint16]; L.amo_bf16_to_float.restype = C.c_float
+        L.amo_double_to_bf16.argtypes = [C.c_double]; L.amo_double_to_bf16.restype = C.c_uint16
+        L.amo_create.argtypes = [C.POINTER(_Config)]; L.amo_create.restype = C.c_void_p
+        L.amo_destroy.argtypes = [C.c_void_p]
+        for name in ("amo_w", "amo_m", "amo_v", "amo_d", "amo_fwd"):
+            f = getattr(L, name)
+            f.argtypes = [C.c_void_p, C.c_uint32]
+            f.restype = C.POINTER(C.c_float)
+        L.amo_step.argtypes = [C.c_void_p, C.c_uint64, C.POINTER(C.c_void_p), C.c_double, C.c_double, C.c_double]
+        L.amo_step.restype = C.c_int
+        L.amo_sparse_average.argtypes = [C.c_void_p, C.c_uint64, C.c_double]; L.amo_sparse_average.restype = C.c_int
+        L.amo_lookahead.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_double]
+        L.amo_consensus_error.argtypes = [C.c_void_p]; L.amo_consensus_error.restype = C.c_double
+        _lib = L
+    return _lib
+
+
+def f32(x) -> float:
+    """A Python float holding exactly the fp32 value nearest to x (hyper-parameters cross the
+    product's C ABI as fp32; the oracle must be given those very values)."""
+    return float(np.float32(x))
+
+
+def philox4x32_10(counter, key):
+    c = (C.c_uint32 * 4)(*counter)
+    k = (C.c_uint32 * 2)(*key)
+    o = (C.c_uint32 * 4)()
+    lib().amo_philox4x32_10(c, k, o)
+    return tuple(int(x) for x in o)
+
+
+def threshold(p: float) -> int:
+    return int(lib().amo_threshold(p))
+
+
+def member(seed: int, s: int, mu: int, p: float) -> bool:
+    return bool(lib().amo_member(seed, s, mu, threshold(p)))
+
+
+def subset(seed: int, s: int, n: int, p: float, mu0: int = 0) -> np.ndarray:
+    """Ascending global indices of S^s inside [mu0, mu0+n)."""
+    L = lib()
+    count = L.amo_subset(seed, s, mu0, n, p, None, 0)
+    out = np.empty(count, dtype=np.uint64)
+    if count:
+        L.amo_subset(seed, s, mu0, n, p, out.ctypes.data, count)
+    return out
+
+
+def double_to_bf16(x: float) -> int:
+    return int(lib().amo_double_to_bf16(x))
+
+
+def bf16_to_float(h: int) -> float:
+    return float(lib().amo_bf16_to_float(h))
+
+
+def lookahead(w: np.ndarray, w_prev: np.ndarray, gamma: float, bf16: bool = False) -> np.ndarray:
+    w = np.ascontiguousarray(w, dtype=np.float32)
+    w_prev = np.ascontiguousarray(w_prev, dtype=np.float32)
+    if bf16:
+        out = np.empty(w.shape, dtype=np.uint16)
+        lib().amo_lookahead(None, out.ctypes.data, w.ctypes.data, w_prev.ctypes.data, w.size, gamma)
+    else:
+        out = np.empty(w.shape, dtype=np.float32)
+        lib().amo_lookahead(out.ctypes.data, None, w.ctypes.data, w_prev.ctypes.data, w.size, gamma)
+    return out
+
+
+class Oracle:
+    """One pipeline stage replicated R times, advanced one step at a time on the CPU."""
+
+    def __init__(self, n, replicas, delay=0, avg_interval=1, fraction=0.05, seed=0,
+                 optimizer=OPT_ADAMW, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01,
+                 lookahead=False, gamma=0.0, correction=CORR_EMA, fwd_bf16=False, grad_bf16=False,
+                 momentum_decay=0.004, mu0=0):
+        self.cfg = _Config(
+            n=n, mu0=mu0, replicas=replicas, delay=delay, avg_interval=avg_interval, optimizer=optimizer,
+            fraction=fraction, seed=seed, beta1=f32(beta1), beta2=f32(beta2), eps=f32(eps),
+            weight_decay=f32(weight_decay), gamma=f32(gamma), lookahead=int(bool(lookahead)),
+            correction=correction, fwd_bf16=int(bool(fwd_bf16)), grad_bf16=int(bool(grad_bf16)),
+            momentum_decay=momentum_decay)
+        self.n, self.R = n, replicas
+        self._h = lib().amo_create(C.byref(self.cfg))
+        if not self._h:
+            raise MemoryError("amo_create failed")
+
+    def close(self):
+        if self._h:
+            lib().amo_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _view(self, name, i) -> np.ndarray:
+        p = getattr(lib(), name)(self._h, i)
+        if self.n == 0:
+            return np.empty(0, dtype=np.float32)
+        return np.ctypeslib.as_array(p, shape=(self.n,))
+
+    def w(self, i): return self._view("amo_w", i)
+    def m(self, i): return self._view("amo_m", i)
+    def v(self, i): return self._view("amo_v", i)
+    def d(self, i): return self._view("amo_d", i)
+    def fwd(self, i): return self._view("amo_fwd", i)
+
+    def set_w(self, w0):
+        """Same starting point for every replica (1-D array), or one row per replica (2-D)."""
+        w0 = np.asarray(w0, dtype=np.float32)
+        for i in range(self.R):
+            self.w(i)[:] = w0 if w0.ndim == 1 else w0[i]
+
+    def step(self, t, grads, lr, lam=0.5, grad_scale=1.0):
+        want = np.uint16 if self.cfg.grad_bf16 else np.float32
+        keep = [np.ascontiguousarray(g, dtype=want) for g in grads]
+        assert len(keep) == self.R and all(g.size == self.n for g in keep)
+        ptrs = (C.c_void_p * self.R)(*[g.ctypes.data for g in keep])
+        rc = lib().amo_step(self._h, t, ptrs, f32(lr), f32(lam), f32(grad_scale))
+        if rc != 0:
+            raise ValueError(f"oracle step out of order: t={t}")
+
+    def sparse_average(self, t, lam=0.5):
+        rc = lib().amo_sparse_average(self._h, t, f32(lam))
+        if rc != 0:
+            raise ValueError(f"oracle sparse_average out of order: t={t}")
+
+    def consensus_error(self) -> float:
+        return float(lib().amo_consensus_error(self._h))
+
+
+def threads() -> int:
+    """How many OpenMP threads the oracle's coordinate loops use."""
+    L = lib()
+    L.amo_threads.restype = C.c_int
+    return int(L.amo_threads())

@@ -1,0 +1,460 @@
+"""Pins of the CPU oracle against things other than itself: published known-answer vectors,
+hand-worked traces, closed forms, special cases that reduce to a library routine, invariants
+stated by the paper's lemmas, and brute force on tiny inputs.  No GPU needed."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as si
+from oracle import oracle as O
+
+EMPTY_P = 1e-12      # floor(p * 2^32) = 0: the subset is empty, i.e. no averaging ever happens
+
+
+# --------------------------------------------------------------------------------------------
+# subset generator
+# --------------------------------------------------------------------------------------------
+def test_philox_known_answers(golden_dir):
+    rows = [l.split() for l in (golden_dir / "philox4x32_10_kat.txt").read_text().splitlines()
+            if l.strip() and not l.startswith("#")]
+    assert len(rows) == 3
+    for r in rows:
+        vals = [int(x, 16) for x in r]
+        assert O.philox4x32_10(vals[0:4], vals[4:6]) == tuple(vals[6:10])
+
+
+def test_threshold_edges():
+    assert O.threshold(1.0) == 2 ** 32
+    assert O.threshold(0.5) == 2 ** 31
+    assert O.threshold(0.05) == math.floor(0.05 * 2 ** 32)
+    assert O.threshold(EMPTY_P) == 0
+    assert O.subset(3, 7, 5000, EMPTY_P).size == 0
+    assert np.array_equal(O.subset(3, 7, 5000, 1.0), np.arange(5000, dtype=np.uint64))
+
+
+def test_membership_uses_the_stated_counter_layout():
+    """member(mu) must be lane mu&3 of philox(counter=(lo(mu>>2), hi(mu>>2), lo(s), hi(s)), key=seed)."""
+    seed, s = 0x1234_5678_9ABC_DEF0, (5 << 32) | 17
+    for mu in [0, 1, 2, 3, 4, 1023, (1 << 34) + 6, (1 << 40) + 3]:
+        g = mu >> 2
+        x = O.philox4x32_10((g & 0xFFFFFFFF, g >> 32, s & 0xFFFFFFFF, s >> 32), (seed & 0xFFFFFFFF, seed >> 32))
+        for p in (0.01, 0.3, 0.9):
+            assert O.member(seed, s, mu, p) == (x[mu & 3] < math.floor(p * 2 ** 32))
+
+
+def test_subset_list_is_the_predicate_brute_force():
+    n, p, seed, s = 1 << 14, 0.05, 11, 3
+    want = np.array([mu for mu in range(n) if O.member(seed, s, mu, p)], dtype=np.uint64)
+    got = O.subset(seed, s, n, p)
+    assert np.array_equal(got, want)
+    assert np.all(np.diff(got.astype(np.int64)) > 0)
+    # a slice of the stage sees the same global subset
+    lo, ln = 4099, 3001
+    assert np.array_equal(O.subset(seed, s, ln, p, mu0=lo), want[(want >= lo) & (want < lo + ln)])
+
+
+def test_subset_statistics():
+    n, p = 200_000, 0.05
+    sets = [O.subset(0, t, n, p) for t in range(1, 41)]
+    sigma = math.sqrt(n * p * (1 - p))
+    for S in sets:
+        assert abs(S.size - n * p) < 5 * sigma                      # |S| ~ Binomial(n, p)
+    assert not np.array_equal(sets[0], sets[1])                         # redrawn every step
+    assert not np.array_equal(O.subset(1, 1, n, p), sets[0])            # depends on the seed
+    assert np.array_equal(O.subset(0, 1, n, p), sets[0])                # pure function of (seed, t)
+    # every coordinate is included with frequency ~ p: chi-square-like bound on the histogram
+    hits = np.zeros(n, dtype=np.int64)
+    for S in sets:
+        hits[S.astype(np.int64)] += 1
+    assert abs(hits.mean() - 40 * p) < 5 * math.sqrt(40 * p * (1 - p) / n)
+    # inclusion is independent between neighbours inside one Philox block (lanes 0..3)
+    a = np.zeros(n, dtype=bool); a[sets[0].astype(np.int64)] = True
+    both = np.count_nonzero(a[0::4] & a[1::4])
+    assert abs(both - (n / 4) * p * p) < 6 * math.sqrt((n / 4) * p * p)
+
+
+# --------------------------------------------------------------------------------------------
+# bf16 helpers against a library conversion
+# --------------------------------------------------------------------------------------------
+def test_bf16_rounding_matches_library():
+    rng = np.random.default_rng(5)
+    x = np.concatenate([rng.standard_normal(4000).astype(np.float32) * np.float32(0.02),
+                        np.array([0.0, -0.0, 1.0, -1.0, 1.00390625, 1.01171875, 3.3895314e38, 1e-40],
+                                 dtype=np.float32)])
+    want = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    got = np.array([O.double_to_bf16(float(v)) for v in x], dtype=np.uint16)
+    assert np.array_equal(got, want)
+    assert np.array_equal(si.to_bf16_bits(x), want)
+    back = np.array([O.bf16_to_float(int(h)) for h in want[:100]], dtype=np.float32)
+    assert np.array_equal(back, si.bf16_bits_to_f32(want[:100]))
+    # ties go to even: 1 + 2^-8 is halfway between 1 and 1 + 2^-7
+    assert O.double_to_bf16(1.0 + 2.0 ** -8) == 0x3F80
+    assert O.double_to_bf16(1.0 + 3 * 2.0 ** -8) == 0x3F82
+    # one rounding, not two: just above the tie must round up even if fp32 would land on the tie
+    assert O.double_to_bf16(1.0 + 2.0 ** -8 + 2.0 ** -40) == 0x3F81
+
+
+# --------------------------------------------------------------------------------------------
+# local step alone == a stand-alone optimizer run (library routine)
+# --------------------------------------------------------------------------------------------
+def _torch_run(make_opt, w0, grads_per_step):
+    p = torch.nn.Parameter(torch.from_numpy(w0.copy()))
+    opt = make_opt([p])
+    for g in grads_per_step:
+        p.grad = torch.from_numpy(g.copy())
+        opt.step()
+    return p.detach().numpy()
+
+
+@pytest.mark.parametrize("name", ["sgd", "sgd_momentum", "adamw", "nadamw"])
+def test_local_step_equals_library_optimizer(name):
+    n, R, steps, lr = 3000, 2, 12, 3e-3
+    w0 = si.stage_weights(n, seed=1)
+    grads = [si.replica_grads(n, R, t, seed=1) for t in range(1, steps + 1)]
+    b1, b2, eps = O.f32(0.9), O.f32(0.999), O.f32(1e-8)
+    if name == "sgd":
+        kw = dict(optimizer=O.OPT_SGD, beta1=0.0, weight_decay=0.0)
+        mk = lambda ps: torch.optim.SGD(ps, lr=O.f32(lr), foreach=False)
+    elif name == "sgd_momentum":
+        kw = dict(optimizer=O.OPT_SGD, beta1=0.9, weight_decay=0.0)
+        mk = lambda ps: torch.optim.SGD(ps, lr=O.f32(lr), momentum=b1, foreach=False)
+    elif name == "adamw":
+        kw = dict(optimizer=O.OPT_ADAMW, weight_decay=0.01)
+        mk = lambda ps: torch.optim.AdamW(ps, lr=O.f32(lr), betas=(b1, b2), eps=eps,
+                                          weight_decay=O.f32(0.01), foreach=False)
+    else:
+        kw = dict(optimizer=O.OPT_NADAMW, weight_decay=0.01)
+        mk = lambda ps: torch.optim.NAdam(ps, lr=O.f32(lr), betas=(b1, b2), eps=eps,
+                                          weight_decay=O.f32(0.01), decoupled_weight_decay=True,
+                                          momentum_decay=0.004, foreach=False)
+    orc = O.Oracle(n, R, delay=1, fraction=EMPTY_P, **kw)       # empty subset: averaging never acts
+    orc.set_w(w0)
+    for t in range(1, steps + 1):
+        orc.step(t, grads[t - 1], lr)
+    for i in range(R):
+        want = _torch_run(mk, w0, [g[i] for g in grads])
+        got = orc.w(i)
+        scale = np.maximum(np.abs(want), np.sqrt(np.mean(want ** 2)))
+        assert np.max(np.abs(got - want) / scale) < 2e-6
+        assert np.array_equal(orc.fwd(i), got)                 # look-ahead off: fwd is w
+        assert not np.any(orc.d(i))
+
+
+def test_first_adamw_step_closed_form():
+    """From zero moments, one AdamW step is w(1 - lr wd) - lr g / (|g| + eps)."""
+    n, lr, wd, eps = 1000, O.f32(1e-3), O.f32(0.01), O.f32(1e-8)
+    w0 = si.stage_weights(n, seed=2)
+    g = si.replica_grads(n, 1, 1, seed=2)[0]
+    orc = O.Oracle(n, 1, fraction=EMPTY_P, optimizer=O.OPT_ADAMW, weight_decay=0.01)
+    orc.set_w(w0)
+    orc.step(1, [g], 1e-3)
+    w64, g64 = w0.astype(np.float64), g.astype(np.float64)
+    want = w64 * (1 - lr * wd) - lr * g64 / (np.abs(g64) + eps)
+    assert np.max(np.abs(orc.w(0) - want)) < 1e-7 * 0.02
+
+
+def test_grad_scale_and_bf16_grads():
+    n = 512
+    w0 = si.stage_weights(n, seed=3)
+    g = si.replica_grads(n, 1, 1, seed=3)[0]
+    a = O.Oracle(n, 1, fraction=EMPTY_P, optimizer=O.OPT_SGD, beta1=0.0, weight_decay=0.0)
+    a.set_w(w0); a.step(1, [g * np.float32(0.5)], 0.25)
+    b = O.Oracle(n, 1, fraction=EMPTY_P, optimizer=O.OPT_SGD, beta1=0.0, weight_decay=0.0)
+    b.set_w(w0); b.step(1, [g], 0.25, grad_scale=0.5)
+    assert np.array_equal(a.w(0), b.w(0))
+    gb = si.to_bf16_bits(g)
+    c = O.Oracle(n, 1, fraction=EMPTY_P, optimizer=O.OPT_SGD, beta1=0.0, weight_decay=0.0, grad_bf16=True)
+    c.set_w(w0); c.step(1, [gb], 0.25)
+    e = O.Oracle(n, 1, fraction=EMPTY_P, optimizer=O.OPT_SGD, beta1=0.0, weight_decay=0.0)
+    e.set_w(w0); e.step(1, [si.bf16_bits_to_f32(gb)], 0.25)
+    assert np.array_equal(c.w(0), e.w(0))
+
+
+# --------------------------------------------------------------------------------------------
+# synchronous special cases of the averaging (tau = 0)
+# --------------------------------------------------------------------------------------------
+def test_full_subset_no_delay_is_dense_averaging_and_large_batch_sgd():
+    """p = 1, tau = 0: every replica ends on the mean of the local results; with plain SGD from a
+    common start that is one SGD step on the mean gradient (synchronous data parallelism)."""
+    n, R, lr = 2048, 4, O.f32(0.5)
+    w0 = si.stage_weights(n, seed=4)
+    orc = O.Oracle(n, R, delay=0, fraction=1.0, optimizer=O.OPT_SGD, beta1=0.0, weight_decay=0.0)
+    orc.set_w(w0)
+    w = w0.astype(np.float64)
+    for t in range(1, 4):
+        g = si.replica_grads(n, R, t, seed=4)
+        orc.step(t, g, lr)
+        w = w - lr * np.mean(np.stack(g).astype(np.float64), axis=0)
+        for i in range(R):
+            assert np.max(np.abs(orc.w(i) - w)) < 2e-8      # a few fp32 roundings of values ~0.05
+            assert np.array_equal(orc.w(i), orc.w(0))
+            assert not np.any(orc.d(i))          # staleness is zero, so the EMA stays zero
+    assert orc.consensus_error() == 0.0
+
+
+def test_no_delay_is_sparta():
+    """tau = 0, any p: subset coordinates take the current mean, the others keep the local result."""
+    n, R, p, lr, seed = 5000, 3, 0.2, O.f32(0.25), 21
+    w0 = np.stack([si.stage_weights(n, seed=10 + i) for i in range(R)])     # replicas already apart
+    orc = O.Oracle(n, R, delay=0, fraction=p, seed=seed, optimizer=O.OPT_SGD, beta1=0.0, weight_decay=0.0)
+    orc.set_w(w0)
+    cur = w0.copy()
+    for t in range(1, 4):
+        g = np.stack(si.replica_grads(n, R, t, seed=6))
+        what = (cur.astype(np.float64) - lr * g.astype(np.float64)).astype(np.float32)
+        S = O.subset(seed, t, n, p).astype(np.int64)
+        want = what.copy()
+        want[:, S] = np.mean(what[:, S].astype(np.float64), axis=0).astype(np.float32)
+        orc.step(t, list(g), lr)
+        got = np.stack([orc.w(i) for i in range(R)])
+        assert np.array_equal(got, want)
+        assert not any(np.any(orc.d(i)) for i in range(R))
+        cur = got
+
+
+def test_sparse_average_shrinks_consensus_error_as_the_lemma_says():
+    """After a synchronous sparse average the consensus error is exactly the part carried by the
+    coordinates that were not selected, which is (1 - p) of the error before, on expectation."""
+    n, R, p, seed = 400_000, 4, 0.1, 5
+    w = np.stack([si.stage_weights(n, seed=30 + i) for i in range(R)])
+    orc = O.Oracle(n, R, delay=0, fraction=p, seed=seed, optimizer=O.OPT_SGD)
+    orc.set_w(w)
+    before = orc.consensus_error()
+    orc.sparse_average(1)
+    after = orc.consensus_error()
+    keep = np.ones(n, dtype=bool)
+    keep[O.subset(seed, 1, n, p).astype(np.int64)] = False
+    w64 = w.astype(np.float64)
+    carried = np.sum((w64[:, keep] - w64[:, keep].mean(axis=0)) ** 2)
+    assert abs(after - carried) < 1e-6 * carried       # fp32 rounding of the mean only
+    assert abs(after / before - (1 - p)) < 0.01
+
+
+# --------------------------------------------------------------------------------------------
+# delayed averaging with EMA correction
+# --------------------------------------------------------------------------------------------
+def _read_trace(golden_dir):
+    rows, extra = [], []
+    for l in (golden_dir / "ema_trace_two_replicas.txt").read_text().splitlines():
+        if not l.strip() or l.startswith("#"):
+            continue
+        f = l.split()
+        (extra if f[0] in ("none", "diff") else rows).append(f)
+    return rows, extra
+
+
+def _trace_oracle(**kw):
+    orc = O.Oracle(1, 2, delay=1, avg_interval=1, fraction=1.0, optimizer=O.OPT_SGD, beta1=0.0,
+                   weight_decay=0.0, **kw)
+    orc.set_w(np.array([1.0], dtype=np.float32))
+    return orc
+
+
+def test_hand_worked_ema_trace(golden_dir):
+    rows, extra = _read_trace(golden_dir)
+    orc = _trace_oracle(correction=O.CORR_EMA)
+    none = _trace_oracle(correction=O.CORR_NONE)
+    diff = _trace_oracle(correction=O.CORR_EMA)
+    for r in rows:
+        t = int(r[0]); g0, g1, wh0, wh1, w0, w1, d0, d1 = map(float, r[1:])
+        grads = [np.array([g0], np.float32), np.array([g1], np.float32)]
+        orc.step(t, grads, 0.5, lam=0.5)
+        assert (orc.w(0)[0], orc.w(1)[0]) == (w0, w1)
+        assert (orc.d(0)[0], orc.d(1)[0]) == (d0, d1)
+        none.step(t, grads, 0.5, lam=0.5)
+        for e in extra:
+            if e[0] == "none" and int(e[1]) == t:
+                assert (none.w(0)[0], none.w(1)[0]) == (float(e[2]), float(e[3]))
+        if t <= 2:
+            diff.step(t, grads, 0.5, lam=1.0)
+            for e in extra:
+                if e[0] == "diff" and int(e[1]) == t:
+                    assert (diff.w(0)[0], diff.w(1)[0]) == (float(e[2]), float(e[3]))
+    # consensus identity of the EMA theorem's proof: w_i - mean w = d_i - mean d on received coordinates
+    w = np.array([orc.w(0)[0], orc.w(1)[0]]); d = np.array([orc.d(0)[0], orc.d(1)[0]])
+    assert np.array_equal(w - w.mean(), d - d.mean())
+
+
+def test_nothing_is_received_before_anything_was_sent():
+    n, R, tau, K = 600, 3, 2, 2
+    w0 = si.stage_weights(n, seed=7)
+    orc = O.Oracle(n, R, delay=tau, avg_interval=K, fraction=1.0, optimizer=O.OPT_SGD, beta1=0.0, weight_decay=0.0)
+    ref = O.Oracle(n, R, delay=tau, avg_interval=K, fraction=EMPTY_P, optimizer=O.OPT_SGD, beta1=0.0, weight_decay=0.0)
+    orc.set_w(w0); ref.set_w(w0)
+    for t in range(1, tau * K + K + 2):
+        g = si.replica_grads(n, R, t, seed=7)
+        orc.step(t, g, 0.1); ref.step(t, g, 0.1)
+        same = all(np.array_equal(orc.w(i), ref.w(i)) for i in range(R))
+        # first receive happens at the first averaging step t with t - tau*K >= 1, i.e. t = tau*K + K
+        assert same == (t < tau * K + K)
+
+
+def test_interval_and_delay_in_rounds():
+    """K = 2, tau = 1: odd steps are purely local; at t = 4 the mean sent at t = 2 arrives."""
+    n, R, p, seed, lr, lam = 800, 2, 0.5, 9, O.f32(0.125), O.f32(0.25)
+    w0 = si.stage_weights(n, seed=8)
+    orc = O.Oracle(n, R, delay=1, avg_interval=2, fraction=p, seed=seed, optimizer=O.OPT_SGD, beta1=0.0, weight_decay=0.0)
+    orc.set_w(w0)
+    cur = np.stack([w0] * R)
+    whats = {}
+    for t in range(1, 5):
+        g = np.stack(si.replica_grads(n, R, t, seed=8))
+        what = (cur.astype(np.float64) - lr * g.astype(np.float64)).astype(np.float32)
+        whats[t] = what
+        want = what.copy()
+        if t == 4:
+            S = O.subset(seed, 2, n, p).astype(np.int64)
+            abar = whats[2][:, S].astype(np.float64).mean(axis=0).astype(np.float32)
+            d = (lam * (what[:, S].astype(np.float64) - whats[2][:, S].astype(np.float64))).astype(np.float32)
+            want[:, S] = (abar.astype(np.float64) + d.astype(np.float64)).astype(np.float32)
+        orc.step(t, list(g), lr, lam=lam)
+        got = np.stack([orc.w(i) for i in range(R)])
+        assert np.array_equal(got, want), t
+        cur = got
+
+
+def test_lambda_one_leaves_the_replica_mean_untouched():
+    """lambda = 1 ("difference only"): w_i[S] = abar_old + w^_i^t - w^_i^old, whose replica mean is
+    the current mean of the local results: the sparse step moves no mass."""
+    n, R, tau, p = 3000, 4, 2, 0.3
+    w0 = si.stage_weights(n, seed=12)
+    a = O.Oracle(n, R, delay=tau, fraction=p, seed=1, optimizer=O.OPT_SGD, beta1=0.0, weight_decay=0.0)
+    b = O.Oracle(n, R, delay=tau, fraction=EMPTY_P, seed=1, optimizer=O.OPT_SGD, beta1=0.0, weight_decay=0.0)
+    a.set_w(w0); b.set_w(w0)
+    for t in range(1, 9):
+        g = si.replica_grads(n, R, t, seed=12)
+        a.step(t, g, 0.05, lam=1.0); b.step(t, g, 0.05, lam=1.0)
+        ma = np.mean(np.stack([a.w(i) for i in range(R)]).astype(np.float64), axis=0)
+        mb = np.mean(np.stack([b.w(i) for i in range(R)]).astype(np.float64), axis=0)
+        assert np.max(np.abs(ma - mb)) < 2e-8
+
+
+def test_consensus_identity_on_received_subset():
+    n, R, tau, p, seed = 4000, 5, 3, 0.25, 77
+    w0 = si.stage_weights(n, seed=13)
+    orc = O.Oracle(n, R, delay=tau, fraction=p, seed=seed, optimizer=O.OPT_ADAMW)
+    orc.set_w(w0)
+    for t in range(1, 11):
+        orc.step(t, si.replica_grads(n, R, t, seed=13), 1e-3, lam=0.5)
+        if t > tau:
+            S = O.subset(seed, t - tau, n, p).astype(np.int64)
+            w = np.stack([orc.w(i)[S] for i in range(R)]).astype(np.float64)
+            d = np.stack([orc.d(i)[S] for i in range(R)]).astype(np.float64)
+            assert np.max(np.abs((w - w.mean(0)) - (d - d.mean(0)))) < 5e-9
+
+
+def test_identical_replicas_stay_identical():
+    n, R = 1000, 3
+    w0 = si.stage_weights(n, seed=14)
+    orc = O.Oracle(n, R, delay=2, fraction=0.3, seed=4, optimizer=O.OPT_ADAMW)
+    orc.set_w(w0)
+    for t in range(1, 8):
+        g = si.replica_grads(n, 1, t, seed=14)[0]
+        orc.step(t, [g] * R, 1e-3)
+        for i in range(1, R):
+            assert np.array_equal(orc.w(i), orc.w(0)) and np.array_equal(orc.d(i), orc.d(0))
+    assert np.any(orc.d(0))
+
+
+def test_ema_closed_form_under_constant_staleness():
+    """If the local weights advance by the same c between send and receive on every visit, the EMA
+    after n visits is c (1 - (1 - lambda)^n)."""
+    c, lam = 0.25, 0.5
+    orc = O.Oracle(1, 1, delay=1, fraction=1.0, optimizer=O.OPT_SGD)
+    for t in range(1, 9):
+        orc.w(0)[0] = np.float32(1.0 + c * t) if t == 1 else np.float32(orc.w(0)[0])
+        if t > 1:
+            # replace the averaged value by "previous local value + c": local progress of exactly c
+            orc.w(0)[0] = np.float32(prev_local + c)
+        prev_local = float(orc.w(0)[0])
+        orc.sparse_average(t, lam=lam)
+        visits = t - 1
+        assert orc.d(0)[0] == c * (1 - (1 - lam) ** visits)
+        if visits:
+            assert orc.w(0)[0] == np.float32((prev_local - c) + orc.d(0)[0])     # old mean + EMA
+
+
+def test_no_correction_is_plain_delayed_averaging():
+    n, R, tau, p, seed, lr = 1500, 3, 2, 0.4, 15, O.f32(0.125)
+    w0 = si.stage_weights(n, seed=15)
+    orc = O.Oracle(n, R, delay=tau, fraction=p, seed=seed, optimizer=O.OPT_SGD, beta1=0.0, weight_decay=0.0,
+                   correction=O.CORR_NONE)
+    orc.set_w(w0)
+    cur, whats = np.stack([w0] * R), {}
+    for t in range(1, 7):
+        g = np.stack(si.replica_grads(n, R, t, seed=15))
+        what = (cur.astype(np.float64) - lr * g.astype(np.float64)).astype(np.float32)
+        whats[t] = what
+        want = what.copy()
+        if t > tau:
+            S = O.subset(seed, t - tau, n, p).astype(np.int64)
+            want[:, S] = whats[t - tau][:, S].astype(np.float64).mean(axis=0).astype(np.float32)
+        orc.step(t, list(g), lr)
+        cur = np.stack([orc.w(i) for i in range(R)])
+        assert np.array_equal(cur, want)
+        assert not any(np.any(orc.d(i)) for i in range(R))
+
+
+# --------------------------------------------------------------------------------------------
+# look-ahead
+# --------------------------------------------------------------------------------------------
+def test_lookahead_scalars():
+    # w_old = 1, g = 0.5, lr = 0.5 -> w^ = 0.75, displacement -0.25; gamma = 0.5 -> fwd = 0.625
+    orc = O.Oracle(1, 1, fraction=EMPTY_P, optimizer=O.OPT_SGD, beta1=0.0, weight_decay=0.0, lookahead=True, gamma=0.5)
+    orc.set_w(np.array([1.0], np.float32))
+    orc.step(1, [np.array([0.5], np.float32)], 0.5)
+    assert orc.w(0)[0] == 0.75 and orc.fwd(0)[0] == 0.625
+    # on a received coordinate only the optimizer's displacement is extrapolated, not the averaging jump:
+    # second step of the hand-worked trace: w = 0.875, displacement 0.5 - 0.75 = -0.25 -> fwd = 0.75
+    tr = O.Oracle(1, 2, delay=1, fraction=1.0, optimizer=O.OPT_SGD, beta1=0.0, weight_decay=0.0, lookahead=True, gamma=0.5)
+    tr.set_w(np.array([1.0], np.float32))
+    tr.step(1, [np.array([0.5], np.float32), np.array([-0.5], np.float32)], 0.5)
+    tr.step(2, [np.array([0.5], np.float32), np.array([0.5], np.float32)], 0.5)
+    assert tr.w(0)[0] == 0.875 and tr.fwd(0)[0] == 0.75
+    # gamma = 0 and look-ahead off both give fwd = w
+    z = O.Oracle(4, 1, fraction=EMPTY_P, optimizer=O.OPT_ADAMW, lookahead=True, gamma=0.0)
+    z.set_w(si.stage_weights(4, seed=1)); z.step(1, si.replica_grads(4, 1, 1), 1e-3)
+    assert np.array_equal(z.fwd(0), z.w(0))
+    # stateless two-point form
+    out = O.lookahead(np.array([0.75], np.float32), np.array([1.0], np.float32), 0.5)
+    assert out[0] == 0.625
+
+
+def test_explicit_lookahead_is_nesterov_momentum():
+    """Heavy-ball SGD whose gradient is taken at fwd = w + gamma (w^ - w_prev) is textbook Nesterov
+    momentum  v <- mu v - lr grad f(w + mu v),  w <- w + v  (here f(w) = w^2 / 2, grad f = identity)."""
+    mu, lr, steps = 0.5, 0.25, 12
+    w0 = np.array([1.0, -2.0, 0.5], dtype=np.float32)
+    orc = O.Oracle(3, 1, fraction=EMPTY_P, optimizer=O.OPT_SGD, beta1=mu, weight_decay=0.0, lookahead=True, gamma=mu)
+    orc.set_w(w0)
+    w, v = w0.astype(np.float64), np.zeros(3)
+    point = w0.copy()                                   # first gradient is taken at w0 (v = 0)
+    for t in range(1, steps + 1):
+        orc.step(t, [point.copy()], lr)                 # grad f at the look-ahead point
+        point = orc.fwd(0).copy()
+        v = mu * v - lr * (w + mu * v)
+        w = w + v
+        assert np.max(np.abs(orc.w(0) - w)) < 1e-6
+        assert np.max(np.abs(orc.fwd(0) - (w + mu * v))) < 1e-6
+
+
+def test_bf16_forward_copy():
+    n = 2000
+    w0 = si.stage_weights(n, seed=16)
+    a = O.Oracle(n, 1, fraction=EMPTY_P, optimizer=O.OPT_ADAMW, lookahead=True, gamma=0.9, fwd_bf16=True)
+    b = O.Oracle(n, 1, fraction=EMPTY_P, optimizer=O.OPT_ADAMW, lookahead=True, gamma=0.9)
+    a.set_w(w0); b.set_w(w0)
+    g = si.replica_grads(n, 1, 1, seed=16)
+    a.step(1, g, 1e-3); b.step(1, g, 1e-3)
+    assert np.array_equal(a.w(0), b.w(0))
+    f = a.fwd(0)
+    assert np.array_equal(si.bf16_bits_to_f32(si.to_bf16_bits(f)), f)       # representable in bf16
+    assert np.max(np.abs(f - b.fwd(0)) / np.abs(b.fwd(0))) <= 2.0 ** -8     # within half a bf16 ulp
+
+
+def test_step_order_is_enforced():
+    orc = O.Oracle(4, 1)
+    with pytest.raises(ValueError):
+        orc.step(2, si.replica_grads(4, 1, 1), 1e-3)
