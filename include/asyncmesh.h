@@ -1,0 +1,156 @@
+/*
+ * asyncmesh.h -- C ABI of the MI355X (gfx950) implementation of the AsyncMesh per-stage update.
+ *
+ * One pipeline stage of n parameters is replicated R times (R = m, the number of data-parallel
+ * replicas in the paper's 2D mesh).  Every training step each replica
+ *   (1) takes its local optimizer step        w^_i^t = OPT(w_i^{t-1}, g_i^{t-1})
+ *                                             [sparse-averaging equation, first line],
+ *   (2) sends w^_i^t[S^t], a random subset of its coordinates, towards the other replicas
+ *                                             [Sec. "Asynchronous sparse averaging"],
+ *   (3) receives the average that was sent tau averaging rounds ago and applies it with the
+ *       EMA-of-staleness correction           [Sec. "Delay correction via estimating average
+ *                                              staleness": the EMA and estimated-average equations
+ *                                              and the corrected update that follows them],
+ *   (4) extrapolates the optimizer's displacement to get the weights of the next forward pass
+ *                                             [Sec. "Asynchronous pipeline parallelism": NAG-style
+ *                                              look-ahead of the last update direction].
+ * The R replicas and the delay buffer ("we simulate the asynchronous setup via buffering",
+ * appendix, wall-clock paragraph) live side by side in the memory of ONE GPU.
+ *
+ * General conventions
+ *   - Every pointer marked DEVICE is memory of the GPU that was current at am_init_state; it is
+ *     owned by the caller, must stay valid until am_destroy, and must be 16-byte aligned
+ *     (bf16 arrays: 8-byte aligned).  Pointers marked HOST are ordinary host memory, read during
+ *     the call only.
+ *   - All work is enqueued on the stream given to am_init_state (am_lookahead: its own argument).
+ *     No call synchronises with the device, allocates device memory, or copies to the host,
+ *     except am_read_flags and am_get_profile, which say so.
+ *   - Every function returns AM_OK (0) or a negative am_status; on an error nothing is enqueued
+ *     and the state is unchanged.  am_last_error() gives a message for the calling thread.
+ *   - No exception crosses this boundary.
+ */
+#ifndef ASYNCMESH_H
+#define ASYNCMESH_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define AM_MAX_REPLICAS 32u
+
+typedef struct am_state am_state;      /* opaque, host side, owned by the library */
+
+typedef enum {
+    AM_OK      =  0,
+    AM_EINVAL  = -1,    /* bad argument or configuration                                   */
+    AM_EALIGN  = -2,    /* a device pointer is not aligned as required                     */
+    AM_ENOMEM  = -3,    /* workspace too small / host allocation failed                    */
+    AM_EORDER  = -4,    /* step index is not the previous one plus one                     */
+    AM_EHIP    = -5     /* a HIP runtime call failed (message has the HIP error string)    */
+} am_status;
+
+/* local optimizer (experimental-setup appendix: NAdamW with momentum 0.99 for asynchronous
+ * pipelines, AdamW for synchronous ones; SGD is what the equations are written for)         */
+typedef enum {
+    AM_OPT_SGD    = 0,  /* m <- beta1 m + g ; w^ = w (1 - lr wd) - lr m   (beta1 = 0: plain SGD, m untouched) */
+    AM_OPT_ADAMW  = 1,  /* Adam moments, bias correction, decoupled weight decay              */
+    AM_OPT_NADAMW = 2   /* Adam with Nesterov momentum (Dozat's schedule), decoupled decay    */
+} am_opt;
+
+typedef enum {
+    AM_CORR_NONE = 0,   /* subset <- old average                 (asynchronous sparse averaging equation) */
+    AM_CORR_EMA  = 1    /* subset <- old average + EMA of staleness   (EMA equation + corrected update)    */
+} am_corr;
+
+typedef enum { AM_F32 = 0, AM_BF16 = 1 } am_dtype;
+
+typedef struct {
+    uint64_t n;              /* d_j: parameters of the stage, per replica; 1 <= n < 2^32 - 2^20          */
+    uint32_t replicas;       /* m = R, 1 .. AM_MAX_REPLICAS                                              */
+    uint32_t delay;          /* tau >= 0, counted in averaging rounds (tau*K steps)                      */
+    uint32_t avg_interval;   /* K >= 1: averaging happens at steps t with t mod K == 0                   */
+    uint32_t optimizer;      /* am_opt                                                                   */
+    double   fraction;       /* p in (0, 1]: every coordinate is in S^t independently with probability p */
+    uint64_t seed;           /* shared by all replicas of the stage; S^t is a pure function of (seed, t) */
+    float    beta1, beta2, eps, weight_decay;
+    float    gamma;          /* look-ahead coefficient (used when lookahead != 0)                        */
+    uint32_t lookahead;      /* 0: fwd = w ; 1: fwd = w + gamma (w^ - w_before_step)                     */
+    uint32_t correction;     /* am_corr                                                                  */
+    uint32_t fwd_dtype;      /* am_dtype of the fwd arrays                                               */
+    uint32_t grad_dtype;     /* am_dtype of the gradient arrays                                          */
+    double   momentum_decay; /* NADAMW only: psi of mu_t = beta1 (1 - 0.5 * 0.96^(t psi)); usual 0.004   */
+} am_config;
+
+/* The subset: S^t = { mu in [0, n) : X(seed, t, mu) < floor(p * 2^32) }, X = word (mu & 3) of
+ * Philox4x32-10 with counter (lo32(mu>>2), hi32(mu>>2), lo32(t), hi32(t)) and key (lo32(seed),
+ * hi32(seed)).  This is the sampling model of the sparse-averaging lemma (each element in the
+ * subset with probability p, independently). */
+
+typedef struct {
+    /* HOST arrays of `replicas` DEVICE pointers each; every pointed-to array has n elements.   */
+    float *const *w;        /* master weights, fp32, in: w^{t-1}, out: w^t                       */
+    float *const *m;        /* first moment / momentum, fp32 (may be NULL for SGD with beta1=0)  */
+    float *const *v;        /* second moment, fp32 (may be NULL for SGD)                         */
+    float *const *d;        /* EMA of staleness d_i, fp32 (may be NULL when correction = NONE)   */
+    void  *const *fwd;      /* weights for the next forward pass, fwd_dtype; NULL = not produced
+                               (allowed only with lookahead = 0 and fwd_dtype = AM_F32)          */
+    void    *workspace;     /* DEVICE, 256-byte aligned: delay ring + subset offsets + flags     */
+    uint64_t workspace_bytes;
+} am_buffers;
+
+/* Bytes of workspace a configuration needs.  The delay ring inside it holds tau+1 slots of
+ * capacity(n, p) * R packed fp32 values, capacity = min(n, p n + 12 sqrt(n p (1-p)) + 1024). */
+am_status am_workspace_bytes(const am_config *cfg, uint64_t *out_bytes);
+
+/* Validate, bind the caller's buffers and the stream, and enqueue the zeroing of m, v, d (d^0 = 0,
+ * experimental-setup appendix) and of the workspace.  w is left as given.  hip_stream is a
+ * hipStream_t (NULL = the default stream).  The next step index is 1. */
+am_status am_init_state(const am_config *cfg, const am_buffers *buf, void *hip_stream, am_state **out);
+
+/* One fused step t (= previous t + 1): parts (1)-(4) above for all R replicas.
+ *   grads      HOST array of R DEVICE pointers to n gradients each (grad_dtype), read only;
+ *              reusable by the caller once the stream has passed this call.
+ *   lr         eta for this step (the caller owns the schedule)
+ *   lambda_t   EMA coefficient in [0, 1] for this step (the paper: 0.5, then cosine decay to 0.01)
+ *   grad_scale gradients are multiplied by this first (e.g. a clipping factor); 1 = none */
+am_status am_step(am_state *st, uint64_t t, const void *const *grads,
+                  float lr, float lambda_t, float grad_scale);
+
+/* Parts (2)-(3) alone, acting on the current w, which plays the role of w^ (for callers that run
+ * their own optimizer).  Counts as step t.  m, v, fwd are not touched. */
+am_status am_sparse_average(am_state *st, uint64_t t, float lambda_t);
+
+/* Stateless part (4) in its literal two-point form: out = w + gamma (w - w_prev), n elements.
+ * out (DEVICE, out_dtype) may alias neither input. */
+am_status am_lookahead(void *out, uint32_t out_dtype, const float *w, const float *w_prev,
+                       uint64_t n, float gamma, void *hip_stream);
+
+/* Materialise S^t in ascending order: dev_out[0 .. count) (DEVICE, uint64, room for `capacity`
+ * indices; more are dropped) and *dev_count = |S^t| (DEVICE, one uint64).  Any t >= 0. */
+am_status am_subset_indices(am_state *st, uint64_t t, uint64_t *dev_out, uint64_t capacity,
+                            uint64_t *dev_count);
+
+/* Synchronises the stream and returns sticky flags: bit 0 = some |S^t| exceeded the ring slot
+ * capacity (the excess coordinates were left out of that round's average). */
+am_status am_read_flags(am_state *st, uint32_t *out_flags);
+
+/* Optional timing of the fused step kernel alone: while on, am_step brackets that kernel with
+ * events on its stream.  am_get_profile synchronises, returns the summed kernel time in
+ * milliseconds and the number of launches since profiling was switched on, and resets both. */
+am_status am_set_profiling(am_state *st, int on);
+am_status am_get_profile(am_state *st, double *out_kernel_ms, uint64_t *out_launches);
+
+/* Slot capacity (coordinates) and number of ring slots of this state; host values, no device work. */
+am_status am_ring_info(const am_state *st, uint64_t *out_capacity, uint32_t *out_slots);
+
+am_status am_destroy(am_state *st);
+
+const char *am_last_error(void);      /* message of the last failing call on this thread */
+const char *am_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ASYNCMESH_H */

@@ -1,0 +1,227 @@
+"""Thin ctypes binding of libasyncmesh.so (include/asyncmesh.h).
+
+Argument marshalling only: every step of the update runs in the library's HIP kernels.  PyTorch
+is used to own device memory and to name the stream.  There is no CPU fallback: importing this
+module without the built library raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+from pathlib import Path
+
+import torch
+
+_PKG = Path(__file__).resolve().parent
+_LIB_PATH = _PKG / "libasyncmesh.so"
+
+MAX_REPLICAS = 32
+OPT_SGD, OPT_ADAMW, OPT_NADAMW = 0, 1, 2
+CORR_NONE, CORR_EMA = 0, 1
+F32, BF16 = 0, 1
+
+EXPORTS = (
+    "am_workspace_bytes", "am_init_state", "am_step", "am_sparse_average", "am_lookahead",
+    "am_subset_indices", "am_read_flags", "am_set_profiling", "am_get_profile", "am_ring_info",
+    "am_destroy", "am_last_error", "am_version",
+)
+
+
+class AsyncMeshError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"asyncmesh error {status}: {message}")
+        self.status = status
+
+
+class Config(C.Structure):
+    """Mirror of am_config."""
+    _fields_ = [
+        ("n", C.c_uint64),
+        ("replicas", C.c_uint32), ("delay", C.c_uint32), ("avg_interval", C.c_uint32), ("optimizer", C.c_uint32),
+        ("fraction", C.c_double), ("seed", C.c_uint64),
+        ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float), ("weight_decay", C.c_float),
+        ("gamma", C.c_float),
+        ("lookahead", C.c_uint32), ("correction", C.c_uint32), ("fwd_dtype", C.c_uint32), ("grad_dtype", C.c_uint32),
+        ("momentum_decay", C.c_double),
+    ]
+
+
+class Buffers(C.Structure):
+    """Mirror of am_buffers."""
+    _fields_ = [
+        ("w", C.POINTER(C.c_void_p)), ("m", C.POINTER(C.c_void_p)), ("v", C.POINTER(C.c_void_p)),
+        ("d", C.POINTER(C.c_void_p)), ("fwd", C.POINTER(C.c_void_p)),
+        ("workspace", C.c_void_p), ("workspace_bytes", C.c_uint64),
+    ]
+
+
+def _load():
+    if not _LIB_PATH.exists():
+        raise ImportError(
+            f"{_LIB_PATH} is missing: build it first (python -m paper_2601_22442_amd.build, or "
+            "__graft_entry__.build()).  There is no fallback path.")
+    L = C.CDLL(str(_LIB_PATH))
+    L.am_workspace_bytes.argtypes = [C.POINTER(Config), C.POINTER(C.c_uint64)]
+    L.am_init_state.argtypes = [C.POINTER(Config), C.POINTER(Buffers), C.c_void_p, C.POINTER(C.c_void_p)]
+    L.am_step.argtypes = [C.c_void_p, C.c_uint64, C.POINTER(C.c_void_p), C.c_float, C.c_float, C.c_float]
+    L.am_sparse_average.argtypes = [C.c_void_p, C.c_uint64, C.c_float]
+    L.am_lookahead.argtypes = [C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p, C.c_uint64, C.c_float, C.c_void_p]
+    L.am_subset_indices.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint64, C.c_void_p]
+    L.am_read_flags.argtypes = [C.c_void_p, C.POINTER(C.c_uint32)]
+    L.am_set_profiling.argtypes = [C.c_void_p, C.c_int]
+    L.am_get_profile.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_uint64)]
+    L.am_ring_info.argtypes = [C.c_void_p, C.POINTER(C.c_uint64), C.POINTER(C.c_uint32)]
+    L.am_destroy.argtypes = [C.c_void_p]
+    for name in EXPORTS:
+        getattr(L, name).restype = C.c_int
+    L.am_last_error.restype = C.c_char_p
+    L.am_last_error.argtypes = []
+    L.am_version.restype = C.c_char_p
+    L.am_version.argtypes = []
+    return L
+
+
+lib = _load()
+
+
+def _check(status: int):
+    if status != 0:
+        raise AsyncMeshError(status, lib.am_last_error().decode())
+
+
+def version() -> str:
+    return lib.am_version().decode()
+
+
+def make_config(n, replicas, delay=0, avg_interval=1, fraction=0.05, seed=0, optimizer=OPT_ADAMW,
+                beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01, lookahead=False, gamma=0.0,
+                correction=CORR_EMA, fwd_dtype=F32, grad_dtype=F32, momentum_decay=0.004) -> Config:
+    return Config(n=n, replicas=replicas, delay=delay, avg_interval=avg_interval, optimizer=optimizer,
+                  fraction=fraction, seed=seed, beta1=beta1, beta2=beta2, eps=eps, weight_decay=weight_decay,
+                  gamma=gamma, lookahead=int(bool(lookahead)), correction=correction,
+                  fwd_dtype=fwd_dtype, grad_dtype=grad_dtype, momentum_decay=momentum_decay)
+
+
+def workspace_bytes(cfg: Config) -> int:
+    out = C.c_uint64(0)
+    _check(lib.am_workspace_bytes(C.byref(cfg), C.byref(out)))
+    return int(out.value)
+
+
+def _ptr_table(tensors):
+    return (C.c_void_p * len(tensors))(*[t.data_ptr() for t in tensors])
+
+
+def _stream_handle(device) -> int:
+    return int(torch.cuda.current_stream(device).cuda_stream)
+
+
+class Stage:
+    """State of one pipeline stage replicated R times on one GPU (am_state plus the device
+    tensors it is bound to).  Methods carry the names of the C entry points."""
+
+    def __init__(self, cfg: Config, w0: torch.Tensor | None = None, device="cuda:0", with_fwd: bool | None = None):
+        self.cfg = cfg
+        self.device = torch.device(device)
+        n, R = int(cfg.n), int(cfg.replicas)
+        self.n, self.R = n, R
+        f32 = dict(dtype=torch.float32, device=self.device)
+        need_m = not (cfg.optimizer == OPT_SGD and cfg.beta1 == 0.0)
+        need_v = cfg.optimizer != OPT_SGD
+        need_d = cfg.correction == CORR_EMA
+        need_fwd = bool(cfg.lookahead) or cfg.fwd_dtype == BF16
+        if with_fwd is None:
+            with_fwd = need_fwd
+        self.w = [torch.empty(n, **f32) for _ in range(R)]
+        self.m = [torch.empty(n, **f32) for _ in range(R)] if need_m else None
+        self.v = [torch.empty(n, **f32) for _ in range(R)] if need_v else None
+        self.d = [torch.empty(n, **f32) for _ in range(R)] if need_d else None
+        fdt = torch.bfloat16 if cfg.fwd_dtype == BF16 else torch.float32
+        self.fwd = [torch.empty(n, dtype=fdt, device=self.device) for _ in range(R)] if with_fwd else None
+        if w0 is not None:
+            self.set_w(w0)
+        self.workspace = torch.empty(workspace_bytes(cfg), dtype=torch.uint8, device=self.device)
+        self._handle = C.c_void_p(None)
+        self._init()
+
+    def _init(self):
+        bufs = Buffers()
+        self._tables = {}
+        for name in ("w", "m", "v", "d", "fwd"):
+            ts = getattr(self, name)
+            if ts is not None:
+                self._tables[name] = _ptr_table(ts)
+                setattr(bufs, name, C.cast(self._tables[name], C.POINTER(C.c_void_p)))
+        bufs.workspace = self.workspace.data_ptr()
+        bufs.workspace_bytes = self.workspace.numel()
+        with torch.cuda.device(self.device):
+            _check(lib.am_init_state(C.byref(self.cfg), C.byref(bufs), _stream_handle(self.device), C.byref(self._handle)))
+
+    def set_w(self, w0: torch.Tensor):
+        """Copy the starting weights in: one row for all replicas (1-D) or one row per replica (2-D)."""
+        w0 = torch.as_tensor(w0)
+        for i in range(self.R):
+            self.w[i].copy_(w0 if w0.dim() == 1 else w0[i])
+
+    # ---- entry points -------------------------------------------------------------------
+    def step(self, t: int, grads, lr: float, lambda_t: float = 0.5, grad_scale: float = 1.0):
+        assert len(grads) == self.R
+        table = _ptr_table(grads)
+        with torch.cuda.device(self.device):
+            _check(lib.am_step(self._handle, t, table, lr, lambda_t, grad_scale))
+
+    def sparse_average(self, t: int, lambda_t: float = 0.5):
+        with torch.cuda.device(self.device):
+            _check(lib.am_sparse_average(self._handle, t, lambda_t))
+
+    def subset_indices(self, t: int, capacity: int | None = None) -> torch.Tensor:
+        cap = self.n if capacity is None else capacity
+        out = torch.empty(max(cap, 1), dtype=torch.int64, device=self.device)
+        count = torch.zeros(1, dtype=torch.int64, device=self.device)
+        with torch.cuda.device(self.device):
+            _check(lib.am_subset_indices(self._handle, t, out.data_ptr(), cap, count.data_ptr()))
+        k = int(count.item())
+        return out[:min(k, cap)], k
+
+    def read_flags(self) -> int:
+        f = C.c_uint32(0)
+        _check(lib.am_read_flags(self._handle, C.byref(f)))
+        return int(f.value)
+
+    def set_profiling(self, on: bool):
+        _check(lib.am_set_profiling(self._handle, int(on)))
+
+    def get_profile(self):
+        ms, k = C.c_double(0), C.c_uint64(0)
+        _check(lib.am_get_profile(self._handle, C.byref(ms), C.byref(k)))
+        return float(ms.value), int(k.value)
+
+    def ring_info(self):
+        cap, slots = C.c_uint64(0), C.c_uint32(0)
+        _check(lib.am_ring_info(self._handle, C.byref(cap), C.byref(slots)))
+        return int(cap.value), int(slots.value)
+
+    def close(self):
+        if self._handle:
+            lib.am_destroy(self._handle)
+            self._handle = C.c_void_p(None)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def init_state(cfg: Config, w0=None, device="cuda:0", with_fwd=None) -> Stage:
+    return Stage(cfg, w0=w0, device=device, with_fwd=with_fwd)
+
+
+def lookahead(w: torch.Tensor, w_prev: torch.Tensor, gamma: float, out_dtype=F32) -> torch.Tensor:
+    """Stateless out = w + gamma (w - w_prev) (am_lookahead)."""
+    assert w.is_cuda and w_prev.is_cuda and w.dtype == torch.float32 and w_prev.dtype == torch.float32
+    assert w.is_contiguous() and w_prev.is_contiguous() and w.numel() == w_prev.numel()
+    out = torch.empty(w.numel(), dtype=torch.bfloat16 if out_dtype == BF16 else torch.float32, device=w.device)
+    with torch.cuda.device(w.device):
+        _check(lib.am_lookahead(out.data_ptr(), out_dtype, w.data_ptr(), w_prev.data_ptr(), w.numel(), gamma,
+                                _stream_handle(w.device)))
+    return out

@@ -1,0 +1,155 @@
+// Device-side building blocks of the AsyncMesh stage update for gfx950 (wave64).
+//
+// Geometry used by every kernel here:
+//   group      = 4 consecutive coordinates (one 128-bit access, one Philox4x32 block)
+//   tile       = 64 groups = 256 consecutive coordinates = what one wavefront handles at a time
+//   superblock = 512 tiles; subset counts are scanned inside a superblock by one workgroup and
+//                across superblocks by a second tiny kernel
+// A selected coordinate's position in a packed ring slot is
+//   sb_base[tile >> 9] + local_off[tile] + (selected coordinates of the tile before it).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace am {
+
+constexpr uint32_t kTileCoords = 256;
+constexpr uint32_t kTilesPerSuperblock = 512;
+constexpr uint32_t kMaxReplicas = 32;
+
+// ---------------------------------------------------------------------------------------------
+// Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11): ten rounds of two 32x32->64 multiplies.
+// ---------------------------------------------------------------------------------------------
+struct U4 { uint32_t x0, x1, x2, x3; };
+
+__device__ __forceinline__ U4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                            uint32_t k0, uint32_t k1)
+{
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+        const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        c1 = (uint32_t)p1;
+        c3 = (uint32_t)p0;
+        c0 = n0;
+        c2 = n2;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    return U4{c0, c1, c2, c3};
+}
+
+struct SubsetKey {
+    uint32_t seed_lo, seed_hi;   // Philox key
+    uint32_t step_lo, step_hi;   // counter words 2, 3
+    uint64_t threshold;          // floor(p 2^32); 2^32 selects everything
+};
+
+// 4-bit membership mask of the coordinates 4*group .. 4*group+3 (bit j = coordinate 4*group+j),
+// restricted to the first nvalid of them.
+__device__ __forceinline__ uint32_t member_mask(const SubsetKey &k, uint64_t group, int nvalid)
+{
+    const U4 x = philox4x32_10((uint32_t)group, (uint32_t)(group >> 32), k.step_lo, k.step_hi,
+                               k.seed_lo, k.seed_hi);
+    uint32_t m = 0;
+    m |= ((uint64_t)x.x0 < k.threshold) ? 1u : 0u;
+    m |= ((uint64_t)x.x1 < k.threshold) ? 2u : 0u;
+    m |= ((uint64_t)x.x2 < k.threshold) ? 4u : 0u;
+    m |= ((uint64_t)x.x3 < k.threshold) ? 8u : 0u;
+    return m & ((1u << nvalid) - 1u);
+}
+
+// ---------------------------------------------------------------------------------------------
+// wave64 helpers
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t lanes_below(uint64_t ballot)
+{
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(ballot >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)ballot, 0u));
+}
+
+// Exclusive prefix, over the lanes of the wave in lane order, of popcount(mask4); total = sum over
+// the whole wave.  Must be called by all 64 lanes together.
+__device__ __forceinline__ uint32_t wave_prefix_mask4(uint32_t mask4, uint32_t &total)
+{
+    uint32_t pre = 0, tot = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const uint64_t b = __ballot((mask4 >> j) & 1u);
+        pre += lanes_below(b);
+        tot += (uint32_t)__popcll(b);
+    }
+    total = tot;
+    return pre;
+}
+
+// ---------------------------------------------------------------------------------------------
+// 128-bit accesses with a scalar tail (only the last group of an array can be partial)
+// ---------------------------------------------------------------------------------------------
+struct F4 { float v[4]; };
+
+__device__ __forceinline__ F4 load_f32x4(const float *__restrict__ p, uint64_t mu, int nvalid)
+{
+    F4 r;
+    if (nvalid == 4) {
+        const float4 t = *reinterpret_cast<const float4 *>(p + mu);
+        r.v[0] = t.x; r.v[1] = t.y; r.v[2] = t.z; r.v[3] = t.w;
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) r.v[j] = (j < nvalid) ? p[mu + j] : 0.0f;
+    }
+    return r;
+}
+
+__device__ __forceinline__ void store_f32x4(float *__restrict__ p, uint64_t mu, int nvalid, const F4 &x)
+{
+    if (nvalid == 4) {
+        *reinterpret_cast<float4 *>(p + mu) = make_float4(x.v[0], x.v[1], x.v[2], x.v[3]);
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (j < nvalid) p[mu + j] = x.v[j];
+    }
+}
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
+
+// round-to-nearest-even fp32 -> bfloat16 (the compiler selects the gfx950 conversion instruction)
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f)
+{
+    const __bf16 b = (__bf16)f;
+    return __builtin_bit_cast(uint16_t, b);
+}
+
+__device__ __forceinline__ F4 load_bf16x4(const uint16_t *__restrict__ p, uint64_t mu, int nvalid)
+{
+    F4 r;
+    if (nvalid == 4) {
+        const uint2 t = *reinterpret_cast<const uint2 *>(p + mu);
+        r.v[0] = __uint_as_float(t.x << 16);
+        r.v[1] = __uint_as_float(t.x & 0xFFFF0000u);
+        r.v[2] = __uint_as_float(t.y << 16);
+        r.v[3] = __uint_as_float(t.y & 0xFFFF0000u);
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) r.v[j] = (j < nvalid) ? bf16_bits_to_f32(p[mu + j]) : 0.0f;
+    }
+    return r;
+}
+
+__device__ __forceinline__ void store_bf16x4(uint16_t *__restrict__ p, uint64_t mu, int nvalid, const F4 &x)
+{
+    if (nvalid == 4) {
+        uint2 t;
+        t.x = (uint32_t)f32_to_bf16_bits(x.v[0]) | ((uint32_t)f32_to_bf16_bits(x.v[1]) << 16);
+        t.y = (uint32_t)f32_to_bf16_bits(x.v[2]) | ((uint32_t)f32_to_bf16_bits(x.v[3]) << 16);
+        *reinterpret_cast<uint2 *>(p + mu) = t;
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (j < nvalid) p[mu + j] = f32_to_bf16_bits(x.v[j]);
+    }
+}
+
+}  // namespace am

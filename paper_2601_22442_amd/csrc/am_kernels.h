@@ -1,0 +1,457 @@
+// Kernels of the AsyncMesh stage update (gfx950).  All of them are bound by HBM bandwidth; none is a
+// contraction, so none uses the matrix cores.
+#pragma once
+#include "am_device.h"
+
+namespace am {
+
+// =============================================================================================
+// Subset offsets:   k_subset_count  ->  k_subset_scan
+// =============================================================================================
+// One workgroup (4 waves) per superblock of 512 tiles.  Pure integer hashing, no array reads.
+// Writes, per tile, the number of selected coordinates in the tiles of the same superblock before
+// it (local_off) and, per superblock, its total (sb_sum).
+__global__ void __launch_bounds__(256)
+k_subset_count(SubsetKey key, uint64_t n, uint32_t ntiles,
+               uint32_t *__restrict__ local_off, uint32_t *__restrict__ sb_sum)
+{
+    __shared__ uint32_t cnt[kTilesPerSuperblock];
+    __shared__ uint32_t wave_tot[4];
+    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    const uint32_t tile0 = blockIdx.x * kTilesPerSuperblock;
+
+    // wave w counts tiles tile0 + w, w+4, ... (adjacent waves hash adjacent tiles)
+    for (uint32_t k = wave; k < kTilesPerSuperblock; k += 4) {
+        const uint32_t tile = tile0 + k;
+        uint32_t total = 0;
+        if (tile < ntiles) {
+            const uint64_t group = (uint64_t)tile * 64u + lane;
+            const uint64_t mu = group * 4u;
+            const int nvalid = mu >= n ? 0 : (n - mu >= 4u ? 4 : (int)(n - mu));
+            (void)wave_prefix_mask4(member_mask(key, group, nvalid), total);
+        }
+        if (lane == 0) cnt[k] = total;
+    }
+    __syncthreads();
+
+    // exclusive scan of the 512 counts: thread j owns entries 2j, 2j+1
+    const uint32_t a = cnt[2 * threadIdx.x], b = cnt[2 * threadIdx.x + 1];
+    uint32_t incl = a + b;                       // inclusive scan across the wave, by shuffles
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t up = __shfl_up(incl, off);
+        if ((int)lane >= off) incl += up;
+    }
+    if (lane == 63) wave_tot[wave] = incl;
+    __syncthreads();
+    uint32_t base = 0;
+    for (uint32_t w = 0; w < wave; ++w) base += wave_tot[w];
+    const uint32_t excl = base + incl - (a + b);
+    const uint32_t t_a = tile0 + 2 * threadIdx.x;
+    if (t_a < ntiles) local_off[t_a] = excl;
+    if (t_a + 1 < ntiles) local_off[t_a + 1] = excl + a;
+    if (threadIdx.x == 255) sb_sum[blockIdx.x] = base + incl;
+}
+
+// Single workgroup: exclusive scan of the superblock totals, in place (sb[i] <- sum of sb[<i]),
+// grand total to sb[nsb]; raises flag bit 0 when the total exceeds the ring slot capacity.
+__global__ void __launch_bounds__(256)
+k_subset_scan(uint32_t *__restrict__ sb, uint32_t nsb, uint32_t capacity, uint32_t *__restrict__ flags,
+              uint64_t *__restrict__ count_out)
+{
+    __shared__ uint64_t part[256];
+    const uint32_t per = (nsb + 255u) / 256u;
+    const uint32_t lo = threadIdx.x * per;
+    const uint32_t hi = lo + per < nsb ? lo + per : nsb;
+    uint64_t s = 0;
+    for (uint32_t i = lo; i < hi; ++i) s += sb[i];
+    part[threadIdx.x] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint64_t run = 0;
+        for (int i = 0; i < 256; ++i) { const uint64_t x = part[i]; part[i] = run; run += x; }
+        sb[nsb] = run > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)run;
+        if (run > capacity && flags) atomicOr(flags, 1u);
+        if (count_out) *count_out = run;
+    }
+    __syncthreads();
+    uint64_t run = part[threadIdx.x];
+    for (uint32_t i = lo; i < hi; ++i) { const uint32_t x = sb[i]; sb[i] = (uint32_t)run; run += x; }
+}
+
+// Ascending index list of a subset (for am_subset_indices).
+__global__ void __launch_bounds__(256)
+k_subset_write(SubsetKey key, uint64_t n, uint32_t ntiles, const uint32_t *__restrict__ local_off,
+               const uint32_t *__restrict__ sb_base, uint64_t *__restrict__ out, uint64_t capacity)
+{
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t nwaves = gridDim.x * 4u;
+    for (uint32_t tile = blockIdx.x * 4u + (threadIdx.x >> 6); tile < ntiles; tile += nwaves) {
+        const uint64_t group = (uint64_t)tile * 64u + lane;
+        const uint64_t mu = group * 4u;
+        const int nvalid = mu >= n ? 0 : (n - mu >= 4u ? 4 : (int)(n - mu));
+        const uint32_t mask = member_mask(key, group, nvalid);
+        uint32_t total;
+        uint64_t pos = (uint64_t)sb_base[tile / kTilesPerSuperblock] + local_off[tile] + wave_prefix_mask4(mask, total);
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if ((mask >> j) & 1u) {
+                if (pos < capacity) out[pos] = mu + j;
+                ++pos;
+            }
+    }
+}
+
+// =============================================================================================
+// Fused step kernel
+// =============================================================================================
+enum : int { kOptSgdPlain = 0, kOptSgdMomentum = 1, kOptAdam = 2 };
+enum : int { kFwdNone = 0, kFwdF32 = 1, kFwdBf16 = 2 };
+
+struct StepArgs {
+    float *w[kMaxReplicas];
+    float *m[kMaxReplicas];
+    float *v[kMaxReplicas];
+    float *d[kMaxReplicas];
+    void *fwd[kMaxReplicas];
+    const void *g[kMaxReplicas];
+    uint64_t n;
+    uint32_t ntiles;
+    uint32_t replicas;
+    // averaging
+    uint32_t do_send, do_recv, ema, same_slot;     // same_slot: tau = 0, the average is of this step's w^
+    SubsetKey key_send, key_recv;
+    float *ring_send;                              // slot written now: [position][replica]
+    const float *ring_recv;                        // slot sent tau rounds ago
+    const uint32_t *send_local_off, *send_sb_base;
+    const uint32_t *recv_local_off, *recv_sb_base;
+    uint32_t capacity;
+    double lambda, one_minus_lambda;
+    // optimizer, every coefficient a per-step scalar evaluated once on the host in double:
+    //   g  = grad_scale * g_raw
+    //   m' = a_m m + b_m g ;  v' = a_v v + b_v g^2
+    //   w^ = w - (c_wd w + (c_g g + c_m m') / (c_v sqrt(v') + eps))           (Adam family)
+    //   w^ = w - (c_wd w + c_m m')     resp.     w - (c_wd w + c_g g)          (SGD with / without momentum)
+    double grad_scale, a_m, b_m, a_v, b_v, c_wd, c_g, c_m, c_v, eps;
+    uint32_t lookahead;
+    double gamma;
+};
+
+// Precision.  State is fp32 in memory (the method's precision).  The accumulating expressions
+// (moments, weight update, EMA, look-ahead) are evaluated in fp64 from the stored fp32 values
+// and rounded once on store, so that rounding noise does not random-walk over hundreds of steps;
+// on this chip an fp64 FMA issues at the rate of an unpacked fp32 FMA, and the kernel is bound by
+// memory.  The square root and the quotient start from the fp32 hardware approximations and take
+// one Newton step in fp64 each, which is far cheaper than fp64 sqrt / divide sequences.
+
+// sqrt(x) of an fp32 value x >= 0, to (nearly) double accuracy
+__device__ __forceinline__ double sqrt_refined(float x)
+{
+    if (x == 0.0f) return 0.0;
+    const float s0 = sqrtf(x);
+    const double s0d = (double)s0;
+    const double residual = fma(-s0d, s0d, (double)x);                     // x - s0^2, exact to fp64
+    return s0d + (double)((float)residual * (0.5f * __builtin_amdgcn_rcpf(s0)));
+}
+
+// num / den for den > 0, to (nearly) double accuracy
+__device__ __forceinline__ double quotient_refined(double num, double den)
+{
+    const float rden = __builtin_amdgcn_rcpf((float)den);
+    const float q0 = (float)num * rden;
+    const double residual = fma(-(double)q0, den, num);                    // num - q0 den
+    return (double)q0 + (double)((float)residual * rden);
+}
+
+// Local optimizer step of replica i on one group: loads w, g (and m, v), returns the new values.
+template <int OPT, bool GRAD_BF16>
+__device__ __forceinline__ void local_step(const StepArgs &a, uint32_t i, uint64_t mu, int nvalid,
+                                           F4 &w_old, F4 &w_hat, F4 &m_new, F4 &v_new)
+{
+    w_old = load_f32x4(a.w[i], mu, nvalid);
+    F4 g = GRAD_BF16 ? load_bf16x4(static_cast<const uint16_t *>(a.g[i]), mu, nvalid)
+                     : load_f32x4(static_cast<const float *>(a.g[i]), mu, nvalid);
+    F4 m_old, v_old;
+    if (OPT != kOptSgdPlain) m_old = load_f32x4(a.m[i], mu, nvalid);
+    if (OPT == kOptAdam) v_old = load_f32x4(a.v[i], mu, nvalid);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const double gj = a.grad_scale * (double)g.v[j];
+        const double wo = (double)w_old.v[j];
+        double step;                                           // what is subtracted besides the decay
+        if (OPT == kOptSgdPlain) {
+            step = a.c_g * gj;
+        } else if (OPT == kOptSgdMomentum) {
+            m_new.v[j] = (float)fma(a.a_m, (double)m_old.v[j], gj);
+            step = a.c_m * (double)m_new.v[j];
+        } else {
+            m_new.v[j] = (float)fma(a.a_m, (double)m_old.v[j], a.b_m * gj);
+            v_new.v[j] = (float)fma(a.a_v, (double)v_old.v[j], a.b_v * gj * gj);
+            const double den = fma(a.c_v, sqrt_refined(v_new.v[j]), a.eps);
+            const double num = fma(a.c_g, gj, a.c_m * (double)m_new.v[j]);
+            step = quotient_refined(num, den);
+        }
+        w_hat.v[j] = (float)(wo - fma(a.c_wd, wo, step));
+    }
+}
+
+// One wavefront per tile; one lane per group; the lane walks over all R replicas of its group, so
+// the subset hash is paid once per group (not once per replica) and the replica mean needs no
+// communication between lanes.
+template <int OPT, bool GRAD_BF16, int FWD>
+__global__ void __launch_bounds__(256)
+k_step(const StepArgs a)
+{
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t nwaves = gridDim.x * 4u;
+    const uint32_t R = a.replicas;
+    const double inv_r = 1.0 / (double)R;
+
+    for (uint32_t tile = blockIdx.x * 4u + (threadIdx.x >> 6); tile < a.ntiles; tile += nwaves) {
+        const uint64_t group = (uint64_t)tile * 64u + lane;
+        const uint64_t mu = group * 4u;
+        const int nvalid = mu >= a.n ? 0 : (a.n - mu >= 4u ? 4 : (int)(a.n - mu));
+
+        // ---- subsets: which of my 4 coordinates are sent now / received now, and where they sit
+        uint32_t mask_send = 0, mask_recv = 0;
+        uint64_t pos_send = 0, pos_recv = 0;
+        if (a.do_send) {
+            uint32_t total;
+            mask_send = member_mask(a.key_send, group, nvalid);
+            pos_send = (uint64_t)a.send_sb_base[tile / kTilesPerSuperblock] + a.send_local_off[tile]
+                     + wave_prefix_mask4(mask_send, total);
+        }
+        if (a.do_recv) {
+            if (a.same_slot) {
+                mask_recv = mask_send;
+                pos_recv = pos_send;
+            } else {
+                uint32_t total;
+                mask_recv = member_mask(a.key_recv, group, nvalid);
+                pos_recv = (uint64_t)a.recv_sb_base[tile / kTilesPerSuperblock] + a.recv_local_off[tile]
+                         + wave_prefix_mask4(mask_recv, total);
+            }
+        }
+        // coordinates beyond the slot capacity are left out, at send and at receive alike
+        {
+            uint64_t p = pos_send;
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if ((mask_send >> j) & 1u) { if (p >= a.capacity) mask_send &= ~(1u << j); ++p; }
+            p = pos_recv;
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if ((mask_recv >> j) & 1u) { if (p >= a.capacity) mask_recv &= ~(1u << j); ++p; }
+        }
+
+        // ---- old average of the coordinates received now
+        float abar[4] = {0.f, 0.f, 0.f, 0.f};
+        if (mask_recv) {
+            if (a.same_slot) {
+                // tau = 0: the average is over this step's local results of all replicas
+                double sum[4] = {0., 0., 0., 0.};
+                for (uint32_t i = 0; i < R; ++i) {
+                    F4 w_old, w_hat, m_new, v_new;
+                    local_step<OPT, GRAD_BF16>(a, i, mu, nvalid, w_old, w_hat, m_new, v_new);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) sum[j] += (double)w_hat.v[j];
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) abar[j] = (float)(sum[j] * inv_r);
+            } else {
+                uint64_t p = pos_recv;
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if ((mask_recv >> j) & 1u) {
+                        const float *__restrict__ src = a.ring_recv + p * R;
+                        double sum = 0.;
+                        for (uint32_t i = 0; i < R; ++i) sum += (double)src[i];
+                        abar[j] = (float)(sum * inv_r);
+                        ++p;
+                    }
+            }
+        }
+
+        // ---- all replicas of this group
+        for (uint32_t i = 0; i < R; ++i) {
+            F4 w_old, w_hat, m_new, v_new;
+            local_step<OPT, GRAD_BF16>(a, i, mu, nvalid, w_old, w_hat, m_new, v_new);
+
+            if (mask_send) {                                   // send: w^ goes into the slot of this round
+                uint64_t p = pos_send;
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if ((mask_send >> j) & 1u) { a.ring_send[p * R + i] = w_hat.v[j]; ++p; }
+            }
+
+            F4 w_new = w_hat;
+            if (mask_recv) {                                   // receive: old average (+ EMA of staleness)
+                uint64_t p = pos_recv;
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if ((mask_recv >> j) & 1u) {
+                        if (a.ema) {
+                            const float sent = a.same_slot ? w_hat.v[j] : a.ring_recv[p * R + i];
+                            float *__restrict__ dp = a.d[i] + mu + j;
+                            const float dn = (float)fma(a.one_minus_lambda, (double)*dp,
+                                                        a.lambda * ((double)w_hat.v[j] - (double)sent));
+                            *dp = dn;
+                            w_new.v[j] = (float)((double)abar[j] + (double)dn);
+                        } else {
+                            w_new.v[j] = abar[j];
+                        }
+                        ++p;
+                    }
+            }
+
+            store_f32x4(a.w[i], mu, nvalid, w_new);
+            if (OPT != kOptSgdPlain) store_f32x4(a.m[i], mu, nvalid, m_new);
+            if (OPT == kOptAdam) store_f32x4(a.v[i], mu, nvalid, v_new);
+            if (FWD != kFwdNone) {
+                F4 f = w_new;
+                if (a.lookahead) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        f.v[j] = (float)fma(a.gamma, (double)w_hat.v[j] - (double)w_old.v[j], (double)w_new.v[j]);
+                }
+                if (FWD == kFwdF32) store_f32x4(static_cast<float *>(a.fwd[i]), mu, nvalid, f);
+                else store_bf16x4(static_cast<uint16_t *>(a.fwd[i]), mu, nvalid, f);
+            }
+        }
+    }
+}
+
+// =============================================================================================
+// Stand-alone sparse averaging (am_sparse_average): gather / average / scatter on the current w
+// =============================================================================================
+// One workgroup handles 4 tiles at a time, one per wave.  Each wave hashes its tile, compacts the
+// selected coordinates into an ascending index list in LDS, then walks that list with its lanes
+// laid out as (coordinate, replica): lane = c * L + i with L = the power of two >= R, so that ring
+// accesses are contiguous and the replica mean is a butterfly over L neighbouring lanes.
+struct SparseArgs {
+    float *w[kMaxReplicas];
+    float *d[kMaxReplicas];
+    uint64_t n;
+    uint32_t ntiles;
+    uint32_t replicas;
+    uint32_t lanes_per_coord;                      // L
+    uint32_t do_send, do_recv, ema;
+    SubsetKey key_send, key_recv;
+    float *ring_send;
+    const float *ring_recv;
+    const uint32_t *send_local_off, *send_sb_base;
+    const uint32_t *recv_local_off, *recv_sb_base;
+    uint32_t capacity;
+    double lambda, one_minus_lambda;
+};
+
+// Hash the wave's tile and leave the ascending list of selected local coordinates (0..255) in idx.
+__device__ __forceinline__ uint32_t stage_tile_indices(const SubsetKey &key, uint64_t n, uint32_t tile,
+                                                       uint32_t lane, uint16_t *idx)
+{
+    const uint64_t group = (uint64_t)tile * 64u + lane;
+    const uint64_t mu = group * 4u;
+    const int nvalid = mu >= n ? 0 : (n - mu >= 4u ? 4 : (int)(n - mu));
+    const uint32_t mask = member_mask(key, group, nvalid);
+    uint32_t total;
+    uint32_t p = wave_prefix_mask4(mask, total);
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        if ((mask >> j) & 1u) idx[p++] = (uint16_t)(lane * 4u + j);
+    return total;
+}
+
+__global__ void __launch_bounds__(256)
+k_sparse(const SparseArgs a)
+{
+    __shared__ uint16_t idx_lds[4][kTileCoords];
+    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    uint16_t *idx = idx_lds[wave];
+    const uint32_t R = a.replicas, L = a.lanes_per_coord;
+    const uint32_t coords_per_pass = 64u / L;
+    const uint32_t c_in_pass = lane / L, i = lane % L;
+    const bool lane_has_replica = i < R;
+    const double inv_r = 1.0 / (double)R;
+    const uint32_t ngroups_of_tiles = (a.ntiles + 3u) / 4u;
+
+    for (uint32_t tg = blockIdx.x; tg < ngroups_of_tiles; tg += gridDim.x) {   // uniform per workgroup
+        const uint32_t tile = tg * 4u + wave;
+        const bool live = tile < a.ntiles;
+
+        // ---------------- send: ring[slot(t)][pos][i] <- w_i[mu] for mu in S^t
+        if (a.do_send) {
+            uint32_t count = 0;
+            if (live) count = stage_tile_indices(a.key_send, a.n, tile, lane, idx);
+            __syncthreads();
+            if (live) {
+                const uint64_t base = (uint64_t)a.send_sb_base[tile / kTilesPerSuperblock] + a.send_local_off[tile];
+                for (uint32_t c0 = 0; c0 < count; c0 += coords_per_pass) {
+                    const uint32_t c = c0 + c_in_pass;
+                    if (c < count && lane_has_replica && base + c < a.capacity) {
+                        const uint64_t mu = (uint64_t)tile * kTileCoords + idx[c];
+                        a.ring_send[(base + c) * R + i] = a.w[i][mu];
+                    }
+                }
+            }
+            __threadfence_block();          // tau = 0: the receive below reads what was just written
+            __syncthreads();
+        }
+
+        // ---------------- receive: mean of ring[slot(t - tau K)], EMA, scatter
+        if (a.do_recv) {
+            uint32_t count = 0;
+            if (live) count = stage_tile_indices(a.key_recv, a.n, tile, lane, idx);
+            __syncthreads();
+            if (live) {
+                const uint64_t base = (uint64_t)a.recv_sb_base[tile / kTilesPerSuperblock] + a.recv_local_off[tile];
+                for (uint32_t c0 = 0; c0 < count; c0 += coords_per_pass) {      // uniform per wave
+                    const uint32_t c = c0 + c_in_pass;
+                    const bool on = c < count && lane_has_replica && base + c < a.capacity;
+                    float sent = 0.f;
+                    if (on) sent = a.ring_recv[(base + c) * R + i];
+                    double sum = (double)sent;
+                    for (uint32_t off = 1; off < L; off <<= 1) sum += __shfl_xor(sum, (int)off);
+                    if (on) {
+                        const float abar = (float)(sum * inv_r);
+                        const uint64_t mu = (uint64_t)tile * kTileCoords + idx[c];
+                        float w_new = abar;
+                        if (a.ema) {
+                            const float w_hat = a.w[i][mu];
+                            float *__restrict__ dp = a.d[i] + mu;
+                            const float dn = (float)fma(a.one_minus_lambda, (double)*dp,
+                                                        a.lambda * ((double)w_hat - (double)sent));
+                            *dp = dn;
+                            w_new = (float)((double)abar + (double)dn);
+                        }
+                        a.w[i][mu] = w_new;
+                    }
+                }
+            }
+            __syncthreads();
+        }
+    }
+}
+
+// =============================================================================================
+// Stateless look-ahead: out = w + gamma (w - w_prev)
+// =============================================================================================
+template <bool OUT_BF16>
+__global__ void __launch_bounds__(256)
+k_lookahead(void *__restrict__ out, const float *__restrict__ w, const float *__restrict__ w_prev,
+            uint64_t n, double gamma)
+{
+    const uint64_t ngroups = (n + 3u) / 4u;
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    for (uint64_t group = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; group < ngroups; group += stride) {
+        const uint64_t mu = group * 4u;
+        const int nvalid = n - mu >= 4u ? 4 : (int)(n - mu);
+        const F4 a = load_f32x4(w, mu, nvalid), b = load_f32x4(w_prev, mu, nvalid);
+        F4 f;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) f.v[j] = (float)fma(gamma, (double)a.v[j] - (double)b.v[j], (double)a.v[j]);
+        if (OUT_BF16) store_bf16x4(static_cast<uint16_t *>(out), mu, nvalid, f);
+        else store_f32x4(static_cast<float *>(out), mu, nvalid, f);
+    }
+}
+
+}  // namespace am

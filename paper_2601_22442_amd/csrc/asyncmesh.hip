@@ -1,0 +1,497 @@
+// Host side of the C ABI declared in include/asyncmesh.h: argument checking, per-step scalars,
+// workspace layout, ring bookkeeping and kernel launches.  No device work happens outside the
+// kernels of am_kernels.h; nothing here allocates device memory.
+#include "../../include/asyncmesh.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "am_kernels.h"
+
+namespace {
+
+thread_local std::string g_last_error;
+
+am_status fail(am_status code, const char *fmt, ...)
+{
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_last_error = buf;
+    return code;
+}
+
+#define AM_HIP(call)                                                                          \
+    do {                                                                                      \
+        hipError_t e_ = (call);                                                               \
+        if (e_ != hipSuccess) return fail(AM_EHIP, "%s: %s", #call, hipGetErrorString(e_));   \
+    } while (0)
+
+inline uint64_t round_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
+inline bool aligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+uint64_t subset_threshold(double p)
+{
+    if (!(p > 0.0)) return 0;
+    if (p >= 1.0) return 1ull << 32;
+    return (uint64_t)std::floor(p * 4294967296.0);
+}
+
+// coordinates one ring slot can hold: the expected subset size plus twelve standard deviations
+uint64_t slot_capacity(uint64_t n, double p)
+{
+    if (p >= 1.0) return n;
+    const double mean = p * (double)n;
+    const double cap = std::ceil(mean + 12.0 * std::sqrt((double)n * p * (1.0 - p))) + 1024.0;
+    return cap >= (double)n ? n : (uint64_t)cap;
+}
+
+struct Layout {
+    uint32_t ntiles, nsb, slots;
+    uint64_t capacity;
+    uint64_t off_flags, off_meta, meta_stride, meta_sb_off, off_ring, ring_stride, total;
+};
+
+// workspace = [flags 256 B][meta x (slots + 1)][ring values x slots]
+//   meta    = local_off u32[ntiles] | sb_base u32[nsb + 1]         (the extra one serves am_subset_indices)
+//   ring    = capacity * R fp32, position-major: [position][replica]
+Layout make_layout(const am_config &c)
+{
+    Layout L{};
+    L.ntiles = (uint32_t)((c.n + am::kTileCoords - 1) / am::kTileCoords);
+    L.nsb = (L.ntiles + am::kTilesPerSuperblock - 1) / am::kTilesPerSuperblock;
+    L.slots = c.delay + 1;
+    L.capacity = slot_capacity(c.n, c.fraction);
+    L.off_flags = 0;
+    L.off_meta = 256;
+    L.meta_sb_off = round_up((uint64_t)L.ntiles * 4, 256);
+    L.meta_stride = L.meta_sb_off + round_up(((uint64_t)L.nsb + 1) * 4, 256);
+    L.off_ring = L.off_meta + L.meta_stride * (L.slots + 1);
+    L.ring_stride = round_up(L.capacity * c.replicas * 4, 256);
+    L.total = L.off_ring + L.ring_stride * L.slots;
+    return L;
+}
+
+am_status check_config(const am_config *c)
+{
+    if (!c) return fail(AM_EINVAL, "config is NULL");
+    if (c->n == 0 || c->n >= (1ull << 32) - (1ull << 20)) return fail(AM_EINVAL, "n=%llu out of range [1, 2^32-2^20)", (unsigned long long)c->n);
+    if (c->replicas == 0 || c->replicas > AM_MAX_REPLICAS) return fail(AM_EINVAL, "replicas=%u out of range [1, %u]", c->replicas, AM_MAX_REPLICAS);
+    if (c->avg_interval == 0) return fail(AM_EINVAL, "avg_interval must be >= 1");
+    if (c->delay > 4096) return fail(AM_EINVAL, "delay=%u is larger than 4096 rounds", c->delay);
+    if (!(c->fraction > 0.0) || !(c->fraction <= 1.0)) return fail(AM_EINVAL, "fraction=%g not in (0, 1]", c->fraction);
+    if (c->optimizer > AM_OPT_NADAMW) return fail(AM_EINVAL, "unknown optimizer %u", c->optimizer);
+    if (c->correction > AM_CORR_EMA) return fail(AM_EINVAL, "unknown correction %u", c->correction);
+    if (c->fwd_dtype > AM_BF16 || c->grad_dtype > AM_BF16) return fail(AM_EINVAL, "unknown dtype");
+    if (!(c->beta1 >= 0.f && c->beta1 < 1.f)) return fail(AM_EINVAL, "beta1=%g not in [0, 1)", c->beta1);
+    if (c->optimizer != AM_OPT_SGD && !(c->beta2 >= 0.f && c->beta2 < 1.f)) return fail(AM_EINVAL, "beta2=%g not in [0, 1)", c->beta2);
+    if (c->optimizer != AM_OPT_SGD && !(c->eps >= 0.f)) return fail(AM_EINVAL, "eps=%g negative", c->eps);
+    if (!std::isfinite(c->weight_decay) || !std::isfinite(c->gamma)) return fail(AM_EINVAL, "weight_decay / gamma not finite");
+    return AM_OK;
+}
+
+}  // namespace
+
+struct am_state {
+    am_config cfg;
+    Layout lay;
+    hipStream_t stream;
+    int device;
+    uint32_t grid_step, grid_sparse;
+    float *w[AM_MAX_REPLICAS], *m[AM_MAX_REPLICAS], *v[AM_MAX_REPLICAS], *d[AM_MAX_REPLICAS];
+    void *fwd[AM_MAX_REPLICAS];
+    bool has_fwd;
+    char *ws;
+    uint64_t last_t;
+    double mu_product;           // NAdam: running product of the momentum schedule
+    uint64_t threshold;
+    // profiling of the fused kernel
+    bool profiling;
+    std::vector<hipEvent_t> ev_pool;
+    size_t ev_used;
+
+    uint32_t *flags() const { return reinterpret_cast<uint32_t *>(ws + lay.off_flags); }
+    uint32_t *meta_local(uint32_t slot) const { return reinterpret_cast<uint32_t *>(ws + lay.off_meta + lay.meta_stride * slot); }
+    uint32_t *meta_sb(uint32_t slot) const { return reinterpret_cast<uint32_t *>(ws + lay.off_meta + lay.meta_stride * slot + lay.meta_sb_off); }
+    float *ring(uint32_t slot) const { return reinterpret_cast<float *>(ws + lay.off_ring + lay.ring_stride * slot); }
+};
+
+namespace {
+
+am::SubsetKey make_key(const am_state *st, uint64_t step)
+{
+    am::SubsetKey k;
+    k.seed_lo = (uint32_t)st->cfg.seed;
+    k.seed_hi = (uint32_t)(st->cfg.seed >> 32);
+    k.step_lo = (uint32_t)step;
+    k.step_hi = (uint32_t)(step >> 32);
+    k.threshold = st->threshold;
+    return k;
+}
+
+// count + scan of S^step into the metadata block `slot`
+am_status launch_subset_offsets(am_state *st, uint64_t step, uint32_t slot, uint64_t *dev_count, bool check_capacity)
+{
+    const Layout &L = st->lay;
+    am::k_subset_count<<<L.nsb, 256, 0, st->stream>>>(make_key(st, step), st->cfg.n, L.ntiles,
+                                                      st->meta_local(slot), st->meta_sb(slot));
+    AM_HIP(hipGetLastError());
+    am::k_subset_scan<<<1, 256, 0, st->stream>>>(st->meta_sb(slot), L.nsb, (uint32_t)L.capacity,
+                                                 check_capacity ? st->flags() : nullptr, dev_count);
+    AM_HIP(hipGetLastError());
+    return AM_OK;
+}
+
+struct Round {
+    bool send, recv, same_slot;
+    uint32_t slot_send, slot_recv;
+    uint64_t step_recv;
+};
+
+Round plan_round(const am_state *st, uint64_t t)
+{
+    Round r{};
+    const uint64_t K = st->cfg.avg_interval, tau = st->cfg.delay;
+    if (t % K != 0) return r;
+    const uint64_t round = t / K;
+    r.send = true;
+    r.slot_send = (uint32_t)(round % (tau + 1));
+    if (t >= tau * K + 1) {                       // s = t - tau K >= 1: something was sent that long ago
+        r.recv = true;
+        r.step_recv = t - tau * K;
+        r.slot_recv = (uint32_t)((round - tau) % (tau + 1));
+        r.same_slot = tau == 0;
+    }
+    return r;
+}
+
+template <int OPT, bool GBF>
+am_status launch_step_fwd(am_state *st, const am::StepArgs &a)
+{
+    const dim3 grid(st->grid_step), block(256);
+    if (!st->has_fwd) am::k_step<OPT, GBF, am::kFwdNone><<<grid, block, 0, st->stream>>>(a);
+    else if (st->cfg.fwd_dtype == AM_F32) am::k_step<OPT, GBF, am::kFwdF32><<<grid, block, 0, st->stream>>>(a);
+    else am::k_step<OPT, GBF, am::kFwdBf16><<<grid, block, 0, st->stream>>>(a);
+    AM_HIP(hipGetLastError());
+    return AM_OK;
+}
+
+template <int OPT>
+am_status launch_step_grad(am_state *st, const am::StepArgs &a)
+{
+    return st->cfg.grad_dtype == AM_BF16 ? launch_step_fwd<OPT, true>(st, a) : launch_step_fwd<OPT, false>(st, a);
+}
+
+uint32_t env_u32(const char *name, uint32_t dflt)
+{
+    const char *s = std::getenv(name);
+    if (!s || !*s) return dflt;
+    const long v = std::strtol(s, nullptr, 10);
+    return v > 0 ? (uint32_t)v : dflt;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *am_last_error(void) { return g_last_error.c_str(); }
+const char *am_version(void) { return "asyncmesh-gfx950 0.1"; }
+
+am_status am_workspace_bytes(const am_config *cfg, uint64_t *out_bytes)
+{
+    if (am_status s = check_config(cfg)) return s;
+    if (!out_bytes) return fail(AM_EINVAL, "out_bytes is NULL");
+    *out_bytes = make_layout(*cfg).total;
+    return AM_OK;
+}
+
+am_status am_init_state(const am_config *cfg, const am_buffers *buf, void *hip_stream, am_state **out)
+{
+    if (am_status s = check_config(cfg)) return s;
+    if (!buf || !out) return fail(AM_EINVAL, "buffers / out is NULL");
+    const uint32_t R = cfg->replicas;
+    const bool need_m = !(cfg->optimizer == AM_OPT_SGD && cfg->beta1 == 0.f);
+    const bool need_v = cfg->optimizer != AM_OPT_SGD;
+    const bool need_d = cfg->correction == AM_CORR_EMA;
+    const bool need_fwd = cfg->lookahead != 0 || cfg->fwd_dtype == AM_BF16;
+    if (!buf->w) return fail(AM_EINVAL, "buffers.w is NULL");
+    if (need_m && !buf->m) return fail(AM_EINVAL, "buffers.m is NULL but the optimizer keeps a first moment");
+    if (need_v && !buf->v) return fail(AM_EINVAL, "buffers.v is NULL but the optimizer keeps a second moment");
+    if (need_d && !buf->d) return fail(AM_EINVAL, "buffers.d is NULL but correction = EMA");
+    if (need_fwd && !buf->fwd) return fail(AM_EINVAL, "buffers.fwd is NULL but look-ahead / bf16 forward weights are on");
+    const uintptr_t fwd_align = cfg->fwd_dtype == AM_BF16 ? 8 : 16;
+    for (uint32_t i = 0; i < R; ++i) {
+        if (!buf->w[i]) return fail(AM_EINVAL, "w[%u] is NULL", i);
+        if (!aligned(buf->w[i], 16)) return fail(AM_EALIGN, "w[%u] is not 16-byte aligned", i);
+        if (need_m) { if (!buf->m[i]) return fail(AM_EINVAL, "m[%u] is NULL", i); if (!aligned(buf->m[i], 16)) return fail(AM_EALIGN, "m[%u] is not 16-byte aligned", i); }
+        if (need_v) { if (!buf->v[i]) return fail(AM_EINVAL, "v[%u] is NULL", i); if (!aligned(buf->v[i], 16)) return fail(AM_EALIGN, "v[%u] is not 16-byte aligned", i); }
+        if (need_d) { if (!buf->d[i]) return fail(AM_EINVAL, "d[%u] is NULL", i); if (!aligned(buf->d[i], 16)) return fail(AM_EALIGN, "d[%u] is not 16-byte aligned", i); }
+        if (buf->fwd) { if (!buf->fwd[i]) return fail(AM_EINVAL, "fwd[%u] is NULL", i); if (!aligned(buf->fwd[i], fwd_align)) return fail(AM_EALIGN, "fwd[%u] is not %u-byte aligned", i, (unsigned)fwd_align); }
+    }
+    const Layout lay = make_layout(*cfg);
+    if (!buf->workspace) return fail(AM_EINVAL, "workspace is NULL");
+    if (!aligned(buf->workspace, 256)) return fail(AM_EALIGN, "workspace is not 256-byte aligned");
+    if (buf->workspace_bytes < lay.total)
+        return fail(AM_ENOMEM, "workspace has %llu bytes, %llu needed", (unsigned long long)buf->workspace_bytes, (unsigned long long)lay.total);
+
+    am_state *st = new (std::nothrow) am_state();
+    if (!st) return fail(AM_ENOMEM, "host allocation failed");
+    st->cfg = *cfg;
+    st->lay = lay;
+    st->stream = static_cast<hipStream_t>(hip_stream);
+    st->has_fwd = buf->fwd != nullptr;
+    st->ws = static_cast<char *>(buf->workspace);
+    st->last_t = 0;
+    st->mu_product = 1.0;
+    st->threshold = subset_threshold(cfg->fraction);
+    st->profiling = false;
+    st->ev_used = 0;
+    for (uint32_t i = 0; i < AM_MAX_REPLICAS; ++i) {
+        st->w[i] = i < R ? buf->w[i] : nullptr;
+        st->m[i] = (i < R && need_m) ? buf->m[i] : nullptr;
+        st->v[i] = (i < R && need_v) ? buf->v[i] : nullptr;
+        st->d[i] = (i < R && need_d) ? buf->d[i] : nullptr;
+        st->fwd[i] = (i < R && buf->fwd) ? buf->fwd[i] : nullptr;
+    }
+
+    hipError_t e = hipGetDevice(&st->device);
+    int cus = 256;
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, st->device);
+    if (e != hipSuccess) { delete st; return fail(AM_EHIP, "device query: %s", hipGetErrorString(e)); }
+    // persistent grids: a fixed number of workgroups per compute unit, each striding over the tiles
+    const uint32_t tile_groups = (lay.ntiles + 3) / 4;
+    const uint32_t want = (uint32_t)cus * env_u32("AM_BLOCKS_PER_CU", 8);
+    st->grid_step = tile_groups < want ? tile_groups : want;
+    st->grid_sparse = st->grid_step;
+
+    // d^0 = 0 and zero moments; clear flags, offsets and ring
+    const size_t bytes = (size_t)cfg->n * sizeof(float);
+    for (uint32_t i = 0; i < R && e == hipSuccess; ++i) {
+        if (need_m) e = hipMemsetAsync(st->m[i], 0, bytes, st->stream);
+        if (need_v && e == hipSuccess) e = hipMemsetAsync(st->v[i], 0, bytes, st->stream);
+        if (need_d && e == hipSuccess) e = hipMemsetAsync(st->d[i], 0, bytes, st->stream);
+    }
+    if (e == hipSuccess) e = hipMemsetAsync(st->ws, 0, lay.total, st->stream);
+    if (e != hipSuccess) { delete st; return fail(AM_EHIP, "hipMemsetAsync: %s", hipGetErrorString(e)); }
+    *out = st;
+    return AM_OK;
+}
+
+am_status am_step(am_state *st, uint64_t t, const void *const *grads, float lr, float lambda_t, float grad_scale)
+{
+    if (!st) return fail(AM_EINVAL, "state is NULL");
+    if (!grads) return fail(AM_EINVAL, "grads is NULL");
+    if (t != st->last_t + 1) return fail(AM_EORDER, "step %llu after step %llu", (unsigned long long)t, (unsigned long long)st->last_t);
+    if (!(lambda_t >= 0.f && lambda_t <= 1.f)) return fail(AM_EINVAL, "lambda_t=%g not in [0, 1]", lambda_t);
+    if (!std::isfinite(lr) || !std::isfinite(grad_scale)) return fail(AM_EINVAL, "lr / grad_scale not finite");
+    const am_config &c = st->cfg;
+    const uintptr_t galign = c.grad_dtype == AM_BF16 ? 8 : 16;
+    for (uint32_t i = 0; i < c.replicas; ++i) {
+        if (!grads[i]) return fail(AM_EINVAL, "grads[%u] is NULL", i);
+        if (!aligned(grads[i], galign)) return fail(AM_EALIGN, "grads[%u] is not %u-byte aligned", i, (unsigned)galign);
+    }
+
+    am::StepArgs a;
+    std::memset(&a, 0, sizeof a);
+    for (uint32_t i = 0; i < c.replicas; ++i) {
+        a.w[i] = st->w[i]; a.m[i] = st->m[i]; a.v[i] = st->v[i]; a.d[i] = st->d[i];
+        a.fwd[i] = st->fwd[i]; a.g[i] = grads[i];
+    }
+    a.n = c.n; a.ntiles = st->lay.ntiles; a.replicas = c.replicas;
+    a.capacity = (uint32_t)st->lay.capacity;
+    a.lambda = (double)lambda_t; a.one_minus_lambda = 1.0 - (double)lambda_t;
+    a.ema = c.correction == AM_CORR_EMA;
+    a.lookahead = c.lookahead != 0; a.gamma = (double)c.gamma;
+    a.grad_scale = (double)grad_scale;
+
+    // per-step scalars, evaluated once in double
+    const double b1 = c.beta1, b2 = c.beta2, lrd = lr, wd = c.weight_decay;
+    double mu_prod_next = st->mu_product;
+    a.c_wd = lrd * wd;
+    a.eps = (double)c.eps;
+    if (c.optimizer == AM_OPT_SGD) {
+        a.a_m = b1; a.c_m = lrd; a.c_g = lrd;
+    } else {
+        const double bc1 = 1.0 - std::pow(b1, (double)t), bc2 = 1.0 - std::pow(b2, (double)t);
+        a.a_m = b1; a.b_m = 1.0 - b1;
+        a.a_v = b2; a.b_v = 1.0 - b2;
+        a.c_v = 1.0 / std::sqrt(bc2);
+        if (c.optimizer == AM_OPT_ADAMW) {
+            a.c_g = 0.0; a.c_m = lrd / bc1;
+        } else {
+            const double mu_t = b1 * (1.0 - 0.5 * std::pow(0.96, (double)t * c.momentum_decay));
+            const double mu_t1 = b1 * (1.0 - 0.5 * std::pow(0.96, (double)(t + 1) * c.momentum_decay));
+            mu_prod_next = st->mu_product * mu_t;
+            a.c_g = lrd * (1.0 - mu_t) / (1.0 - mu_prod_next);
+            a.c_m = lrd * mu_t1 / (1.0 - mu_prod_next * mu_t1);
+        }
+    }
+
+    const Round r = plan_round(st, t);
+    a.do_send = r.send; a.do_recv = r.recv; a.same_slot = r.same_slot;
+    if (r.send) {
+        if (am_status s = launch_subset_offsets(st, t, r.slot_send, nullptr, true)) return s;
+        a.key_send = make_key(st, t);
+        a.ring_send = st->ring(r.slot_send);
+        a.send_local_off = st->meta_local(r.slot_send);
+        a.send_sb_base = st->meta_sb(r.slot_send);
+    }
+    if (r.recv) {
+        a.key_recv = make_key(st, r.step_recv);
+        a.ring_recv = st->ring(r.slot_recv);
+        a.recv_local_off = st->meta_local(r.slot_recv);
+        a.recv_sb_base = st->meta_sb(r.slot_recv);
+    }
+
+    hipEvent_t ev0 = nullptr, ev1 = nullptr;
+    if (st->profiling) {
+        while (st->ev_pool.size() < st->ev_used + 2) {
+            hipEvent_t e;
+            AM_HIP(hipEventCreate(&e));
+            st->ev_pool.push_back(e);
+        }
+        ev0 = st->ev_pool[st->ev_used];
+        ev1 = st->ev_pool[st->ev_used + 1];
+        AM_HIP(hipEventRecord(ev0, st->stream));
+    }
+    am_status s;
+    if (c.optimizer == AM_OPT_SGD) s = c.beta1 == 0.f ? launch_step_grad<am::kOptSgdPlain>(st, a) : launch_step_grad<am::kOptSgdMomentum>(st, a);
+    else s = launch_step_grad<am::kOptAdam>(st, a);
+    if (s) return s;
+    if (st->profiling) {
+        AM_HIP(hipEventRecord(ev1, st->stream));
+        st->ev_used += 2;
+    }
+    st->last_t = t;
+    st->mu_product = mu_prod_next;
+    return AM_OK;
+}
+
+am_status am_sparse_average(am_state *st, uint64_t t, float lambda_t)
+{
+    if (!st) return fail(AM_EINVAL, "state is NULL");
+    if (t != st->last_t + 1) return fail(AM_EORDER, "step %llu after step %llu", (unsigned long long)t, (unsigned long long)st->last_t);
+    if (!(lambda_t >= 0.f && lambda_t <= 1.f)) return fail(AM_EINVAL, "lambda_t=%g not in [0, 1]", lambda_t);
+    const am_config &c = st->cfg;
+    const Round r = plan_round(st, t);
+    if (r.send) {
+        am::SparseArgs a;
+        std::memset(&a, 0, sizeof a);
+        for (uint32_t i = 0; i < c.replicas; ++i) { a.w[i] = st->w[i]; a.d[i] = st->d[i]; }
+        a.n = c.n; a.ntiles = st->lay.ntiles; a.replicas = c.replicas;
+        uint32_t L = 1;
+        while (L < c.replicas) L <<= 1;
+        a.lanes_per_coord = L;
+        a.do_send = 1; a.do_recv = r.recv; a.ema = c.correction == AM_CORR_EMA;
+        a.capacity = (uint32_t)st->lay.capacity;
+        a.lambda = (double)lambda_t; a.one_minus_lambda = 1.0 - (double)lambda_t;
+        if (am_status s = launch_subset_offsets(st, t, r.slot_send, nullptr, true)) return s;
+        a.key_send = make_key(st, t);
+        a.ring_send = st->ring(r.slot_send);
+        a.send_local_off = st->meta_local(r.slot_send);
+        a.send_sb_base = st->meta_sb(r.slot_send);
+        if (r.recv) {
+            a.key_recv = make_key(st, r.step_recv);
+            a.ring_recv = st->ring(r.slot_recv);
+            a.recv_local_off = st->meta_local(r.slot_recv);
+            a.recv_sb_base = st->meta_sb(r.slot_recv);
+        }
+        am::k_sparse<<<st->grid_sparse, 256, 0, st->stream>>>(a);
+        AM_HIP(hipGetLastError());
+    }
+    st->last_t = t;
+    return AM_OK;
+}
+
+am_status am_lookahead(void *out, uint32_t out_dtype, const float *w, const float *w_prev, uint64_t n, float gamma, void *hip_stream)
+{
+    if (!out || !w || !w_prev) return fail(AM_EINVAL, "NULL pointer");
+    if (out_dtype > AM_BF16) return fail(AM_EINVAL, "unknown dtype");
+    if (!std::isfinite(gamma)) return fail(AM_EINVAL, "gamma not finite");
+    if (!aligned(w, 16) || !aligned(w_prev, 16) || !aligned(out, out_dtype == AM_BF16 ? 8 : 16)) return fail(AM_EALIGN, "pointer not aligned");
+    if (n == 0) return AM_OK;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const uint64_t ngroups = (n + 3) / 4;
+    const uint64_t blocks_needed = (ngroups + 255) / 256;
+    const uint32_t grid = (uint32_t)(blocks_needed < 256 * 16 ? blocks_needed : 256 * 16);
+    if (out_dtype == AM_BF16) am::k_lookahead<true><<<grid, 256, 0, s>>>(out, w, w_prev, n, (double)gamma);
+    else am::k_lookahead<false><<<grid, 256, 0, s>>>(out, w, w_prev, n, (double)gamma);
+    AM_HIP(hipGetLastError());
+    return AM_OK;
+}
+
+am_status am_subset_indices(am_state *st, uint64_t t, uint64_t *dev_out, uint64_t capacity, uint64_t *dev_count)
+{
+    if (!st) return fail(AM_EINVAL, "state is NULL");
+    if (!dev_count) return fail(AM_EINVAL, "dev_count is NULL");
+    if (!dev_out && capacity) return fail(AM_EINVAL, "dev_out is NULL with capacity > 0");
+    if (!aligned(dev_out, 8) || !aligned(dev_count, 8)) return fail(AM_EALIGN, "pointer not 8-byte aligned");
+    const uint32_t scratch = st->lay.slots;          // the metadata block after the ring slots' own
+    if (am_status s = launch_subset_offsets(st, t, scratch, dev_count, false)) return s;
+    if (capacity) {
+        am::k_subset_write<<<st->grid_step, 256, 0, st->stream>>>(make_key(st, t), st->cfg.n, st->lay.ntiles,
+                                                                  st->meta_local(scratch), st->meta_sb(scratch), dev_out, capacity);
+        AM_HIP(hipGetLastError());
+    }
+    return AM_OK;
+}
+
+am_status am_read_flags(am_state *st, uint32_t *out_flags)
+{
+    if (!st || !out_flags) return fail(AM_EINVAL, "NULL argument");
+    AM_HIP(hipMemcpyAsync(out_flags, st->flags(), sizeof(uint32_t), hipMemcpyDeviceToHost, st->stream));
+    AM_HIP(hipStreamSynchronize(st->stream));
+    return AM_OK;
+}
+
+am_status am_set_profiling(am_state *st, int on)
+{
+    if (!st) return fail(AM_EINVAL, "state is NULL");
+    if (on && !st->profiling) st->ev_used = 0;
+    st->profiling = on != 0;
+    return AM_OK;
+}
+
+am_status am_get_profile(am_state *st, double *out_kernel_ms, uint64_t *out_launches)
+{
+    if (!st || !out_kernel_ms || !out_launches) return fail(AM_EINVAL, "NULL argument");
+    AM_HIP(hipStreamSynchronize(st->stream));
+    double total = 0.0;
+    for (size_t k = 0; k + 1 < st->ev_used; k += 2) {
+        float ms = 0.f;
+        AM_HIP(hipEventElapsedTime(&ms, st->ev_pool[k], st->ev_pool[k + 1]));
+        total += ms;
+    }
+    *out_kernel_ms = total;
+    *out_launches = st->ev_used / 2;
+    st->ev_used = 0;
+    return AM_OK;
+}
+
+am_status am_ring_info(const am_state *st, uint64_t *out_capacity, uint32_t *out_slots)
+{
+    if (!st) return fail(AM_EINVAL, "state is NULL");
+    if (out_capacity) *out_capacity = st->lay.capacity;
+    if (out_slots) *out_slots = st->lay.slots;
+    return AM_OK;
+}
+
+am_status am_destroy(am_state *st)
+{
+    if (!st) return AM_OK;
+    for (hipEvent_t e : st->ev_pool) (void)hipEventDestroy(e);
+    delete st;
+    return AM_OK;
+}
+
+}  // extern "C"

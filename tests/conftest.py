@@ -15,3 +15,13 @@ def pytest_configure(config):
 @pytest.fixture(scope="session")
 def golden_dir():
     return ROOT / "tests" / "golden"
+
+
+@pytest.fixture(scope="session")
+def amlib():
+    """The built C-ABI library through its binding; built here only when nothing has been built yet."""
+    from paper_2601_22442_amd.build import LIB, build_library
+    if not LIB.exists():
+        build_library(force=True)
+    import paper_2601_22442_amd as am
+    return am

@@ -1,0 +1,328 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle, element by element, on the same
+seeded inputs.  Bar: subset indices bit-exact; fp32 values within 1e-6 relative, bf16 outputs
+within 1e-2 relative, both measured against max(|ref|, rms(ref))."""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as si
+from oracle import oracle as O
+
+pytestmark = pytest.mark.gpu
+
+TOL_F32 = 1e-6
+TOL_BF16 = 1e-2
+EMPTY_P = 1e-12
+
+
+def rel_err(got: np.ndarray, ref: np.ndarray) -> float:
+    got = got.astype(np.float64); ref = ref.astype(np.float64)
+    if ref.size == 0:
+        return 0.0
+    rms = float(np.sqrt(np.mean(ref ** 2)))
+    if rms == 0.0:
+        return 0.0 if not np.any(got) else float("inf")
+    return float(np.max(np.abs(got - ref) / np.maximum(np.abs(ref), rms)))
+
+
+def make_pair(am, n, R, w0=None, fwd_bf16=False, grad_bf16=False, force_fwd=False, **kw):
+    """A GPU stage and an oracle with the same configuration and starting weights.  kw holds the
+    configuration fields that carry the same name (and the same enum values) on both sides."""
+    if w0 is None:
+        w0 = si.stage_weights(n, kw.get("seed", 0))
+    cfg = am.make_config(n, R, fwd_dtype=am.BF16 if fwd_bf16 else am.F32,
+                         grad_dtype=am.BF16 if grad_bf16 else am.F32, **kw)
+    with_fwd = bool(kw.get("lookahead", False)) or fwd_bf16 or force_fwd
+    st = am.init_state(cfg, torch.from_numpy(np.ascontiguousarray(w0)).cuda(), with_fwd=with_fwd)
+    orc = O.Oracle(n, R, fwd_bf16=fwd_bf16, grad_bf16=grad_bf16, **kw)
+    orc.set_w(w0)
+    return st, orc
+
+
+def grads_for(n, R, t, seed, bf16):
+    g = si.replica_grads(n, R, t, seed)
+    if bf16:
+        g = [si.to_bf16_bits(x) for x in g]
+        dev = [torch.from_numpy(x.view(np.int16)).cuda().view(torch.bfloat16) for x in g]
+    else:
+        dev = [torch.from_numpy(x).cuda() for x in g]
+    return g, dev
+
+
+def compare(st, orc, where=""):
+    R = orc.R
+    worst = {}
+    for i in range(R):
+        for name in ("w", "m", "v", "d"):
+            ts = getattr(st, name)
+            if ts is None:
+                continue
+            e = rel_err(ts[i].cpu().numpy(), getattr(orc, name)(i))
+            worst[name] = max(worst.get(name, 0.0), e)
+            assert e < TOL_F32, f"{where} {name}[{i}] rel err {e:.3e}"
+        if st.fwd is not None:
+            bf = st.fwd[i].dtype == torch.bfloat16
+            e = rel_err(st.fwd[i].float().cpu().numpy(), orc.fwd(i))
+            worst["fwd"] = max(worst.get("fwd", 0.0), e)
+            assert e < (TOL_BF16 if bf else TOL_F32), f"{where} fwd[{i}] rel err {e:.3e}"
+    assert st.read_flags() == 0
+    return worst
+
+
+def run_steps(am, n, R, steps, lr=3e-4, lam=0.5, grad_scale=1.0, check_every=1, **kw):
+    print(f"case n={n} R={R} steps={steps} {kw}", flush=True)
+    st, orc = make_pair(am, n, R, **kw)
+    bf = kw.get("grad_bf16", False)
+    for t in range(1, steps + 1):
+        g, gd = grads_for(n, R, t, kw.get("seed", 0), bf)
+        st.step(t, gd, lr, lam, grad_scale)
+        orc.step(t, g, lr, lam, grad_scale)
+        if t % check_every == 0 or t == steps:
+            worst = compare(st, orc, f"n={n} R={R} t={t} {kw}")
+    print("  worst rel err at last step:", {k: f"{v:.1e}" for k, v in worst.items()}, flush=True)
+    return st, orc
+
+
+# --------------------------------------------------------------------------------------------
+# subset indices: bit exact
+# --------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("n,p,seed", [
+    (1, 1.0, 0), (3, 0.5, 1), (255, 0.3, 2), (256, 0.05, 3), (257, 0.05, 3), (100_003, 0.05, 0),
+    (131_072 * 3 + 5, 0.01, 7), (1_048_576, 0.05, 0), (2_000_000, 0.10, 0xDEADBEEF12345678),
+    (70_001, 1.0, 5), (70_001, EMPTY_P, 5),
+])
+def test_subset_indices_bit_exact(amlib, n, p, seed):
+    am = amlib
+    cfg = am.make_config(n, 1, fraction=p, seed=seed, optimizer=am.OPT_SGD, beta1=0.0, correction=am.CORR_NONE)
+    st = am.init_state(cfg, torch.zeros(n))
+    for t in (0, 1, 2, 1000, (1 << 32) + 5):
+        idx, k = st.subset_indices(t)
+        want = O.subset(seed, t, n, p)
+        assert k == want.size
+        assert np.array_equal(idx.cpu().numpy().astype(np.uint64), want), (n, p, seed, t)
+    # truncated output keeps the ascending prefix and still reports the full count
+    idx, k = st.subset_indices(1, capacity=10)
+    want = O.subset(seed, 1, n, p)
+    assert k == want.size and np.array_equal(idx.cpu().numpy().astype(np.uint64), want[:10])
+
+
+def test_subset_indices_beyond_2_to_30(amlib):
+    """n > 2^30: every index produced satisfies the oracle's predicate, and windows of the stage
+    match the oracle's enumeration exactly."""
+    am = amlib
+    n, p, seed, t = (1 << 30) + 12_345, 2e-4, 9, 3
+    cfg = am.make_config(n, 1, fraction=p, seed=seed, optimizer=am.OPT_SGD, beta1=0.0, correction=am.CORR_NONE)
+    st = am.init_state(cfg, None)
+    idx, k = st.subset_indices(t, capacity=400_000)
+    got = idx.cpu().numpy().astype(np.uint64)
+    assert k == got.size and np.all(np.diff(got.astype(np.int64)) > 0) and got[-1] < n
+    rng = np.random.default_rng(0)
+    for mu in rng.choice(got, 300, replace=False):
+        assert O.member(seed, t, int(mu), p)
+    for lo in (0, (1 << 30) - 70_000, n - 200_000, 536_870_912 - 1000):
+        ln = min(200_000, n - lo)
+        want = O.subset(seed, t, ln, p, mu0=lo)
+        assert np.array_equal(got[(got >= lo) & (got < lo + ln)], want)
+    assert abs(k - n * p) < 6 * (n * p) ** 0.5
+
+
+# --------------------------------------------------------------------------------------------
+# fused step
+# --------------------------------------------------------------------------------------------
+def test_config_tiny(amlib):
+    """1,048,576 fp32 params, R=4, staleness 1, 5 % per step, Adam-style state, 10 steps, seed 0."""
+    st, orc = run_steps(amlib, 1_048_576, 4, 10, delay=1, fraction=0.05, seed=0, optimizer=O.OPT_ADAMW)
+    assert any(np.any(orc.d(i)) for i in range(4))           # the EMA path did real work
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 4, 5, 255, 256, 257, 1023, 4099, 131_072 + 7, 3 * 131_072 + 1])
+def test_ragged_sizes(amlib, n):
+    run_steps(amlib, n, 3, 5, delay=1, fraction=0.3, seed=n, optimizer=O.OPT_ADAMW, lookahead=True, gamma=0.9)
+
+
+@pytest.mark.parametrize("R", [1, 2, 3, 5, 8, 16, 32])
+def test_replica_counts(amlib, R):
+    run_steps(amlib, 10_007, R, 6, delay=2, fraction=0.2, seed=R, optimizer=O.OPT_ADAMW)
+
+
+@pytest.mark.parametrize("tau,K", [(0, 1), (0, 3), (1, 1), (1, 2), (3, 1), (2, 3), (7, 1)])
+def test_delay_and_interval(amlib, tau, K):
+    run_steps(amlib, 20_011, 4, 3 * (tau + 1) * K + 2, delay=tau, avg_interval=K, fraction=0.25, seed=5,
+              optimizer=O.OPT_ADAMW, lookahead=True, gamma=0.5)
+
+
+@pytest.mark.parametrize("p", [EMPTY_P, 0.01, 0.05, 0.5, 1.0])
+def test_fractions(amlib, p):
+    run_steps(amlib, 50_021, 4, 6, delay=1, fraction=p, seed=3, optimizer=O.OPT_ADAMW)
+
+
+@pytest.mark.parametrize("opt,b1", [(O.OPT_SGD, 0.0), (O.OPT_SGD, 0.9), (O.OPT_ADAMW, 0.9), (O.OPT_ADAMW, 0.99),
+                                    (O.OPT_NADAMW, 0.99)])
+@pytest.mark.parametrize("corr", [O.CORR_NONE, O.CORR_EMA])
+def test_optimizers_and_corrections(amlib, opt, b1, corr):
+    run_steps(amlib, 30_011, 3, 8, lr=1e-3, delay=2, fraction=0.2, seed=11, optimizer=opt, beta1=b1,
+              correction=corr, lookahead=True, gamma=0.9, weight_decay=0.01)
+
+
+def test_lambda_and_grad_scale(amlib):
+    run_steps(amlib, 12_345, 4, 6, lam=1.0, grad_scale=0.25, delay=1, fraction=0.3, seed=2)
+    run_steps(amlib, 12_345, 4, 6, lam=0.01, delay=1, fraction=0.3, seed=2)
+    run_steps(amlib, 12_345, 4, 6, lam=0.0, delay=1, fraction=0.3, seed=2)
+
+
+@pytest.mark.parametrize("fwd_bf16,grad_bf16,look", [(True, True, True), (True, False, False), (False, True, True),
+                                                     (False, False, False)])
+def test_dtypes(amlib, fwd_bf16, grad_bf16, look):
+    run_steps(amlib, 40_009, 4, 6, delay=1, fraction=0.1, seed=8, fwd_bf16=fwd_bf16, grad_bf16=grad_bf16,
+              lookahead=look, gamma=0.9, force_fwd=True)
+
+
+def test_config_small_model_stage(amlib):
+    """12 d^2 = 7,077,888 params (d=768), R=4, staleness 2, 10 %, look-ahead on, 100 steps."""
+    run_steps(amlib, 7_077_888, 4, 100, check_every=25, delay=2, fraction=0.10, seed=0,
+              optimizer=O.OPT_ADAMW, lookahead=True, gamma=0.9)
+
+
+def test_config_bf16_stage_reduced(amlib):
+    """bf16 gradients and forward weights over fp32 masters, R=16, staleness 8, 1 % (the large
+    configuration's settings on a stage the oracle finishes in seconds)."""
+    run_steps(amlib, 1_000_003, 16, 12, check_every=4, delay=8, fraction=0.01, seed=0, fwd_bf16=True,
+              grad_bf16=True)
+
+
+def test_replicas_apart_from_the_start(amlib):
+    n, R = 9_001, 4
+    w0 = np.stack([si.stage_weights(n, 40 + i) for i in range(R)])
+    st, orc = make_pair(amlib, n, R, w0=w0, delay=1, fraction=0.5, seed=1)
+    for t in range(1, 6):
+        g, gd = grads_for(n, R, t, 1, False)
+        st.step(t, gd, 1e-3, 0.5); orc.step(t, g, 1e-3, 0.5)
+    compare(st, orc)
+
+
+# --------------------------------------------------------------------------------------------
+# full-size stage, sampled: the 125M-parameter configuration in the benchmark's launch shape
+# --------------------------------------------------------------------------------------------
+def _tiled_dev(pool_dev, n, offset):
+    reps = (n + offset) // pool_dev.numel() + 2
+    return pool_dev.repeat(reps)[offset:offset + n].clone()
+
+
+def test_full_size_stage_on_sampled_windows(amlib):
+    am = amlib
+    n, R, tau, p, seed, steps = 125_829_120, 8, 4, 0.05, 0, 7
+    pool_n = 1 << 20
+    w_pool = si.stage_weights(pool_n, seed)
+    cfg = am.make_config(n, R, delay=tau, fraction=p, seed=seed, lookahead=True, gamma=0.9)
+    st = am.init_state(cfg, _tiled_dev(torch.from_numpy(w_pool).cuda(), n, 0))
+    windows = [(0, 70_000), (131_072 * 211 - 3_000, 70_000), (62_914_560 - 5, 40_000), (n - 70_001, 70_001)]
+    oracles = []
+    for lo, ln in windows:
+        orc = O.Oracle(ln, R, delay=tau, fraction=p, seed=seed, lookahead=True, gamma=0.9, mu0=lo)
+        orc.set_w(si.tiled(w_pool, ln, lo))
+        oracles.append(orc)
+    for t in range(1, steps + 1):
+        pools = si.replica_grads(pool_n, R, t, seed)
+        offs = [(7919 * (i + 1) * t) % pool_n for i in range(R)]
+        gd = [_tiled_dev(torch.from_numpy(pools[i]).cuda(), n, offs[i]) for i in range(R)]
+        st.step(t, gd, 3e-4, 0.5)
+        for (lo, ln), orc in zip(windows, oracles):
+            orc.step(t, [si.tiled(pools[i], ln, lo + offs[i]) for i in range(R)], 3e-4, 0.5)
+        del gd
+    torch.cuda.synchronize()
+    for (lo, ln), orc in zip(windows, oracles):
+        for i in range(R):
+            for name in ("w", "m", "v", "d", "fwd"):
+                got = getattr(st, name)[i][lo:lo + ln].cpu().numpy()
+                e = rel_err(got, getattr(orc, name)(i))
+                assert e < TOL_F32, f"window {lo} {name}[{i}] rel err {e:.3e}"
+        assert any(np.any(orc.d(i)) for i in range(R))
+    assert st.read_flags() == 0
+    # the whole-stage subset count agrees with the oracle on the windows and with Binomial(n, p) overall
+    idx, k = st.subset_indices(3)
+    got = idx.cpu().numpy().astype(np.uint64)
+    assert abs(k - n * p) < 6 * (n * p * (1 - p)) ** 0.5
+    for lo, ln in windows:
+        assert np.array_equal(got[(got >= lo) & (got < lo + ln)], O.subset(seed, 3, ln, p, mu0=lo))
+
+
+# --------------------------------------------------------------------------------------------
+# stand-alone entry points
+# --------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("n,R,tau,K,p,corr", [
+    (1, 1, 0, 1, 1.0, O.CORR_EMA), (257, 2, 1, 1, 0.5, O.CORR_EMA), (10_007, 3, 0, 1, 0.2, O.CORR_EMA),
+    (10_007, 4, 2, 1, 0.05, O.CORR_EMA), (10_007, 5, 1, 2, 0.3, O.CORR_NONE), (131_072 + 9, 8, 3, 1, 0.05, O.CORR_EMA),
+    (50_000, 16, 1, 1, 1.0, O.CORR_EMA), (50_000, 32, 2, 1, 0.01, O.CORR_EMA), (50_000, 7, 1, 1, EMPTY_P, O.CORR_EMA),
+])
+def test_sparse_average_alone(amlib, n, R, tau, K, p, corr):
+    """The caller runs its own optimizer (here: adds a seeded perturbation to w between calls)."""
+    am = amlib
+    w0 = np.stack([si.stage_weights(n, 100 + i) for i in range(R)])
+    st, orc = make_pair(am, n, R, w0=w0, delay=tau, avg_interval=K, fraction=p, seed=17, correction=corr,
+                        optimizer=O.OPT_SGD, beta1=0.0)
+    for t in range(1, 3 * (tau + 1) * K + 2):
+        bump = si.replica_grads(n, R, t, 17)
+        for i in range(R):
+            orc.w(i)[:] += bump[i]
+            st.w[i] += torch.from_numpy(bump[i]).cuda()
+        st.sparse_average(t, 0.5)
+        orc.sparse_average(t, 0.5)
+        for i in range(R):
+            assert rel_err(st.w[i].cpu().numpy(), orc.w(i)) < TOL_F32, (t, i)
+            if st.d is not None:
+                assert rel_err(st.d[i].cpu().numpy(), orc.d(i)) < TOL_F32, (t, i)
+    assert st.read_flags() == 0
+
+
+@pytest.mark.parametrize("n", [1, 5, 1000, 1_000_003])
+@pytest.mark.parametrize("bf16", [False, True])
+def test_lookahead_alone(amlib, n, bf16):
+    am = amlib
+    w = si.stage_weights(n, 1); wp = si.stage_weights(n, 2)
+    out = am.lookahead(torch.from_numpy(w).cuda(), torch.from_numpy(wp).cuda(), 0.9, am.BF16 if bf16 else am.F32)
+    if bf16:
+        ref = si.bf16_bits_to_f32(O.lookahead(w, wp, O.f32(0.9), bf16=True))
+        assert rel_err(out.float().cpu().numpy(), ref) < TOL_BF16
+    else:
+        assert rel_err(out.cpu().numpy(), O.lookahead(w, wp, O.f32(0.9))) < TOL_F32
+
+
+# --------------------------------------------------------------------------------------------
+# API behaviour on the device
+# --------------------------------------------------------------------------------------------
+def test_step_order_and_argument_errors(amlib):
+    am = amlib
+    n, R = 1000, 2
+    st = am.init_state(am.make_config(n, R, delay=1, fraction=0.1), torch.zeros(n))
+    g = [torch.zeros(n, device="cuda") for _ in range(R)]
+    with pytest.raises(am.AsyncMeshError) as e:
+        st.step(2, g, 1e-3)
+    assert e.value.status == -4
+    st.step(1, g, 1e-3)
+    with pytest.raises(am.AsyncMeshError) as e:
+        st.step(1, g, 1e-3)
+    assert e.value.status == -4
+    with pytest.raises(am.AsyncMeshError) as e:
+        st.step(2, [g[0], g[1][1:]], 1e-3)                      # misaligned gradient pointer
+    assert e.value.status == -2
+    with pytest.raises(am.AsyncMeshError) as e:
+        st.step(2, g, 1e-3, lambda_t=1.5)
+    assert e.value.status == -1
+    st.step(2, g, 1e-3)                                         # failed calls left the state untouched
+    cap, slots = st.ring_info()
+    assert slots == 2 and 100 <= cap <= n
+
+
+def test_kernel_profiling_hooks(amlib):
+    am = amlib
+    n, R = 200_000, 2
+    st = am.init_state(am.make_config(n, R, delay=1, fraction=0.1), torch.zeros(n))
+    g = [torch.zeros(n, device="cuda") for _ in range(R)]
+    st.set_profiling(True)
+    for t in range(1, 6):
+        st.step(t, g, 1e-3)
+    ms, k = st.get_profile()
+    assert k == 5 and 0.0 < ms < 1000.0
+    st.set_profiling(False)
+    st.step(6, g, 1e-3)
+    assert st.get_profile()[1] == 0

@@ -1,0 +1,85 @@
+"""Host-only checks of the C-ABI library: it loads, exports every symbol the header declares, and
+rejects bad arguments before any device work.  No GPU needed (no compute call is made)."""
+import ctypes as C
+import re
+from pathlib import Path
+
+import pytest
+
+ROOT = Path(__file__).resolve().parent.parent
+
+
+def _declared_symbols():
+    text = (ROOT / "include" / "asyncmesh.h").read_text()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(am_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(amlib):
+    names = _declared_symbols()
+    assert {"am_init_state", "am_step", "am_sparse_average", "am_lookahead", "am_subset_indices",
+            "am_workspace_bytes", "am_destroy"} <= set(names)
+    raw = C.CDLL(str(ROOT / "paper_2601_22442_amd" / "libasyncmesh.so"))
+    for name in names:
+        assert hasattr(raw, name), name
+    from paper_2601_22442_amd import binding
+    assert sorted(binding.EXPORTS) == names
+
+
+def test_config_struct_matches_header_layout(amlib):
+    from paper_2601_22442_amd.binding import Config
+    assert C.sizeof(Config) == 88
+    assert Config.fraction.offset == 24 and Config.seed.offset == 32
+    assert Config.beta1.offset == 40 and Config.gamma.offset == 56
+    assert Config.grad_dtype.offset == 72 and Config.momentum_decay.offset == 80
+
+
+def test_workspace_bytes_and_capacity_formula(amlib):
+    am = amlib
+    cfg = am.make_config(125_829_120, 8, delay=4, fraction=0.05)
+    b = am.workspace_bytes(cfg)
+    # ring: 5 slots x (p n + 12 sigma + 1024) coordinates x 8 replicas x 4 bytes, plus small offset tables
+    cap = 0.05 * 125_829_120 + 12 * (125_829_120 * 0.05 * 0.95) ** 0.5 + 1024
+    assert 5 * cap * 32 < b < 5 * cap * 32 * 1.02
+    full = am.workspace_bytes(am.make_config(1000, 2, delay=0, fraction=1.0))
+    assert full >= 1000 * 2 * 4
+
+
+@pytest.mark.parametrize("kw,needle", [
+    (dict(n=0), "n="), (dict(n=2 ** 32), "n="), (dict(replicas=0), "replicas"), (dict(replicas=33), "replicas"),
+    (dict(avg_interval=0), "avg_interval"), (dict(fraction=0.0), "fraction"), (dict(fraction=1.5), "fraction"),
+    (dict(optimizer=7), "optimizer"), (dict(correction=5), "correction"), (dict(beta1=1.0), "beta1"),
+    (dict(fwd_dtype=3), "dtype"),
+])
+def test_bad_configs_are_rejected(amlib, kw, needle):
+    am = amlib
+    base = dict(n=1000, replicas=2)
+    base.update(kw)
+    with pytest.raises(am.AsyncMeshError) as e:
+        am.workspace_bytes(am.make_config(**base))
+    assert e.value.status == -1 and needle in str(e.value)
+
+
+def test_init_rejects_bad_buffers_before_touching_the_device(amlib):
+    am = amlib
+    from paper_2601_22442_amd import binding as B
+    cfg = am.make_config(1000, 2, delay=1, fraction=0.1)
+    h = C.c_void_p(None)
+
+    def table(vals):
+        return C.cast((C.c_void_p * len(vals))(*vals), C.POINTER(C.c_void_p))
+
+    good = table([0x10000, 0x20000])
+    bufs = B.Buffers(w=good, m=good, v=good, d=good, workspace=0x100000, workspace_bytes=16)
+    assert B.lib.am_init_state(C.byref(cfg), C.byref(bufs), None, C.byref(h)) == -3        # workspace too small
+    assert b"workspace" in B.lib.am_last_error()
+    bufs = B.Buffers(w=table([0x10000, 0x20004]), m=good, v=good, d=good, workspace=0x100000, workspace_bytes=1 << 30)
+    assert B.lib.am_init_state(C.byref(cfg), C.byref(bufs), None, C.byref(h)) == -2        # misaligned w[1]
+    bufs = B.Buffers(w=good, m=good, v=good, workspace=0x100000, workspace_bytes=1 << 30)
+    assert B.lib.am_init_state(C.byref(cfg), C.byref(bufs), None, C.byref(h)) == -1        # EMA needs d
+    cfg2 = am.make_config(1000, 2, lookahead=True, gamma=0.5)
+    bufs = B.Buffers(w=good, m=good, v=good, d=good, workspace=0x100000, workspace_bytes=1 << 30)
+    assert B.lib.am_init_state(C.byref(cfg2), C.byref(bufs), None, C.byref(h)) == -1       # look-ahead needs fwd
+    assert B.lib.am_step(None, 1, None, 0.1, 0.5, 1.0) == -1
+    assert B.lib.am_lookahead(None, 0, None, None, 4, 0.5, None) == -1
+    assert B.lib.am_destroy(None) == 0
