@@ -1,0 +1,189 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused AsyncMesh stage update on one MI355X.
+
+A step = one am_step call = local optimizer step + look-ahead + asynchronous sparse averaging
+with EMA correction for all R replicas of the stage (subset offsets, then the fused kernel).
+Inputs (weights, optimizer state, gradients) are resident in HBM before the timed region.
+Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import sys
+import time
+from pathlib import Path
+
+ROOT = Path(__file__).resolve().parent
+if str(ROOT) not in sys.path:
+    sys.path.insert(0, str(ROOT))
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
+
+# name -> (n, R, tau, p, lookahead, bf16)
+WORKLOADS = {
+    "tiny":      dict(n=1_048_576,     R=4,  tau=1, p=0.05, lookahead=False, bf16=False),
+    "small":     dict(n=7_077_888,     R=4,  tau=2, p=0.10, lookahead=True,  bf16=False),
+    "stage125m": dict(n=125_829_120,   R=8,  tau=4, p=0.05, lookahead=True,  bf16=False),
+    "bf16":      dict(n=125_829_120,   R=16, tau=8, p=0.01, lookahead=False, bf16=True),
+    "model1b":   dict(n=1_000_000_000, R=8,  tau=4, p=0.10, lookahead=True,  bf16=False),
+}
+DESCRIPTION = {
+    "stage125m": "one stage of 125,829,120 fp32 params (2.5 layers at d=2048), R=8 replicas, staleness 4, "
+                 "subset 5%, AdamW, look-ahead and EMA correction on",
+}
+
+
+def algorithmic_bytes_per_param(w) -> float:
+    """HBM bytes the method itself must move per parameter per replica per step: read w, g, m, v and
+    write w, m, v (28 B with fp32 gradients), the forward copy (4 B, or 2 B in bf16), and per
+    selected coordinate 4 B sent, 4 B received, 4+4 B of the EMA vector read and written (16 p)."""
+    g = 2 if w["bf16"] else 4
+    fwd = (2 if w["bf16"] else 4) if (w["lookahead"] or w["bf16"]) else 0
+    return 4 + g + 4 + 4 + 4 + 4 + 4 + fwd + 16 * w["p"]
+
+
+def tiled_on_device(torch, pool, n, offset):
+    reps = (n + offset) // pool.numel() + 2
+    return pool.repeat(reps)[offset:offset + n].clone()
+
+
+def cpu_baseline(w, seconds_target=12.0):
+    """The oracle as it stands, on the host cores, on a slice of the same workload."""
+    import numpy as np
+
+    import synth_inputs as si
+    from oracle import oracle as O
+
+    R, tau, p = w["R"], w["tau"], w["p"]
+    ln = min(w["n"], 2_000_000)
+    orc = O.Oracle(ln, R, delay=tau, fraction=p, seed=0, lookahead=w["lookahead"], gamma=0.9,
+                   fwd_bf16=w["bf16"], grad_bf16=w["bf16"], mu0=0)
+    orc.set_w(si.stage_weights(ln, 0))
+    grads = si.replica_grads(ln, R, 1, 0)
+    if w["bf16"]:
+        grads = [si.to_bf16_bits(g) for g in grads]
+    t_used, done = 0.0, 0
+    t = 0
+    while True:
+        t += 1
+        t0 = time.perf_counter()
+        orc.step(t, grads, 3e-4, 0.5)
+        dt = time.perf_counter() - t0
+        if t > tau + 1:                       # count only steps where send and receive are both live
+            t_used += dt
+            done += 1
+        if t_used > seconds_target or t > 2000:
+            break
+    return {
+        "value": R * ln * done / t_used, "unit": "params/s", "cores": O.threads(), "kind": "oracle",
+        "sample": f"first {ln} coordinates of the stage, all {R} replicas, {done} steps after start-up "
+                  f"({t_used:.1f} s of CPU time)",
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="stage125m", choices=sorted(WORKLOADS))
+    ap.add_argument("--skip-cpu", action="store_true", help="leave out the CPU oracle leg (profiling runs)")
+    ap.add_argument("--avg-interval", type=int, default=1, help="K: average every K-th step (1 = the paper's default)")
+    ap.add_argument("--fraction", type=float, default=None, help="override the workload's subset fraction p")
+    ap.add_argument("--delay", type=int, default=None, help="override the workload's delay tau")
+    ap.add_argument("--no-correction", action="store_true", help="plain delayed averaging (no EMA vector)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (replicas are simulated as HBM-resident copies on it); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2601_22442_amd as am
+    import synth_inputs as si
+
+    w = dict(WORKLOADS[args.workload])
+    if args.fraction is not None:
+        w["p"] = args.fraction
+    if args.delay is not None:
+        w["tau"] = args.delay
+    n, R, tau, p = w["n"], w["R"], w["tau"], w["p"]
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    cfg = am.make_config(n, R, delay=tau, avg_interval=args.avg_interval, fraction=p, seed=0, optimizer=am.OPT_ADAMW,
+                         correction=am.CORR_NONE if args.no_correction else am.CORR_EMA,
+                         lookahead=w["lookahead"], gamma=0.9,
+                         fwd_dtype=am.BF16 if w["bf16"] else am.F32,
+                         grad_dtype=am.BF16 if w["bf16"] else am.F32)
+    pool_n = 1 << 20
+    w_pool = torch.from_numpy(si.stage_weights(pool_n, 0)).to(dev)
+    st = am.init_state(cfg, tiled_on_device(torch, w_pool, n, 0))
+    # two gradient sets per replica, cycled (traffic per step is unchanged)
+    gsets = []
+    for s in range(2):
+        pools = si.replica_grads(pool_n, R, s + 1, 0)
+        gs = []
+        for i in range(R):
+            g = tiled_on_device(torch, torch.from_numpy(pools[i]).to(dev), n, (7919 * (i + 1) * (s + 1)) % pool_n)
+            gs.append(g.to(torch.bfloat16) if w["bf16"] else g)
+        gsets.append(gs)
+    torch.cuda.synchronize()
+
+    warm = max(args.warmup, tau + 1)          # timed region starts with send and receive both live
+    t = 0
+    for _ in range(warm):
+        t += 1
+        st.step(t, gsets[t & 1], 3e-4, 0.5)
+    torch.cuda.synchronize()
+
+    st.set_profiling(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        t += 1
+        st.step(t, gsets[t & 1], 3e-4, 0.5)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    kernel_ms, launches = st.get_profile()
+    st.set_profiling(False)
+    assert launches == args.steps
+    assert st.read_flags() == 0, "a subset overflowed its ring slot"
+
+    bpp = algorithmic_bytes_per_param(w)
+    bytes_per_launch = bpp * R * n
+    kernel_s = kernel_ms / 1e3 / launches
+    achieved = bytes_per_launch / kernel_s / 1e9
+    ms_per_step = elapsed / args.steps * 1e3
+    out = {
+        "metric": "fused AsyncMesh step: params/s and achieved HBM GB/s (% peak), 125M stage",
+        "value": R * n * args.steps / elapsed,
+        "unit": "params/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": warm, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": DESCRIPTION.get(args.workload, args.workload), "name": args.workload,
+                   "n": n, "replicas": R, "delay": tau, "fraction": p, "lookahead": w["lookahead"],
+                   "avg_interval": args.avg_interval,
+                   "correction": "none" if args.no_correction else "ema", "bf16": w["bf16"], "algorithmic_bytes_per_param": bpp},
+        "step_GBps": bytes_per_launch / (elapsed / args.steps) / 1e9,
+        "step_frac_of_hbm_peak": bytes_per_launch / (elapsed / args.steps) / 1e9 / HBM_PEAK_GBPS,
+        "roofline": {"kernel": "k_step", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": MEASURED_TRAFFIC.get(args.workload),
+                     "kernel_ms": kernel_s * 1e3, "algorithmic_bytes_per_launch": bytes_per_launch},
+    }
+    if not args.skip_cpu:
+        del st, gsets
+        out["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(out))
+
+
+# HBM bytes per launch of the fused kernel measured with rocprofv3 hardware counters (FETCH_SIZE and
+# WRITE_SIZE, each scaled by what the same counter reads for a plain copy of known size); see
+# profiles/.  None = not measured for that workload.
+MEASURED_TRAFFIC: dict = {}
+
+
+if __name__ == "__main__":
+    main()

@@ -17,6 +17,17 @@ HIPCC_FLAGS = [
 ]
 
 
+PROBE_SRC = PKG / "csrc" / "hbm_copy_probe.hip"
+PROBE = PKG / "hbm_copy_probe"
+
+
+def build_probe() -> Path:
+    """The plain-copy yardstick program (used only when profiling)."""
+    flags = [f for f in HIPCC_FLAGS if f not in ("-fPIC", "-shared")]
+    subprocess.run(["hipcc", *flags, "-o", str(PROBE), str(PROBE_SRC)], check=True)
+    return PROBE
+
+
 def stale() -> bool:
     return not LIB.exists() or any(LIB.stat().st_mtime < d.stat().st_mtime for d in DEPS)
 
@@ -32,3 +43,4 @@ def build_library(force: bool = True, verbose: bool = False) -> Path:
 
 if __name__ == "__main__":
     print(build_library(force=True, verbose="-v" in sys.argv))
+    print(build_probe())

@@ -5,8 +5,8 @@
 //   tile       = 64 groups = 256 consecutive coordinates = what one wavefront handles at a time
 //   superblock = 512 tiles; subset counts are scanned inside a superblock by one workgroup and
 //                across superblocks by a second tiny kernel
-// A selected coordinate's position in a packed ring slot is
-//   sb_base[tile >> 9] + local_off[tile] + (selected coordinates of the tile before it).
+// A tile's first entry in a packed list (of selected coordinates, or of the whole lines a tile
+// owns in a ring slot) is  sb_base[tile >> 9] + local_off[tile].
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -15,6 +15,7 @@ namespace am {
 
 constexpr uint32_t kTileCoords = 256;
 constexpr uint32_t kTilesPerSuperblock = 512;
+constexpr uint32_t kLineFloats = 32;        // floats per 128-byte line, the unit in which memory is written
 constexpr uint32_t kMaxReplicas = 32;
 
 // ---------------------------------------------------------------------------------------------

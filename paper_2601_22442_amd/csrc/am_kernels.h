@@ -9,10 +9,12 @@ namespace am {
 // Subset offsets:   k_subset_count  ->  k_subset_scan
 // =============================================================================================
 // One workgroup (4 waves) per superblock of 512 tiles.  Pure integer hashing, no array reads.
-// Writes, per tile, the number of selected coordinates in the tiles of the same superblock before
+// A tile's size is its number of selected coordinates (unit = 1: packed index lists) or that
+// number rounded up to whole 128-byte lines of 32 floats (unit = 32: ring slots, where every tile
+// owns whole lines).  Writes, per tile, the summed size of the tiles of the same superblock before
 // it (local_off) and, per superblock, its total (sb_sum).
 __global__ void __launch_bounds__(256)
-k_subset_count(SubsetKey key, uint64_t n, uint32_t ntiles,
+k_subset_count(SubsetKey key, uint64_t n, uint32_t ntiles, uint32_t unit,
                uint32_t *__restrict__ local_off, uint32_t *__restrict__ sb_sum)
 {
     __shared__ uint32_t cnt[kTilesPerSuperblock];
@@ -30,7 +32,7 @@ k_subset_count(SubsetKey key, uint64_t n, uint32_t ntiles,
             const int nvalid = mu >= n ? 0 : (n - mu >= 4u ? 4 : (int)(n - mu));
             (void)wave_prefix_mask4(member_mask(key, group, nvalid), total);
         }
-        if (lane == 0) cnt[k] = total;
+        if (lane == 0) cnt[k] = (total + unit - 1u) / unit;
     }
     __syncthreads();
 
@@ -121,18 +123,18 @@ struct StepArgs {
     // averaging
     uint32_t do_send, do_recv, ema, same_slot;     // same_slot: tau = 0, the average is of this step's w^
     SubsetKey key_send, key_recv;
-    float *ring_send;                              // slot written now: [position][replica]
+    float *ring_send;                              // slot written now: [replica][line][32]
     const float *ring_recv;                        // slot sent tau rounds ago
-    const uint32_t *send_local_off, *send_sb_base;
+    const uint32_t *send_local_off, *send_sb_base; // first line of each tile = sb_base[tile >> 9] + local_off[tile]
     const uint32_t *recv_local_off, *recv_sb_base;
-    uint32_t capacity;
+    uint32_t cap_lines;                            // lines (of 32 floats) per replica in a ring slot
     double lambda, one_minus_lambda;
     // optimizer, every coefficient a per-step scalar evaluated once on the host in double:
-    //   g  = grad_scale * g_raw
+    //   g  = grad_scale * g_raw                        (folded into b_m, b_v, c_g on the host)
     //   m' = a_m m + b_m g ;  v' = a_v v + b_v g^2
     //   w^ = w - (c_wd w + (c_g g + c_m m') / (c_v sqrt(v') + eps))           (Adam family)
     //   w^ = w - (c_wd w + c_m m')     resp.     w - (c_wd w + c_g g)          (SGD with / without momentum)
-    double grad_scale, a_m, b_m, a_v, b_v, c_wd, c_g, c_m, c_v, eps;
+    double a_m, b_m, a_v, b_v, c_wd, c_g, c_m, c_v, eps;
     uint32_t lookahead;
     double gamma;
 };
@@ -163,30 +165,30 @@ __device__ __forceinline__ double quotient_refined(double num, double den)
     return (double)q0 + (double)((float)residual * rden);
 }
 
-// Local optimizer step of replica i on one group: loads w, g (and m, v), returns the new values.
-template <int OPT, bool GRAD_BF16>
-__device__ __forceinline__ void local_step(const StepArgs &a, uint32_t i, uint64_t mu, int nvalid,
-                                           F4 &w_old, F4 &w_hat, F4 &m_new, F4 &v_new)
+// What one replica's update of one group reads from memory.
+struct GroupIn {
+    F4 w, g, m, v;          // weights, gradients (widened), moments
+    F4 d;                   // EMA entries of the group (loaded only when its sector receives)
+    float sent[4];          // what this replica sent tau rounds ago for my received coordinates
+};
+
+// Local optimizer step on one group, from loaded operands.
+template <int OPT>
+__device__ __forceinline__ void local_step(const StepArgs &a, const GroupIn &in, F4 &w_hat, F4 &m_new, F4 &v_new)
 {
-    w_old = load_f32x4(a.w[i], mu, nvalid);
-    F4 g = GRAD_BF16 ? load_bf16x4(static_cast<const uint16_t *>(a.g[i]), mu, nvalid)
-                     : load_f32x4(static_cast<const float *>(a.g[i]), mu, nvalid);
-    F4 m_old, v_old;
-    if (OPT != kOptSgdPlain) m_old = load_f32x4(a.m[i], mu, nvalid);
-    if (OPT == kOptAdam) v_old = load_f32x4(a.v[i], mu, nvalid);
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        const double gj = a.grad_scale * (double)g.v[j];
-        const double wo = (double)w_old.v[j];
+        const double gj = (double)in.g.v[j];                   // grad_scale is folded into b_m, b_v, c_g
+        const double wo = (double)in.w.v[j];
         double step;                                           // what is subtracted besides the decay
         if (OPT == kOptSgdPlain) {
             step = a.c_g * gj;
         } else if (OPT == kOptSgdMomentum) {
-            m_new.v[j] = (float)fma(a.a_m, (double)m_old.v[j], gj);
+            m_new.v[j] = (float)fma(a.a_m, (double)in.m.v[j], a.b_m * gj);
             step = a.c_m * (double)m_new.v[j];
         } else {
-            m_new.v[j] = (float)fma(a.a_m, (double)m_old.v[j], a.b_m * gj);
-            v_new.v[j] = (float)fma(a.a_v, (double)v_old.v[j], a.b_v * gj * gj);
+            m_new.v[j] = (float)fma(a.a_m, (double)in.m.v[j], a.b_m * gj);
+            v_new.v[j] = (float)fma(a.a_v, (double)in.v.v[j], a.b_v * gj * gj);
             const double den = fma(a.c_v, sqrt_refined(v_new.v[j]), a.eps);
             const double num = fma(a.c_g, gj, a.c_m * (double)m_new.v[j]);
             step = quotient_refined(num, den);
@@ -195,139 +197,248 @@ __device__ __forceinline__ void local_step(const StepArgs &a, uint32_t i, uint64
     }
 }
 
+// LDS written by some lanes of a wave is about to be read by other lanes of the same wave.
+__device__ __forceinline__ void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Where the coordinates of one group sit in the subsets of this step.
+struct GroupSubsets {
+    uint32_t mask_send, mask_recv;      // bit j: coordinate 4*group + j is sent / received now
+    uint32_t rank_send, rank_recv;      // rank of the first such coordinate among those of the tile
+    uint64_t run_send, run_recv;        // float offset, inside one replica's part of the slot, of the tile's lines
+    uint32_t lines_send;                // whole lines the tile sends per replica
+    bool line_recv;                     // the 128-byte line of d holding the group receives something
+};
+
+// Issues the loads of replica i's operands for one group.
+template <int OPT, bool GRAD_BF16>
+__device__ __forceinline__ void load_group(const StepArgs &a, uint32_t i, uint64_t mu, int nvalid,
+                                           const GroupSubsets &s, GroupIn &in)
+{
+    in.w = load_f32x4(a.w[i], mu, nvalid);
+    in.g = GRAD_BF16 ? load_bf16x4(static_cast<const uint16_t *>(a.g[i]), mu, nvalid)
+                     : load_f32x4(static_cast<const float *>(a.g[i]), mu, nvalid);
+    if (OPT != kOptSgdPlain) in.m = load_f32x4(a.m[i], mu, nvalid);
+    if (OPT == kOptAdam) in.v = load_f32x4(a.v[i], mu, nvalid);
+    if (s.line_recv) in.d = load_f32x4(a.d[i], mu, nvalid);
+    if (s.mask_recv && a.ema && !a.same_slot) {
+        const float *__restrict__ src = a.ring_recv + (uint64_t)i * a.cap_lines * kLineFloats + s.run_recv + s.rank_recv;
+        uint32_t c = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if ((s.mask_recv >> j) & 1u) in.sent[j] = src[c++];
+    }
+}
+
+// Replica i of one group, from loaded operands to stored results.
+template <int OPT, int FWD>
+__device__ __forceinline__ void step_replica(const StepArgs &a, uint32_t i, uint64_t mu, int nvalid, uint32_t lane,
+                                             const GroupSubsets &s, const float (&abar)[4], GroupIn &in,
+                                             float *send_lds)
+{
+    F4 w_hat, m_new, v_new;
+    local_step<OPT>(a, in, w_hat, m_new, v_new);
+
+    if (s.lines_send) {
+        // send: the tile's w^ values are gathered in LDS (the tail of the last line stays zero) and
+        // leave as whole 128-byte lines
+        uint32_t c = s.rank_send;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if ((s.mask_send >> j) & 1u) send_lds[c++] = w_hat.v[j];
+        wave_lds_sync();
+        float *__restrict__ dst = a.ring_send + (uint64_t)i * a.cap_lines * kLineFloats + s.run_send;
+        for (uint32_t r = lane; r < s.lines_send * kLineFloats; r += 64u) dst[r] = send_lds[r];
+        wave_lds_sync();
+    }
+
+    F4 w_new = w_hat;
+    if (s.mask_recv) {                                     // receive: old average (+ EMA of staleness)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if ((s.mask_recv >> j) & 1u) {
+                if (a.ema) {
+                    const float sent = a.same_slot ? w_hat.v[j] : in.sent[j];
+                    in.d.v[j] = (float)fma(a.one_minus_lambda, (double)in.d.v[j],
+                                           a.lambda * ((double)w_hat.v[j] - (double)sent));
+                    w_new.v[j] = (float)((double)abar[j] + (double)in.d.v[j]);
+                } else {
+                    w_new.v[j] = abar[j];
+                }
+            }
+    }
+    if (s.line_recv) store_f32x4(a.d[i], mu, nvalid, in.d);
+
+    store_f32x4(a.w[i], mu, nvalid, w_new);
+    if (OPT != kOptSgdPlain) store_f32x4(a.m[i], mu, nvalid, m_new);
+    if (OPT == kOptAdam) store_f32x4(a.v[i], mu, nvalid, v_new);
+    if (FWD != kFwdNone) {
+        F4 f = w_new;
+        if (a.lookahead) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                f.v[j] = (float)fma(a.gamma, (double)w_hat.v[j] - (double)in.w.v[j], (double)w_new.v[j]);
+        }
+        if (FWD == kFwdF32) store_f32x4(static_cast<float *>(a.fwd[i]), mu, nvalid, f);
+        else store_bf16x4(static_cast<uint16_t *>(a.fwd[i]), mu, nvalid, f);
+    }
+}
+
 // One wavefront per tile; one lane per group; the lane walks over all R replicas of its group, so
-// the subset hash is paid once per group (not once per replica) and the replica mean needs no
-// communication between lanes.
+// the subset hash is paid once per group (not once per replica) and everything a replica's update
+// needs is in the lane's registers.  The loads of replica i+1 are issued before replica i is
+// computed, so two replicas' worth of reads are in flight per wave.
+//
+// This memory system writes 128-byte lines: a narrower write costs a read-modify-write of the line
+// and, measured, several times the time of a whole-line write.  Both sparse structures are
+// therefore laid out so that only whole lines are ever written:
+//  * Ring slot: per replica, every tile owns ceil(count / 32) whole lines ([replica][line][32]);
+//    a tile's selected values sit at the start of its lines in ascending coordinate order, the rest
+//    of the last line is zero.  A wave gathers its values in LDS and stores whole lines.
+//  * EMA vector d: dense in memory, touched only on received coordinates.  The 8 lanes that share
+//    a 128-byte line of d load and store their groups together whenever any of them holds a
+//    received coordinate, so the line is rewritten as a whole.
+//
+// FULL = every coordinate of the tile exists (all but possibly the last tile of the stage): all
+// dense accesses are unconditional 128-bit ones.
+template <int OPT, bool GRAD_BF16, int FWD, bool FULL>
+__device__ __forceinline__ void step_tile(const StepArgs &a, uint32_t tile, uint32_t lane,
+                                          float *abar_lds, float *send_lds)
+{
+    const uint32_t R = a.replicas;
+    const double inv_r = 1.0 / (double)R;
+    const uint64_t group = (uint64_t)tile * 64u + lane;
+    const uint64_t mu = group * 4u;
+    const int nvalid = FULL ? 4 : (mu >= a.n ? 0 : (a.n - mu >= 4u ? 4 : (int)(a.n - mu)));
+    const uint64_t slot_floats = (uint64_t)a.cap_lines * kLineFloats;      // per replica
+
+    // ---- subsets: which of my 4 coordinates are sent now / received now, and where the tile's
+    //      lines start.  A tile whose lines would pass the slot capacity is left out, at send and at
+    //      receive alike.
+    GroupSubsets s;
+    s.mask_send = s.mask_recv = s.rank_send = s.rank_recv = s.lines_send = 0;
+    s.run_send = s.run_recv = 0;
+    uint32_t count_recv = 0;
+    if (a.do_send) {
+        uint32_t count;
+        s.mask_send = member_mask(a.key_send, group, nvalid);
+        s.rank_send = wave_prefix_mask4(s.mask_send, count);
+        const uint32_t first = a.send_sb_base[tile / kTilesPerSuperblock] + a.send_local_off[tile];
+        s.lines_send = (count + kLineFloats - 1u) / kLineFloats;
+        if ((uint64_t)first + s.lines_send > a.cap_lines) { s.mask_send = 0; s.lines_send = 0; count = 0; }
+        s.run_send = (uint64_t)first * kLineFloats;
+        if (a.same_slot) count_recv = count;
+    }
+    if (a.do_recv) {
+        if (a.same_slot) {
+            s.mask_recv = s.mask_send; s.rank_recv = s.rank_send; s.run_recv = s.run_send;
+        } else {
+            s.mask_recv = member_mask(a.key_recv, group, nvalid);
+            s.rank_recv = wave_prefix_mask4(s.mask_recv, count_recv);
+            const uint32_t first = a.recv_sb_base[tile / kTilesPerSuperblock] + a.recv_local_off[tile];
+            const uint32_t lines = (count_recv + kLineFloats - 1u) / kLineFloats;
+            if ((uint64_t)first + lines > a.cap_lines) { s.mask_recv = 0; count_recv = 0; }
+            s.run_recv = (uint64_t)first * kLineFloats;
+        }
+    }
+    {
+        const uint64_t any = __ballot(s.mask_recv != 0u);
+        s.line_recv = a.ema && (((any >> (lane & ~7u)) & 0xFFull) != 0ull);
+    }
+
+    // first replica's operands go out before anything else waits on memory
+    GroupIn cur;
+    load_group<OPT, GRAD_BF16>(a, 0, mu, nvalid, s, cur);
+
+    if (s.lines_send) {                                     // zero the gather area once: line tails stay zero
+        for (uint32_t r = lane; r < s.lines_send * kLineFloats; r += 64u) send_lds[r] = 0.f;
+    }
+
+    // ---- old average of the coordinates received now
+    float abar[4] = {0.f, 0.f, 0.f, 0.f};
+    if (a.do_recv && !a.same_slot) {
+        // lane c sums what the R replicas sent for the c-th received coordinate of the tile
+        for (uint32_t c = lane; c < count_recv; c += 64u) {
+            double sum = 0.;
+            const float *__restrict__ src = a.ring_recv + s.run_recv + c;
+            for (uint32_t i0 = 0; i0 < R; i0 += 8u) {              // 8 independent loads in flight
+                float t[8];
+#pragma unroll
+                for (uint32_t k = 0; k < 8u; ++k) {                 // past the last replica: reload it, count it as 0
+                    const uint32_t i = i0 + k < R ? i0 + k : R - 1u;
+                    t[k] = src[(uint64_t)i * slot_floats];
+                }
+#pragma unroll
+                for (uint32_t k = 0; k < 8u; ++k) sum += i0 + k < R ? (double)t[k] : 0.0;
+            }
+            abar_lds[c] = (float)(sum * inv_r);
+        }
+        wave_lds_sync();
+        uint32_t c = s.rank_recv;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if ((s.mask_recv >> j) & 1u) abar[j] = abar_lds[c++];
+    } else if (a.do_recv && s.mask_recv) {
+        // tau = 0: the average is over this step's local results of all replicas
+        double sum[4] = {0., 0., 0., 0.};
+        for (uint32_t i = 0; i < R; ++i) {
+            GroupIn in;
+            F4 w_hat, m_new, v_new;
+            load_group<OPT, GRAD_BF16>(a, i, mu, nvalid, s, in);
+            local_step<OPT>(a, in, w_hat, m_new, v_new);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) sum[j] += (double)w_hat.v[j];
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) abar[j] = (float)(sum[j] * inv_r);
+    }
+    wave_lds_sync();
+
+    // ---- all replicas of this group, two operand buffers in turn: the loads of replica i+1 are in
+    //      flight while replica i is computed and stored
+    GroupIn other;
+    for (uint32_t i = 0; i < R; i += 2u) {
+        if (i + 1u < R) load_group<OPT, GRAD_BF16>(a, i + 1u, mu, nvalid, s, other);
+        step_replica<OPT, FWD>(a, i, mu, nvalid, lane, s, abar, cur, send_lds);
+        if (i + 1u < R) {
+            if (i + 2u < R) load_group<OPT, GRAD_BF16>(a, i + 2u, mu, nvalid, s, cur);
+            step_replica<OPT, FWD>(a, i + 1u, mu, nvalid, lane, s, abar, other, send_lds);
+        }
+    }
+}
+
+// grid = one workgroup per 4 consecutive tiles (no loop over tiles: each wave handles one tile and
+// retires, which keeps the chip's accesses sweeping through memory as one compact front)
 template <int OPT, bool GRAD_BF16, int FWD>
 __global__ void __launch_bounds__(256)
 k_step(const StepArgs a)
 {
-    const uint32_t lane = threadIdx.x & 63u;
-    const uint32_t nwaves = gridDim.x * 4u;
-    const uint32_t R = a.replicas;
-    const double inv_r = 1.0 / (double)R;
-
-    for (uint32_t tile = blockIdx.x * 4u + (threadIdx.x >> 6); tile < a.ntiles; tile += nwaves) {
-        const uint64_t group = (uint64_t)tile * 64u + lane;
-        const uint64_t mu = group * 4u;
-        const int nvalid = mu >= a.n ? 0 : (a.n - mu >= 4u ? 4 : (int)(a.n - mu));
-
-        // ---- subsets: which of my 4 coordinates are sent now / received now, and where they sit
-        uint32_t mask_send = 0, mask_recv = 0;
-        uint64_t pos_send = 0, pos_recv = 0;
-        if (a.do_send) {
-            uint32_t total;
-            mask_send = member_mask(a.key_send, group, nvalid);
-            pos_send = (uint64_t)a.send_sb_base[tile / kTilesPerSuperblock] + a.send_local_off[tile]
-                     + wave_prefix_mask4(mask_send, total);
-        }
-        if (a.do_recv) {
-            if (a.same_slot) {
-                mask_recv = mask_send;
-                pos_recv = pos_send;
-            } else {
-                uint32_t total;
-                mask_recv = member_mask(a.key_recv, group, nvalid);
-                pos_recv = (uint64_t)a.recv_sb_base[tile / kTilesPerSuperblock] + a.recv_local_off[tile]
-                         + wave_prefix_mask4(mask_recv, total);
-            }
-        }
-        // coordinates beyond the slot capacity are left out, at send and at receive alike
-        {
-            uint64_t p = pos_send;
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                if ((mask_send >> j) & 1u) { if (p >= a.capacity) mask_send &= ~(1u << j); ++p; }
-            p = pos_recv;
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                if ((mask_recv >> j) & 1u) { if (p >= a.capacity) mask_recv &= ~(1u << j); ++p; }
-        }
-
-        // ---- old average of the coordinates received now
-        float abar[4] = {0.f, 0.f, 0.f, 0.f};
-        if (mask_recv) {
-            if (a.same_slot) {
-                // tau = 0: the average is over this step's local results of all replicas
-                double sum[4] = {0., 0., 0., 0.};
-                for (uint32_t i = 0; i < R; ++i) {
-                    F4 w_old, w_hat, m_new, v_new;
-                    local_step<OPT, GRAD_BF16>(a, i, mu, nvalid, w_old, w_hat, m_new, v_new);
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) sum[j] += (double)w_hat.v[j];
-                }
-#pragma unroll
-                for (int j = 0; j < 4; ++j) abar[j] = (float)(sum[j] * inv_r);
-            } else {
-                uint64_t p = pos_recv;
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    if ((mask_recv >> j) & 1u) {
-                        const float *__restrict__ src = a.ring_recv + p * R;
-                        double sum = 0.;
-                        for (uint32_t i = 0; i < R; ++i) sum += (double)src[i];
-                        abar[j] = (float)(sum * inv_r);
-                        ++p;
-                    }
-            }
-        }
-
-        // ---- all replicas of this group
-        for (uint32_t i = 0; i < R; ++i) {
-            F4 w_old, w_hat, m_new, v_new;
-            local_step<OPT, GRAD_BF16>(a, i, mu, nvalid, w_old, w_hat, m_new, v_new);
-
-            if (mask_send) {                                   // send: w^ goes into the slot of this round
-                uint64_t p = pos_send;
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    if ((mask_send >> j) & 1u) { a.ring_send[p * R + i] = w_hat.v[j]; ++p; }
-            }
-
-            F4 w_new = w_hat;
-            if (mask_recv) {                                   // receive: old average (+ EMA of staleness)
-                uint64_t p = pos_recv;
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    if ((mask_recv >> j) & 1u) {
-                        if (a.ema) {
-                            const float sent = a.same_slot ? w_hat.v[j] : a.ring_recv[p * R + i];
-                            float *__restrict__ dp = a.d[i] + mu + j;
-                            const float dn = (float)fma(a.one_minus_lambda, (double)*dp,
-                                                        a.lambda * ((double)w_hat.v[j] - (double)sent));
-                            *dp = dn;
-                            w_new.v[j] = (float)((double)abar[j] + (double)dn);
-                        } else {
-                            w_new.v[j] = abar[j];
-                        }
-                        ++p;
-                    }
-            }
-
-            store_f32x4(a.w[i], mu, nvalid, w_new);
-            if (OPT != kOptSgdPlain) store_f32x4(a.m[i], mu, nvalid, m_new);
-            if (OPT == kOptAdam) store_f32x4(a.v[i], mu, nvalid, v_new);
-            if (FWD != kFwdNone) {
-                F4 f = w_new;
-                if (a.lookahead) {
-#pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        f.v[j] = (float)fma(a.gamma, (double)w_hat.v[j] - (double)w_old.v[j], (double)w_new.v[j]);
-                }
-                if (FWD == kFwdF32) store_f32x4(static_cast<float *>(a.fwd[i]), mu, nvalid, f);
-                else store_bf16x4(static_cast<uint16_t *>(a.fwd[i]), mu, nvalid, f);
-            }
-        }
-    }
+    __shared__ float abar_lds[4][kTileCoords];
+    __shared__ float send_lds[4][kTileCoords];
+    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    const uint32_t tile = (uint32_t)__builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4u + wave));   // same for the wave
+    if (tile >= a.ntiles) return;
+    if ((uint64_t)(tile + 1u) * kTileCoords <= a.n)
+        step_tile<OPT, GRAD_BF16, FWD, true>(a, tile, lane, abar_lds[wave], send_lds[wave]);
+    else
+        step_tile<OPT, GRAD_BF16, FWD, false>(a, tile, lane, abar_lds[wave], send_lds[wave]);
 }
 
 // =============================================================================================
 // Stand-alone sparse averaging (am_sparse_average): gather / average / scatter on the current w
 // =============================================================================================
-// One workgroup handles 4 tiles at a time, one per wave.  Each wave hashes its tile, compacts the
-// selected coordinates into an ascending index list in LDS, then walks that list with its lanes
-// laid out as (coordinate, replica): lane = c * L + i with L = the power of two >= R, so that ring
-// accesses are contiguous and the replica mean is a butterfly over L neighbouring lanes.
+// One workgroup handles 4 tiles at a time, one per wave.  Each wave hashes its tile and compacts the
+// selected coordinates into an ascending index list in LDS.
+//   send:    the wave walks its lines of the slot ([replica][line][32]) with consecutive lanes on
+//            consecutive floats, gathering w_i[mu] for the list entries and zero for the tail of the
+//            last line, so that whole lines are written;
+//   receive: lanes are laid out as (coordinate, replica), lane = c * L + i with L = the power of
+//            two >= R, the replica mean is a butterfly over L neighbouring lanes, and each lane
+//            updates its own (coordinate, replica) entry of d and w.
 struct SparseArgs {
     float *w[kMaxReplicas];
     float *d[kMaxReplicas];
@@ -341,7 +452,7 @@ struct SparseArgs {
     const float *ring_recv;
     const uint32_t *send_local_off, *send_sb_base;
     const uint32_t *recv_local_off, *recv_sb_base;
-    uint32_t capacity;
+    uint32_t cap_lines;
     double lambda, one_minus_lambda;
 };
 
@@ -372,24 +483,26 @@ k_sparse(const SparseArgs a)
     const uint32_t c_in_pass = lane / L, i = lane % L;
     const bool lane_has_replica = i < R;
     const double inv_r = 1.0 / (double)R;
+    const uint64_t slot_floats = (uint64_t)a.cap_lines * kLineFloats;
     const uint32_t ngroups_of_tiles = (a.ntiles + 3u) / 4u;
 
     for (uint32_t tg = blockIdx.x; tg < ngroups_of_tiles; tg += gridDim.x) {   // uniform per workgroup
         const uint32_t tile = tg * 4u + wave;
         const bool live = tile < a.ntiles;
 
-        // ---------------- send: ring[slot(t)][pos][i] <- w_i[mu] for mu in S^t
+        // ---------------- send: ring[slot(t)][i][lines of the tile] <- w_i[mu] for mu in S^t
         if (a.do_send) {
             uint32_t count = 0;
             if (live) count = stage_tile_indices(a.key_send, a.n, tile, lane, idx);
             __syncthreads();
             if (live) {
-                const uint64_t base = (uint64_t)a.send_sb_base[tile / kTilesPerSuperblock] + a.send_local_off[tile];
-                for (uint32_t c0 = 0; c0 < count; c0 += coords_per_pass) {
-                    const uint32_t c = c0 + c_in_pass;
-                    if (c < count && lane_has_replica && base + c < a.capacity) {
-                        const uint64_t mu = (uint64_t)tile * kTileCoords + idx[c];
-                        a.ring_send[(base + c) * R + i] = a.w[i][mu];
+                const uint32_t first = a.send_sb_base[tile / kTilesPerSuperblock] + a.send_local_off[tile];
+                const uint32_t run = (count + kLineFloats - 1u) / kLineFloats * kLineFloats;   // floats per replica
+                if ((uint64_t)first + run / kLineFloats <= a.cap_lines) {
+                    for (uint32_t e = lane; e < run * R; e += 64u) {
+                        const uint32_t r = e % run, rep = e / run;
+                        const float val = r < count ? a.w[rep][(uint64_t)tile * kTileCoords + idx[r]] : 0.f;
+                        a.ring_send[(uint64_t)rep * slot_floats + (uint64_t)first * kLineFloats + r] = val;
                     }
                 }
             }
@@ -403,12 +516,15 @@ k_sparse(const SparseArgs a)
             if (live) count = stage_tile_indices(a.key_recv, a.n, tile, lane, idx);
             __syncthreads();
             if (live) {
-                const uint64_t base = (uint64_t)a.recv_sb_base[tile / kTilesPerSuperblock] + a.recv_local_off[tile];
+                const uint32_t first = a.recv_sb_base[tile / kTilesPerSuperblock] + a.recv_local_off[tile];
+                const uint32_t lines = (count + kLineFloats - 1u) / kLineFloats;
+                if ((uint64_t)first + lines > a.cap_lines) count = 0;                 // tile was left out at send
+                const float *__restrict__ src = a.ring_recv + (uint64_t)first * kLineFloats;
                 for (uint32_t c0 = 0; c0 < count; c0 += coords_per_pass) {      // uniform per wave
                     const uint32_t c = c0 + c_in_pass;
-                    const bool on = c < count && lane_has_replica && base + c < a.capacity;
+                    const bool on = c < count && lane_has_replica;
                     float sent = 0.f;
-                    if (on) sent = a.ring_recv[(base + c) * R + i];
+                    if (on) sent = src[(uint64_t)i * slot_floats + c];
                     double sum = (double)sent;
                     for (uint32_t off = 1; off < L; off <<= 1) sum += __shfl_xor(sum, (int)off);
                     if (on) {

@@ -47,37 +47,48 @@ uint64_t subset_threshold(double p)
     return (uint64_t)std::floor(p * 4294967296.0);
 }
 
-// coordinates one ring slot can hold: the expected subset size plus twelve standard deviations
-uint64_t slot_capacity(uint64_t n, double p)
+// Lines (of 32 floats) one replica's part of a ring slot must hold.  Every tile of 256
+// coordinates owns ceil(X / 32) whole lines, X ~ Binomial(256, p) its number of selected
+// coordinates; the slot has room for the expected total plus twelve standard deviations.
+uint64_t slot_capacity_lines(uint64_t ntiles, double p)
 {
-    if (p >= 1.0) return n;
-    const double mean = p * (double)n;
-    const double cap = std::ceil(mean + 12.0 * std::sqrt((double)n * p * (1.0 - p))) + 1024.0;
-    return cap >= (double)n ? n : (uint64_t)cap;
+    const uint64_t all = ntiles * (am::kTileCoords / am::kLineFloats);
+    if (p >= 1.0) return all;
+    double mean = 0.0, sq = 0.0;
+    const double lp = std::log(p), lq = std::log1p(-p), T = am::kTileCoords;
+    for (int k = 0; k <= (int)am::kTileCoords; ++k) {
+        const double pmf = std::exp(std::lgamma(T + 1.0) - std::lgamma(k + 1.0) - std::lgamma(T - k + 1.0) + k * lp + (T - k) * lq);
+        const double lines = (double)((k + am::kLineFloats - 1) / am::kLineFloats);
+        mean += pmf * lines;
+        sq += pmf * lines * lines;
+    }
+    const double var = sq - mean * mean > 0.0 ? sq - mean * mean : 0.0;
+    const double cap = std::ceil((double)ntiles * mean + 12.0 * std::sqrt((double)ntiles * var)) + 64.0;
+    return cap >= (double)all ? all : (uint64_t)cap;
 }
 
 struct Layout {
     uint32_t ntiles, nsb, slots;
-    uint64_t capacity;
+    uint64_t cap_lines;
     uint64_t off_flags, off_meta, meta_stride, meta_sb_off, off_ring, ring_stride, total;
 };
 
 // workspace = [flags 256 B][meta x (slots + 1)][ring values x slots]
 //   meta    = local_off u32[ntiles] | sb_base u32[nsb + 1]         (the extra one serves am_subset_indices)
-//   ring    = capacity * R fp32, position-major: [position][replica]
+//   ring    = R * cap_lines * 32 fp32: [replica][line][32]; a tile owns whole lines
 Layout make_layout(const am_config &c)
 {
     Layout L{};
     L.ntiles = (uint32_t)((c.n + am::kTileCoords - 1) / am::kTileCoords);
     L.nsb = (L.ntiles + am::kTilesPerSuperblock - 1) / am::kTilesPerSuperblock;
     L.slots = c.delay + 1;
-    L.capacity = slot_capacity(c.n, c.fraction);
+    L.cap_lines = slot_capacity_lines(L.ntiles, c.fraction);
     L.off_flags = 0;
     L.off_meta = 256;
     L.meta_sb_off = round_up((uint64_t)L.ntiles * 4, 256);
     L.meta_stride = L.meta_sb_off + round_up(((uint64_t)L.nsb + 1) * 4, 256);
     L.off_ring = L.off_meta + L.meta_stride * (L.slots + 1);
-    L.ring_stride = round_up(L.capacity * c.replicas * 4, 256);
+    L.ring_stride = round_up(L.cap_lines * am::kLineFloats * c.replicas * 4, 256);
     L.total = L.off_ring + L.ring_stride * L.slots;
     return L;
 }
@@ -139,15 +150,17 @@ am::SubsetKey make_key(const am_state *st, uint64_t step)
     return k;
 }
 
-// count + scan of S^step into the metadata block `slot`
-am_status launch_subset_offsets(am_state *st, uint64_t step, uint32_t slot, uint64_t *dev_count, bool check_capacity)
+// count + scan of S^step into the metadata block `slot`; for_ring: sizes in whole lines per tile and
+// checked against the slot capacity, else sizes in coordinates
+am_status launch_subset_offsets(am_state *st, uint64_t step, uint32_t slot, uint64_t *dev_count, bool for_ring)
 {
     const Layout &L = st->lay;
     am::k_subset_count<<<L.nsb, 256, 0, st->stream>>>(make_key(st, step), st->cfg.n, L.ntiles,
+                                                      for_ring ? am::kLineFloats : 1u,
                                                       st->meta_local(slot), st->meta_sb(slot));
     AM_HIP(hipGetLastError());
-    am::k_subset_scan<<<1, 256, 0, st->stream>>>(st->meta_sb(slot), L.nsb, (uint32_t)L.capacity,
-                                                 check_capacity ? st->flags() : nullptr, dev_count);
+    am::k_subset_scan<<<1, 256, 0, st->stream>>>(st->meta_sb(slot), L.nsb, (uint32_t)L.cap_lines,
+                                                 for_ring ? st->flags() : nullptr, dev_count);
     AM_HIP(hipGetLastError());
     return AM_OK;
 }
@@ -190,14 +203,6 @@ template <int OPT>
 am_status launch_step_grad(am_state *st, const am::StepArgs &a)
 {
     return st->cfg.grad_dtype == AM_BF16 ? launch_step_fwd<OPT, true>(st, a) : launch_step_fwd<OPT, false>(st, a);
-}
-
-uint32_t env_u32(const char *name, uint32_t dflt)
-{
-    const char *s = std::getenv(name);
-    if (!s || !*s) return dflt;
-    const long v = std::strtol(s, nullptr, 10);
-    return v > 0 ? (uint32_t)v : dflt;
 }
 
 }  // namespace
@@ -268,11 +273,12 @@ am_status am_init_state(const am_config *cfg, const am_buffers *buf, void *hip_s
     int cus = 256;
     if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, st->device);
     if (e != hipSuccess) { delete st; return fail(AM_EHIP, "device query: %s", hipGetErrorString(e)); }
-    // persistent grids: a fixed number of workgroups per compute unit, each striding over the tiles
+    // fused step: one workgroup per 4 tiles; the other kernels stride over the tiles with a fixed
+    // number of workgroups per compute unit
     const uint32_t tile_groups = (lay.ntiles + 3) / 4;
-    const uint32_t want = (uint32_t)cus * env_u32("AM_BLOCKS_PER_CU", 8);
-    st->grid_step = tile_groups < want ? tile_groups : want;
-    st->grid_sparse = st->grid_step;
+    const uint32_t want = (uint32_t)cus * 8u;
+    st->grid_step = tile_groups;
+    st->grid_sparse = tile_groups < want ? tile_groups : want;
 
     // d^0 = 0 and zero moments; clear flags, offsets and ring
     const size_t bytes = (size_t)cfg->n * sizeof(float);
@@ -308,11 +314,11 @@ am_status am_step(am_state *st, uint64_t t, const void *const *grads, float lr, 
         a.fwd[i] = st->fwd[i]; a.g[i] = grads[i];
     }
     a.n = c.n; a.ntiles = st->lay.ntiles; a.replicas = c.replicas;
-    a.capacity = (uint32_t)st->lay.capacity;
+    a.cap_lines = (uint32_t)st->lay.cap_lines;
     a.lambda = (double)lambda_t; a.one_minus_lambda = 1.0 - (double)lambda_t;
     a.ema = c.correction == AM_CORR_EMA;
     a.lookahead = c.lookahead != 0; a.gamma = (double)c.gamma;
-    a.grad_scale = (double)grad_scale;
+    const double gs = (double)grad_scale;        // folded into the coefficients that multiply g
 
     // per-step scalars, evaluated once in double
     const double b1 = c.beta1, b2 = c.beta2, lrd = lr, wd = c.weight_decay;
@@ -320,11 +326,11 @@ am_status am_step(am_state *st, uint64_t t, const void *const *grads, float lr, 
     a.c_wd = lrd * wd;
     a.eps = (double)c.eps;
     if (c.optimizer == AM_OPT_SGD) {
-        a.a_m = b1; a.c_m = lrd; a.c_g = lrd;
+        a.a_m = b1; a.b_m = gs; a.c_m = lrd; a.c_g = lrd * gs;
     } else {
         const double bc1 = 1.0 - std::pow(b1, (double)t), bc2 = 1.0 - std::pow(b2, (double)t);
-        a.a_m = b1; a.b_m = 1.0 - b1;
-        a.a_v = b2; a.b_v = 1.0 - b2;
+        a.a_m = b1; a.b_m = (1.0 - b1) * gs;
+        a.a_v = b2; a.b_v = (1.0 - b2) * gs * gs;
         a.c_v = 1.0 / std::sqrt(bc2);
         if (c.optimizer == AM_OPT_ADAMW) {
             a.c_g = 0.0; a.c_m = lrd / bc1;
@@ -332,7 +338,7 @@ am_status am_step(am_state *st, uint64_t t, const void *const *grads, float lr, 
             const double mu_t = b1 * (1.0 - 0.5 * std::pow(0.96, (double)t * c.momentum_decay));
             const double mu_t1 = b1 * (1.0 - 0.5 * std::pow(0.96, (double)(t + 1) * c.momentum_decay));
             mu_prod_next = st->mu_product * mu_t;
-            a.c_g = lrd * (1.0 - mu_t) / (1.0 - mu_prod_next);
+            a.c_g = lrd * (1.0 - mu_t) / (1.0 - mu_prod_next) * gs;
             a.c_m = lrd * mu_t1 / (1.0 - mu_prod_next * mu_t1);
         }
     }
@@ -393,7 +399,7 @@ am_status am_sparse_average(am_state *st, uint64_t t, float lambda_t)
         while (L < c.replicas) L <<= 1;
         a.lanes_per_coord = L;
         a.do_send = 1; a.do_recv = r.recv; a.ema = c.correction == AM_CORR_EMA;
-        a.capacity = (uint32_t)st->lay.capacity;
+        a.cap_lines = (uint32_t)st->lay.cap_lines;
         a.lambda = (double)lambda_t; a.one_minus_lambda = 1.0 - (double)lambda_t;
         if (am_status s = launch_subset_offsets(st, t, r.slot_send, nullptr, true)) return s;
         a.key_send = make_key(st, t);
@@ -439,7 +445,7 @@ am_status am_subset_indices(am_state *st, uint64_t t, uint64_t *dev_out, uint64_
     const uint32_t scratch = st->lay.slots;          // the metadata block after the ring slots' own
     if (am_status s = launch_subset_offsets(st, t, scratch, dev_count, false)) return s;
     if (capacity) {
-        am::k_subset_write<<<st->grid_step, 256, 0, st->stream>>>(make_key(st, t), st->cfg.n, st->lay.ntiles,
+        am::k_subset_write<<<st->grid_sparse, 256, 0, st->stream>>>(make_key(st, t), st->cfg.n, st->lay.ntiles,
                                                                   st->meta_local(scratch), st->meta_sb(scratch), dev_out, capacity);
         AM_HIP(hipGetLastError());
     }
@@ -481,7 +487,7 @@ am_status am_get_profile(am_state *st, double *out_kernel_ms, uint64_t *out_laun
 am_status am_ring_info(const am_state *st, uint64_t *out_capacity, uint32_t *out_slots)
 {
     if (!st) return fail(AM_EINVAL, "state is NULL");
-    if (out_capacity) *out_capacity = st->lay.capacity;
+    if (out_capacity) *out_capacity = st->lay.cap_lines * am::kLineFloats;
     if (out_slots) *out_slots = st->lay.slots;
     return AM_OK;
 }

@@ -1,6 +1,7 @@
 """Host-only checks of the C-ABI library: it loads, exports every symbol the header declares, and
 rejects bad arguments before any device work.  No GPU needed (no compute call is made)."""
 import ctypes as C
+import math
 import re
 from pathlib import Path
 
@@ -35,14 +36,21 @@ def test_config_struct_matches_header_layout(amlib):
 
 
 def test_workspace_bytes_and_capacity_formula(amlib):
+    """A ring slot holds, per replica, whole 128-byte lines: ceil(X/32) per tile of 256 coordinates,
+    X ~ Binomial(256, p); room for the expected total plus 12 standard deviations."""
     am = amlib
-    cfg = am.make_config(125_829_120, 8, delay=4, fraction=0.05)
-    b = am.workspace_bytes(cfg)
-    # ring: 5 slots x (p n + 12 sigma + 1024) coordinates x 8 replicas x 4 bytes, plus small offset tables
-    cap = 0.05 * 125_829_120 + 12 * (125_829_120 * 0.05 * 0.95) ** 0.5 + 1024
-    assert 5 * cap * 32 < b < 5 * cap * 32 * 1.02
+    n, R, tau, p = 125_829_120, 8, 4, 0.05
+    ntiles = n // 256
+    pmf = [math.comb(256, k) * p ** k * (1 - p) ** (256 - k) for k in range(257)]
+    lines = [(k + 31) // 32 for k in range(257)]
+    mean = sum(a * b for a, b in zip(pmf, lines))
+    var = sum(a * b * b for a, b in zip(pmf, lines)) - mean ** 2
+    cap_lines = math.ceil(ntiles * mean + 12 * math.sqrt(ntiles * var)) + 64
+    ring = (tau + 1) * cap_lines * 32 * R * 4
+    b = am.workspace_bytes(am.make_config(n, R, delay=tau, fraction=p))
+    assert ring < b < ring * 1.01 + (1 << 20)                     # plus the small offset tables
     full = am.workspace_bytes(am.make_config(1000, 2, delay=0, fraction=1.0))
-    assert full >= 1000 * 2 * 4
+    assert full >= 4 * 256 * 2 * 4                                 # p = 1: every tile owns all its 8 lines
 
 
 @pytest.mark.parametrize("kw,needle", [
