@@ -100,8 +100,10 @@ typedef struct {
     uint64_t workspace_bytes;
 } am_buffers;
 
-/* Bytes of workspace a configuration needs.  The delay ring inside it holds tau+1 slots of
- * capacity(n, p) * R packed fp32 values, capacity = min(n, p n + 12 sqrt(n p (1-p)) + 1024). */
+/* Bytes of workspace a configuration needs.  The delay ring inside it holds tau+1 slots; in a
+ * slot every tile of 256 coordinates owns, per replica, ceil(X/32) whole 128-byte lines, X its
+ * number of selected coordinates; a slot has room for the expected number of lines plus twelve
+ * standard deviations. */
 am_status am_workspace_bytes(const am_config *cfg, uint64_t *out_bytes);
 
 /* Validate, bind the caller's buffers and the stream, and enqueue the zeroing of m, v, d (d^0 = 0,
@@ -132,8 +134,8 @@ am_status am_lookahead(void *out, uint32_t out_dtype, const float *w, const floa
 am_status am_subset_indices(am_state *st, uint64_t t, uint64_t *dev_out, uint64_t capacity,
                             uint64_t *dev_count);
 
-/* Synchronises the stream and returns sticky flags: bit 0 = some |S^t| exceeded the ring slot
- * capacity (the excess coordinates were left out of that round's average). */
+/* Synchronises the stream and returns sticky flags: bit 0 = some S^t needed more lines than a
+ * ring slot holds (the tiles past the capacity were left out of that round's average). */
 am_status am_read_flags(am_state *st, uint32_t *out_flags);
 
 /* Optional timing of the fused step kernel alone: while on, am_step brackets that kernel with
@@ -142,7 +144,8 @@ am_status am_read_flags(am_state *st, uint32_t *out_flags);
 am_status am_set_profiling(am_state *st, int on);
 am_status am_get_profile(am_state *st, double *out_kernel_ms, uint64_t *out_launches);
 
-/* Slot capacity (coordinates) and number of ring slots of this state; host values, no device work. */
+/* Slot capacity (fp32 positions per replica = lines * 32) and number of ring slots of this state;
+ * host values, no device work. */
 am_status am_ring_info(const am_state *st, uint64_t *out_capacity, uint32_t *out_slots);
 
 am_status am_destroy(am_state *st);
