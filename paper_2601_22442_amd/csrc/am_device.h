@@ -89,12 +89,16 @@ __device__ __forceinline__ uint32_t wave_prefix_mask4(uint32_t mask4, uint32_t &
 // 128-bit accesses with a scalar tail (only the last group of an array can be partial)
 // ---------------------------------------------------------------------------------------------
 struct F4 { float v[4]; };
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef uint32_t v2u __attribute__((ext_vector_type(2)));
 
+// The arrays of this update are streamed: every element is read once and written once per step,
+// so the dense accesses carry the non-temporal hint.
 __device__ __forceinline__ F4 load_f32x4(const float *__restrict__ p, uint64_t mu, int nvalid)
 {
     F4 r;
     if (nvalid == 4) {
-        const float4 t = *reinterpret_cast<const float4 *>(p + mu);
+        const v4f t = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(p + mu));
         r.v[0] = t.x; r.v[1] = t.y; r.v[2] = t.z; r.v[3] = t.w;
     } else {
 #pragma unroll
@@ -106,7 +110,8 @@ __device__ __forceinline__ F4 load_f32x4(const float *__restrict__ p, uint64_t m
 __device__ __forceinline__ void store_f32x4(float *__restrict__ p, uint64_t mu, int nvalid, const F4 &x)
 {
     if (nvalid == 4) {
-        *reinterpret_cast<float4 *>(p + mu) = make_float4(x.v[0], x.v[1], x.v[2], x.v[3]);
+        const v4f t = {x.v[0], x.v[1], x.v[2], x.v[3]};
+        __builtin_nontemporal_store(t, reinterpret_cast<v4f *>(p + mu));
     } else {
 #pragma unroll
         for (int j = 0; j < 4; ++j)
@@ -127,7 +132,7 @@ __device__ __forceinline__ F4 load_bf16x4(const uint16_t *__restrict__ p, uint64
 {
     F4 r;
     if (nvalid == 4) {
-        const uint2 t = *reinterpret_cast<const uint2 *>(p + mu);
+        const v2u t = __builtin_nontemporal_load(reinterpret_cast<const v2u *>(p + mu));
         r.v[0] = __uint_as_float(t.x << 16);
         r.v[1] = __uint_as_float(t.x & 0xFFFF0000u);
         r.v[2] = __uint_as_float(t.y << 16);
@@ -142,10 +147,10 @@ __device__ __forceinline__ F4 load_bf16x4(const uint16_t *__restrict__ p, uint64
 __device__ __forceinline__ void store_bf16x4(uint16_t *__restrict__ p, uint64_t mu, int nvalid, const F4 &x)
 {
     if (nvalid == 4) {
-        uint2 t;
+        v2u t;
         t.x = (uint32_t)f32_to_bf16_bits(x.v[0]) | ((uint32_t)f32_to_bf16_bits(x.v[1]) << 16);
         t.y = (uint32_t)f32_to_bf16_bits(x.v[2]) | ((uint32_t)f32_to_bf16_bits(x.v[3]) << 16);
-        *reinterpret_cast<uint2 *>(p + mu) = t;
+        __builtin_nontemporal_store(t, reinterpret_cast<v2u *>(p + mu));
     } else {
 #pragma unroll
         for (int j = 0; j < 4; ++j)

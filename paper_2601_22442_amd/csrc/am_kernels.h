@@ -168,8 +168,7 @@ __device__ __forceinline__ double quotient_refined(double num, double den)
 // What one replica's update of one group reads from memory.
 struct GroupIn {
     F4 w, g, m, v;          // weights, gradients (widened), moments
-    F4 d;                   // EMA entries of the group (loaded only when its sector receives)
-    float sent[4];          // what this replica sent tau rounds ago for my received coordinates
+    F4 d;                   // EMA entries of the group (loaded only when its line receives)
 };
 
 // Local optimizer step on one group, from loaded operands.
@@ -209,6 +208,7 @@ __device__ __forceinline__ void wave_lds_sync()
 struct GroupSubsets {
     uint32_t mask_send, mask_recv;      // bit j: coordinate 4*group + j is sent / received now
     uint32_t rank_send, rank_recv;      // rank of the first such coordinate among those of the tile
+    uint32_t count_recv;                // received coordinates of the tile
     uint64_t run_send, run_recv;        // float offset, inside one replica's part of the slot, of the tile's lines
     uint32_t lines_send;                // whole lines the tile sends per replica
     bool line_recv;                     // the 128-byte line of d holding the group receives something
@@ -217,28 +217,22 @@ struct GroupSubsets {
 // Issues the loads of replica i's operands for one group.
 template <int OPT, bool GRAD_BF16>
 __device__ __forceinline__ void load_group(const StepArgs &a, uint32_t i, uint64_t mu, int nvalid,
-                                           const GroupSubsets &s, GroupIn &in)
+                                           bool with_d, GroupIn &in)
 {
     in.w = load_f32x4(a.w[i], mu, nvalid);
     in.g = GRAD_BF16 ? load_bf16x4(static_cast<const uint16_t *>(a.g[i]), mu, nvalid)
                      : load_f32x4(static_cast<const float *>(a.g[i]), mu, nvalid);
     if (OPT != kOptSgdPlain) in.m = load_f32x4(a.m[i], mu, nvalid);
     if (OPT == kOptAdam) in.v = load_f32x4(a.v[i], mu, nvalid);
-    if (s.line_recv) in.d = load_f32x4(a.d[i], mu, nvalid);
-    if (s.mask_recv && a.ema && !a.same_slot) {
-        const float *__restrict__ src = a.ring_recv + (uint64_t)i * a.cap_lines * kLineFloats + s.run_recv + s.rank_recv;
-        uint32_t c = 0;
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            if ((s.mask_recv >> j) & 1u) in.sent[j] = src[c++];
-    }
+    if (with_d) in.d = load_f32x4(a.d[i], mu, nvalid);
 }
 
-// Replica i of one group, from loaded operands to stored results.
+// Replica i of one group, from loaded operands to stored results.  sent_lds: what replica i sent
+// tau rounds ago for the received coordinates of the tile, in rank order.
 template <int OPT, int FWD>
 __device__ __forceinline__ void step_replica(const StepArgs &a, uint32_t i, uint64_t mu, int nvalid, uint32_t lane,
                                              const GroupSubsets &s, const float (&abar)[4], GroupIn &in,
-                                             float *send_lds)
+                                             const float *sent_lds, float *send_lds)
 {
     F4 w_hat, m_new, v_new;
     local_step<OPT>(a, in, w_hat, m_new, v_new);
@@ -252,23 +246,25 @@ __device__ __forceinline__ void step_replica(const StepArgs &a, uint32_t i, uint
             if ((s.mask_send >> j) & 1u) send_lds[c++] = w_hat.v[j];
         wave_lds_sync();
         float *__restrict__ dst = a.ring_send + (uint64_t)i * a.cap_lines * kLineFloats + s.run_send;
-        for (uint32_t r = lane; r < s.lines_send * kLineFloats; r += 64u) dst[r] = send_lds[r];
+        for (uint32_t r = lane; r < s.lines_send * kLineFloats; r += 64u) __builtin_nontemporal_store(send_lds[r], dst + r);
         wave_lds_sync();
     }
 
     F4 w_new = w_hat;
     if (s.mask_recv) {                                     // receive: old average (+ EMA of staleness)
+        uint32_t c = s.rank_recv;
 #pragma unroll
         for (int j = 0; j < 4; ++j)
             if ((s.mask_recv >> j) & 1u) {
                 if (a.ema) {
-                    const float sent = a.same_slot ? w_hat.v[j] : in.sent[j];
+                    const float sent = a.same_slot ? w_hat.v[j] : sent_lds[c];
                     in.d.v[j] = (float)fma(a.one_minus_lambda, (double)in.d.v[j],
                                            a.lambda * ((double)w_hat.v[j] - (double)sent));
                     w_new.v[j] = (float)((double)abar[j] + (double)in.d.v[j]);
                 } else {
                     w_new.v[j] = abar[j];
                 }
+                ++c;
             }
     }
     if (s.line_recv) store_f32x4(a.d[i], mu, nvalid, in.d);
@@ -288,10 +284,13 @@ __device__ __forceinline__ void step_replica(const StepArgs &a, uint32_t i, uint
     }
 }
 
-// One wavefront per tile; one lane per group; the lane walks over all R replicas of its group, so
-// the subset hash is paid once per group (not once per replica) and everything a replica's update
-// needs is in the lane's registers.  The loads of replica i+1 are issued before replica i is
-// computed, so two replicas' worth of reads are in flight per wave.
+// One workgroup per tile of 256 coordinates; its waves are the replicas (wave w takes replicas
+// w, w + W, ...; W = min(R, 16) waves), one lane per group of 4 coordinates.  Each wave streams
+// its replica's 1 KB of every array once and retires; measured on MI355X this shape, with
+// non-temporal accesses, is the fastest way through the 4-read / 4-write stream mix of this update.
+// Every wave hashes the tile's two subsets itself (integer work that hides under the memory time);
+// the only thing the waves of a tile share is what the replicas sent tau rounds ago, which they
+// put side by side in LDS to form the old average.
 //
 // This memory system writes 128-byte lines: a narrower write costs a read-modify-write of the line
 // and, measured, several times the time of a whole-line write.  Both sparse structures are
@@ -306,23 +305,26 @@ __device__ __forceinline__ void step_replica(const StepArgs &a, uint32_t i, uint
 // FULL = every coordinate of the tile exists (all but possibly the last tile of the stage): all
 // dense accesses are unconditional 128-bit ones.
 template <int OPT, bool GRAD_BF16, int FWD, bool FULL>
-__device__ __forceinline__ void step_tile(const StepArgs &a, uint32_t tile, uint32_t lane,
-                                          float *abar_lds, float *send_lds)
+__device__ __forceinline__ void step_tile(const StepArgs &a, uint32_t tile, uint32_t wave, uint32_t nwaves,
+                                          uint32_t lane, float *sent_lds, float *send_lds)
 {
     const uint32_t R = a.replicas;
-    const double inv_r = 1.0 / (double)R;
     const uint64_t group = (uint64_t)tile * 64u + lane;
     const uint64_t mu = group * 4u;
     const int nvalid = FULL ? 4 : (mu >= a.n ? 0 : (a.n - mu >= 4u ? 4 : (int)(a.n - mu)));
     const uint64_t slot_floats = (uint64_t)a.cap_lines * kLineFloats;      // per replica
 
+    // first replica's dense operands go out before anything else waits on memory
+    GroupIn in;
+    const bool have_first = wave < R;
+    if (have_first) load_group<OPT, GRAD_BF16>(a, wave, mu, nvalid, false, in);
+
     // ---- subsets: which of my 4 coordinates are sent now / received now, and where the tile's
     //      lines start.  A tile whose lines would pass the slot capacity is left out, at send and at
     //      receive alike.
     GroupSubsets s;
-    s.mask_send = s.mask_recv = s.rank_send = s.rank_recv = s.lines_send = 0;
+    s.mask_send = s.mask_recv = s.rank_send = s.rank_recv = s.lines_send = s.count_recv = 0;
     s.run_send = s.run_recv = 0;
-    uint32_t count_recv = 0;
     if (a.do_send) {
         uint32_t count;
         s.mask_send = member_mask(a.key_send, group, nvalid);
@@ -331,17 +333,17 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, uint32_t tile, uint
         s.lines_send = (count + kLineFloats - 1u) / kLineFloats;
         if ((uint64_t)first + s.lines_send > a.cap_lines) { s.mask_send = 0; s.lines_send = 0; count = 0; }
         s.run_send = (uint64_t)first * kLineFloats;
-        if (a.same_slot) count_recv = count;
+        if (a.same_slot) s.count_recv = count;
     }
     if (a.do_recv) {
         if (a.same_slot) {
             s.mask_recv = s.mask_send; s.rank_recv = s.rank_send; s.run_recv = s.run_send;
         } else {
             s.mask_recv = member_mask(a.key_recv, group, nvalid);
-            s.rank_recv = wave_prefix_mask4(s.mask_recv, count_recv);
+            s.rank_recv = wave_prefix_mask4(s.mask_recv, s.count_recv);
             const uint32_t first = a.recv_sb_base[tile / kTilesPerSuperblock] + a.recv_local_off[tile];
-            const uint32_t lines = (count_recv + kLineFloats - 1u) / kLineFloats;
-            if ((uint64_t)first + lines > a.cap_lines) { s.mask_recv = 0; count_recv = 0; }
+            const uint32_t lines = (s.count_recv + kLineFloats - 1u) / kLineFloats;
+            if ((uint64_t)first + lines > a.cap_lines) { s.mask_recv = 0; s.count_recv = 0; }
             s.run_recv = (uint64_t)first * kLineFloats;
         }
     }
@@ -349,83 +351,72 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, uint32_t tile, uint
         const uint64_t any = __ballot(s.mask_recv != 0u);
         s.line_recv = a.ema && (((any >> (lane & ~7u)) & 0xFFull) != 0ull);
     }
-
-    // first replica's operands go out before anything else waits on memory
-    GroupIn cur;
-    load_group<OPT, GRAD_BF16>(a, 0, mu, nvalid, s, cur);
+    if (have_first && s.line_recv) in.d = load_f32x4(a.d[wave], mu, nvalid);
 
     if (s.lines_send) {                                     // zero the gather area once: line tails stay zero
         for (uint32_t r = lane; r < s.lines_send * kLineFloats; r += 64u) send_lds[r] = 0.f;
     }
 
-    // ---- old average of the coordinates received now
+    // ---- old average of the coordinates received now: every wave puts what its replicas sent
+    //      (tau = 0: their w^ of this step) side by side in LDS, then each lane sums over the replicas
     float abar[4] = {0.f, 0.f, 0.f, 0.f};
-    if (a.do_recv && !a.same_slot) {
-        // lane c sums what the R replicas sent for the c-th received coordinate of the tile
-        for (uint32_t c = lane; c < count_recv; c += 64u) {
-            double sum = 0.;
-            const float *__restrict__ src = a.ring_recv + s.run_recv + c;
-            for (uint32_t i0 = 0; i0 < R; i0 += 8u) {              // 8 independent loads in flight
-                float t[8];
+    if (a.do_recv) {                                        // same for the whole workgroup
+        for (uint32_t i = wave; i < R; i += nwaves) {
+            float *row = sent_lds + i * kTileCoords;
+            if (a.same_slot) {
+                if (s.count_recv) {
+                    GroupIn pre;
+                    F4 w_hat, m_new, v_new;
+                    if (i == wave) pre = in; else load_group<OPT, GRAD_BF16>(a, i, mu, nvalid, false, pre);
+                    local_step<OPT>(a, pre, w_hat, m_new, v_new);
+                    uint32_t c = s.rank_recv;
 #pragma unroll
-                for (uint32_t k = 0; k < 8u; ++k) {                 // past the last replica: reload it, count it as 0
-                    const uint32_t i = i0 + k < R ? i0 + k : R - 1u;
-                    t[k] = src[(uint64_t)i * slot_floats];
+                    for (int j = 0; j < 4; ++j)
+                        if ((s.mask_recv >> j) & 1u) row[c++] = w_hat.v[j];
                 }
-#pragma unroll
-                for (uint32_t k = 0; k < 8u; ++k) sum += i0 + k < R ? (double)t[k] : 0.0;
+            } else {
+                const float *__restrict__ src = a.ring_recv + (uint64_t)i * slot_floats + s.run_recv;
+                for (uint32_t c = lane; c < s.count_recv; c += 64u) row[c] = src[c];
             }
-            abar_lds[c] = (float)(sum * inv_r);
         }
-        wave_lds_sync();
-        uint32_t c = s.rank_recv;
+        __syncthreads();
+        if (s.mask_recv) {
+            const double inv_r = 1.0 / (double)R;
+            uint32_t c = s.rank_recv;
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            if ((s.mask_recv >> j) & 1u) abar[j] = abar_lds[c++];
-    } else if (a.do_recv && s.mask_recv) {
-        // tau = 0: the average is over this step's local results of all replicas
-        double sum[4] = {0., 0., 0., 0.};
-        for (uint32_t i = 0; i < R; ++i) {
-            GroupIn in;
-            F4 w_hat, m_new, v_new;
-            load_group<OPT, GRAD_BF16>(a, i, mu, nvalid, s, in);
-            local_step<OPT>(a, in, w_hat, m_new, v_new);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) sum[j] += (double)w_hat.v[j];
+            for (int j = 0; j < 4; ++j)
+                if ((s.mask_recv >> j) & 1u) {
+                    double sum = 0.;
+                    for (uint32_t i = 0; i < R; ++i) sum += (double)sent_lds[i * kTileCoords + c];
+                    abar[j] = (float)(sum * inv_r);
+                    ++c;
+                }
         }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) abar[j] = (float)(sum[j] * inv_r);
     }
-    wave_lds_sync();
 
-    // ---- all replicas of this group, two operand buffers in turn: the loads of replica i+1 are in
-    //      flight while replica i is computed and stored
-    GroupIn other;
-    for (uint32_t i = 0; i < R; i += 2u) {
-        if (i + 1u < R) load_group<OPT, GRAD_BF16>(a, i + 1u, mu, nvalid, s, other);
-        step_replica<OPT, FWD>(a, i, mu, nvalid, lane, s, abar, cur, send_lds);
-        if (i + 1u < R) {
-            if (i + 2u < R) load_group<OPT, GRAD_BF16>(a, i + 2u, mu, nvalid, s, cur);
-            step_replica<OPT, FWD>(a, i + 1u, mu, nvalid, lane, s, abar, other, send_lds);
-        }
+    // ---- my replicas
+    for (uint32_t i = wave; i < R; i += nwaves) {
+        if (i != wave) load_group<OPT, GRAD_BF16>(a, i, mu, nvalid, s.line_recv, in);
+        step_replica<OPT, FWD>(a, i, mu, nvalid, lane, s, abar, in, sent_lds + i * kTileCoords, send_lds);
     }
 }
 
-// grid = one workgroup per 4 consecutive tiles (no loop over tiles: each wave handles one tile and
-// retires, which keeps the chip's accesses sweeping through memory as one compact front)
+// grid = one workgroup per tile; blockDim = 64 * min(R, 16); dynamic LDS = (R + waves) * 256 floats
 template <int OPT, bool GRAD_BF16, int FWD>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(1024)
 k_step(const StepArgs a)
 {
-    __shared__ float abar_lds[4][kTileCoords];
-    __shared__ float send_lds[4][kTileCoords];
-    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
-    const uint32_t tile = (uint32_t)__builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4u + wave));   // same for the wave
-    if (tile >= a.ntiles) return;
+    extern __shared__ float lds[];
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const uint32_t nwaves = blockDim.x >> 6;
+    const uint32_t tile = blockIdx.x;
+    float *sent_lds = lds;                                              // [R][256]
+    float *send_lds = lds + (a.replicas + wave) * kTileCoords;         // [wave][256]
     if ((uint64_t)(tile + 1u) * kTileCoords <= a.n)
-        step_tile<OPT, GRAD_BF16, FWD, true>(a, tile, lane, abar_lds[wave], send_lds[wave]);
+        step_tile<OPT, GRAD_BF16, FWD, true>(a, tile, wave, nwaves, lane, sent_lds, send_lds);
     else
-        step_tile<OPT, GRAD_BF16, FWD, false>(a, tile, lane, abar_lds[wave], send_lds[wave]);
+        step_tile<OPT, GRAD_BF16, FWD, false>(a, tile, wave, nwaves, lane, sent_lds, send_lds);
 }
 
 // =============================================================================================

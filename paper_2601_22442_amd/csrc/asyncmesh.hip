@@ -118,7 +118,7 @@ struct am_state {
     Layout lay;
     hipStream_t stream;
     int device;
-    uint32_t grid_step, grid_sparse;
+    uint32_t grid_sparse;
     float *w[AM_MAX_REPLICAS], *m[AM_MAX_REPLICAS], *v[AM_MAX_REPLICAS], *d[AM_MAX_REPLICAS];
     void *fwd[AM_MAX_REPLICAS];
     bool has_fwd;
@@ -191,10 +191,13 @@ Round plan_round(const am_state *st, uint64_t t)
 template <int OPT, bool GBF>
 am_status launch_step_fwd(am_state *st, const am::StepArgs &a)
 {
-    const dim3 grid(st->grid_step), block(256);
-    if (!st->has_fwd) am::k_step<OPT, GBF, am::kFwdNone><<<grid, block, 0, st->stream>>>(a);
-    else if (st->cfg.fwd_dtype == AM_F32) am::k_step<OPT, GBF, am::kFwdF32><<<grid, block, 0, st->stream>>>(a);
-    else am::k_step<OPT, GBF, am::kFwdBf16><<<grid, block, 0, st->stream>>>(a);
+    // one workgroup per tile, one wave per replica (at most 16 waves: more replicas take turns)
+    const uint32_t waves = st->cfg.replicas < 16u ? st->cfg.replicas : 16u;
+    const dim3 grid(st->lay.ntiles), block(64u * waves);
+    const size_t lds = (size_t)(st->cfg.replicas + waves) * am::kTileCoords * sizeof(float);
+    if (!st->has_fwd) am::k_step<OPT, GBF, am::kFwdNone><<<grid, block, lds, st->stream>>>(a);
+    else if (st->cfg.fwd_dtype == AM_F32) am::k_step<OPT, GBF, am::kFwdF32><<<grid, block, lds, st->stream>>>(a);
+    else am::k_step<OPT, GBF, am::kFwdBf16><<<grid, block, lds, st->stream>>>(a);
     AM_HIP(hipGetLastError());
     return AM_OK;
 }
@@ -273,11 +276,9 @@ am_status am_init_state(const am_config *cfg, const am_buffers *buf, void *hip_s
     int cus = 256;
     if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, st->device);
     if (e != hipSuccess) { delete st; return fail(AM_EHIP, "device query: %s", hipGetErrorString(e)); }
-    // fused step: one workgroup per 4 tiles; the other kernels stride over the tiles with a fixed
-    // number of workgroups per compute unit
+    // the stand-alone kernels stride over the tiles with a fixed number of workgroups per compute unit
     const uint32_t tile_groups = (lay.ntiles + 3) / 4;
     const uint32_t want = (uint32_t)cus * 8u;
-    st->grid_step = tile_groups;
     st->grid_sparse = tile_groups < want ? tile_groups : want;
 
     // d^0 = 0 and zero moments; clear flags, offsets and ring
