@@ -121,9 +121,10 @@ def main():
     pool_n = 1 << 20
     w_pool = torch.from_numpy(si.stage_weights(pool_n, 0)).to(dev)
     st = am.init_state(cfg, tiled_on_device(torch, w_pool, n, 0))
-    # two gradient sets per replica, cycled (traffic per step is unchanged)
+    # two gradient sets per replica, cycled (traffic per step is unchanged); one set where two do not fit
     gsets = []
-    for s in range(2):
+    nsets = 1 if n * R * 4 > 24e9 else 2
+    for s in range(nsets):
         pools = si.replica_grads(pool_n, R, s + 1, 0)
         gs = []
         for i in range(R):
@@ -136,14 +137,14 @@ def main():
     t = 0
     for _ in range(warm):
         t += 1
-        st.step(t, gsets[t & 1], 3e-4, 0.5)
+        st.step(t, gsets[t % nsets], 3e-4, 0.5)
     torch.cuda.synchronize()
 
     st.set_profiling(True)
     t0 = time.perf_counter()
     for _ in range(args.steps):
         t += 1
-        st.step(t, gsets[t & 1], 3e-4, 0.5)
+        st.step(t, gsets[t % nsets], 3e-4, 0.5)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     kernel_ms, launches = st.get_profile()

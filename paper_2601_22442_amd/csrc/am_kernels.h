@@ -250,7 +250,9 @@ __device__ __forceinline__ void step_replica(const StepArgs &a, uint32_t i, uint
         wave_lds_sync();
     }
 
-    F4 w_new = w_hat;
+    F4 w_new;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) w_new.v[j] = w_hat.v[j];
     if (s.mask_recv) {                                     // receive: old average (+ EMA of staleness)
         uint32_t c = s.rank_recv;
 #pragma unroll
@@ -285,7 +287,7 @@ __device__ __forceinline__ void step_replica(const StepArgs &a, uint32_t i, uint
 }
 
 // One workgroup per tile of 256 coordinates; its waves are the replicas (wave w takes replicas
-// w, w + W, ...; W = min(R, 16) waves), one lane per group of 4 coordinates.  Each wave streams
+// w, w + W, ...; W = min(R, 8) waves), one lane per group of 4 coordinates.  Each wave streams
 // its replica's 1 KB of every array once and retires; measured on MI355X this shape, with
 // non-temporal accesses, is the fastest way through the 4-read / 4-write stream mix of this update.
 // Every wave hashes the tile's two subsets itself (integer work that hides under the memory time);
@@ -401,9 +403,9 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, uint32_t tile, uint
     }
 }
 
-// grid = one workgroup per tile; blockDim = 64 * min(R, 16); dynamic LDS = (R + waves) * 256 floats
+// grid = one workgroup per tile; blockDim = 64 * min(R, 8); dynamic LDS = (R + waves) * 256 floats
 template <int OPT, bool GRAD_BF16, int FWD>
-__global__ void __launch_bounds__(1024)
+__global__ void __launch_bounds__(512)
 k_step(const StepArgs a)
 {
     extern __shared__ float lds[];

@@ -191,8 +191,9 @@ Round plan_round(const am_state *st, uint64_t t)
 template <int OPT, bool GBF>
 am_status launch_step_fwd(am_state *st, const am::StepArgs &a)
 {
-    // one workgroup per tile, one wave per replica (at most 16 waves: more replicas take turns)
-    const uint32_t waves = st->cfg.replicas < 16u ? st->cfg.replicas : 16u;
+    // one workgroup per tile, one wave per replica (at most 8 waves, so that several workgroups fit
+    // a compute unit; with more replicas the waves take turns)
+    const uint32_t waves = st->cfg.replicas < 8u ? st->cfg.replicas : 8u;
     const dim3 grid(st->lay.ntiles), block(64u * waves);
     const size_t lds = (size_t)(st->cfg.replicas + waves) * am::kTileCoords * sizeof(float);
     if (!st->has_fwd) am::k_step<OPT, GBF, am::kFwdNone><<<grid, block, lds, st->stream>>>(a);
