@@ -13,6 +13,32 @@ namespace am {
 // number rounded up to whole 128-byte lines of 32 floats (unit = 32: ring slots, where every tile
 // owns whole lines).  Writes, per tile, the summed size of the tiles of the same superblock before
 // it (local_off) and, per superblock, its total (sb_sum).
+// cnt[512] (LDS) holds the sizes of the tiles of superblock blockIdx.x: write their exclusive
+// prefix to local_off and their total to sb_sum.  Called by all 256 threads after a barrier.
+__device__ __forceinline__ void scan_superblock(const uint32_t *cnt, uint32_t *wave_tot, uint32_t ntiles,
+                                                uint32_t *__restrict__ local_off, uint32_t *__restrict__ sb_sum)
+{
+    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    const uint32_t tile0 = blockIdx.x * kTilesPerSuperblock;
+    // thread j owns entries 2j, 2j+1
+    const uint32_t a = cnt[2 * threadIdx.x], b = cnt[2 * threadIdx.x + 1];
+    uint32_t incl = a + b;                       // inclusive scan across the wave, by shuffles
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t up = __shfl_up(incl, off);
+        if ((int)lane >= off) incl += up;
+    }
+    if (lane == 63) wave_tot[wave] = incl;
+    __syncthreads();
+    uint32_t base = 0;
+    for (uint32_t w = 0; w < wave; ++w) base += wave_tot[w];
+    const uint32_t excl = base + incl - (a + b);
+    const uint32_t t_a = tile0 + 2 * threadIdx.x;
+    if (t_a < ntiles) local_off[t_a] = excl;
+    if (t_a + 1 < ntiles) local_off[t_a + 1] = excl + a;
+    if (threadIdx.x == 255) sb_sum[blockIdx.x] = base + incl;
+}
+
 __global__ void __launch_bounds__(256)
 k_subset_count(SubsetKey key, uint64_t n, uint32_t ntiles, uint32_t unit,
                uint32_t *__restrict__ local_off, uint32_t *__restrict__ sb_sum)
@@ -35,24 +61,22 @@ k_subset_count(SubsetKey key, uint64_t n, uint32_t ntiles, uint32_t unit,
         if (lane == 0) cnt[k] = (total + unit - 1u) / unit;
     }
     __syncthreads();
+    scan_superblock(cnt, wave_tot, ntiles, local_off, sb_sum);
+}
 
-    // exclusive scan of the 512 counts: thread j owns entries 2j, 2j+1
-    const uint32_t a = cnt[2 * threadIdx.x], b = cnt[2 * threadIdx.x + 1];
-    uint32_t incl = a + b;                       // inclusive scan across the wave, by shuffles
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const uint32_t up = __shfl_up(incl, off);
-        if ((int)lane >= off) incl += up;
-    }
-    if (lane == 63) wave_tot[wave] = incl;
+// Same, from tile sizes that are already in memory (the fused step kernel leaves the line counts
+// of the next step's subset there, so that step needs no hashing pass of its own).
+__global__ void __launch_bounds__(256)
+k_subset_offsets(const uint32_t *__restrict__ tile_size, uint32_t ntiles,
+                 uint32_t *__restrict__ local_off, uint32_t *__restrict__ sb_sum)
+{
+    __shared__ uint32_t cnt[kTilesPerSuperblock];
+    __shared__ uint32_t wave_tot[4];
+    const uint32_t tile0 = blockIdx.x * kTilesPerSuperblock;
+    for (uint32_t k = threadIdx.x; k < kTilesPerSuperblock; k += 256u)
+        cnt[k] = tile0 + k < ntiles ? tile_size[tile0 + k] : 0u;
     __syncthreads();
-    uint32_t base = 0;
-    for (uint32_t w = 0; w < wave; ++w) base += wave_tot[w];
-    const uint32_t excl = base + incl - (a + b);
-    const uint32_t t_a = tile0 + 2 * threadIdx.x;
-    if (t_a < ntiles) local_off[t_a] = excl;
-    if (t_a + 1 < ntiles) local_off[t_a + 1] = excl + a;
-    if (threadIdx.x == 255) sb_sum[blockIdx.x] = base + incl;
+    scan_superblock(cnt, wave_tot, ntiles, local_off, sb_sum);
 }
 
 // Single workgroup: exclusive scan of the superblock totals, in place (sb[i] <- sum of sb[<i]),
@@ -122,7 +146,9 @@ struct StepArgs {
     uint32_t replicas;
     // averaging
     uint32_t do_send, do_recv, ema, same_slot;     // same_slot: tau = 0, the average is of this step's w^
-    SubsetKey key_send, key_recv;
+    uint32_t do_next;                              // also count the lines each tile will send next step
+    SubsetKey key_send, key_recv, key_next;
+    uint32_t *next_lines;                          // [ntiles], written when do_next
     float *ring_send;                              // slot written now: [replica][line][32]
     const float *ring_recv;                        // slot sent tau rounds ago
     const uint32_t *send_local_off, *send_sb_base; // first line of each tile = sb_base[tile >> 9] + local_off[tile]
@@ -354,6 +380,12 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, uint32_t tile, uint
         s.line_recv = a.ema && (((any >> (lane & ~7u)) & 0xFFull) != 0ull);
     }
     if (have_first && s.line_recv) in.d = load_f32x4(a.d[wave], mu, nvalid);
+
+    if (a.do_next && wave == 0) {                           // one wave per tile sizes the next step's send
+        uint32_t count;
+        (void)wave_prefix_mask4(member_mask(a.key_next, group, nvalid), count);
+        if (lane == 0) a.next_lines[tile] = (count + kLineFloats - 1u) / kLineFloats;
+    }
 
     if (s.lines_send) {                                     // zero the gather area once: line tails stay zero
         for (uint32_t r = lane; r < s.lines_send * kLineFloats; r += 64u) send_lds[r] = 0.f;

@@ -70,10 +70,10 @@ uint64_t slot_capacity_lines(uint64_t ntiles, double p)
 struct Layout {
     uint32_t ntiles, nsb, slots;
     uint64_t cap_lines;
-    uint64_t off_flags, off_meta, meta_stride, meta_sb_off, off_ring, ring_stride, total;
+    uint64_t off_flags, off_next, off_meta, meta_stride, meta_sb_off, off_ring, ring_stride, total;
 };
 
-// workspace = [flags 256 B][meta x (slots + 1)][ring values x slots]
+// workspace = [flags 256 B][next_lines u32[ntiles]][meta x (slots + 1)][ring values x slots]
 //   meta    = local_off u32[ntiles] | sb_base u32[nsb + 1]         (the extra one serves am_subset_indices)
 //   ring    = R * cap_lines * 32 fp32: [replica][line][32]; a tile owns whole lines
 Layout make_layout(const am_config &c)
@@ -84,7 +84,8 @@ Layout make_layout(const am_config &c)
     L.slots = c.delay + 1;
     L.cap_lines = slot_capacity_lines(L.ntiles, c.fraction);
     L.off_flags = 0;
-    L.off_meta = 256;
+    L.off_next = 256;
+    L.off_meta = L.off_next + round_up((uint64_t)L.ntiles * 4, 256);
     L.meta_sb_off = round_up((uint64_t)L.ntiles * 4, 256);
     L.meta_stride = L.meta_sb_off + round_up(((uint64_t)L.nsb + 1) * 4, 256);
     L.off_ring = L.off_meta + L.meta_stride * (L.slots + 1);
@@ -124,6 +125,7 @@ struct am_state {
     bool has_fwd;
     char *ws;
     uint64_t last_t;
+    uint64_t next_lines_step;    // the step whose send subset next_lines() was sized for (0 = none)
     double mu_product;           // NAdam: running product of the momentum schedule
     uint64_t threshold;
     // profiling of the fused kernel
@@ -132,6 +134,7 @@ struct am_state {
     size_t ev_used;
 
     uint32_t *flags() const { return reinterpret_cast<uint32_t *>(ws + lay.off_flags); }
+    uint32_t *next_lines() const { return reinterpret_cast<uint32_t *>(ws + lay.off_next); }
     uint32_t *meta_local(uint32_t slot) const { return reinterpret_cast<uint32_t *>(ws + lay.off_meta + lay.meta_stride * slot); }
     uint32_t *meta_sb(uint32_t slot) const { return reinterpret_cast<uint32_t *>(ws + lay.off_meta + lay.meta_stride * slot + lay.meta_sb_off); }
     float *ring(uint32_t slot) const { return reinterpret_cast<float *>(ws + lay.off_ring + lay.ring_stride * slot); }
@@ -155,9 +158,14 @@ am::SubsetKey make_key(const am_state *st, uint64_t step)
 am_status launch_subset_offsets(am_state *st, uint64_t step, uint32_t slot, uint64_t *dev_count, bool for_ring)
 {
     const Layout &L = st->lay;
-    am::k_subset_count<<<L.nsb, 256, 0, st->stream>>>(make_key(st, step), st->cfg.n, L.ntiles,
-                                                      for_ring ? am::kLineFloats : 1u,
-                                                      st->meta_local(slot), st->meta_sb(slot));
+    if (for_ring && st->next_lines_step == step && step != 0) {
+        // the previous fused step already sized this subset's tiles
+        am::k_subset_offsets<<<L.nsb, 256, 0, st->stream>>>(st->next_lines(), L.ntiles, st->meta_local(slot), st->meta_sb(slot));
+    } else {
+        am::k_subset_count<<<L.nsb, 256, 0, st->stream>>>(make_key(st, step), st->cfg.n, L.ntiles,
+                                                          for_ring ? am::kLineFloats : 1u,
+                                                          st->meta_local(slot), st->meta_sb(slot));
+    }
     AM_HIP(hipGetLastError());
     am::k_subset_scan<<<1, 256, 0, st->stream>>>(st->meta_sb(slot), L.nsb, (uint32_t)L.cap_lines,
                                                  for_ring ? st->flags() : nullptr, dev_count);
@@ -261,6 +269,7 @@ am_status am_init_state(const am_config *cfg, const am_buffers *buf, void *hip_s
     st->has_fwd = buf->fwd != nullptr;
     st->ws = static_cast<char *>(buf->workspace);
     st->last_t = 0;
+    st->next_lines_step = 0;
     st->mu_product = 1.0;
     st->threshold = subset_threshold(cfg->fraction);
     st->profiling = false;
@@ -361,6 +370,13 @@ am_status am_step(am_state *st, uint64_t t, const void *const *grads, float lr, 
         a.recv_sb_base = st->meta_sb(r.slot_recv);
     }
 
+    const bool do_next = (t + 1) % c.avg_interval == 0;      // the next step sends: size its tiles on the way
+    a.do_next = do_next;
+    if (do_next) {
+        a.key_next = make_key(st, t + 1);
+        a.next_lines = st->next_lines();
+    }
+
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
     if (st->profiling) {
         while (st->ev_pool.size() < st->ev_used + 2) {
@@ -381,6 +397,7 @@ am_status am_step(am_state *st, uint64_t t, const void *const *grads, float lr, 
         st->ev_used += 2;
     }
     st->last_t = t;
+    if (do_next) st->next_lines_step = t + 1;
     st->mu_product = mu_prod_next;
     return AM_OK;
 }

@@ -274,6 +274,22 @@ def test_sparse_average_alone(amlib, n, R, tau, K, p, corr):
     assert st.read_flags() == 0
 
 
+def test_fused_steps_and_stand_alone_averaging_interleaved(amlib):
+    """am_step and am_sparse_average share the ring, the step counter and the subset offsets."""
+    n, R, tau = 70_003, 4, 1
+    st, orc = make_pair(amlib, n, R, delay=tau, fraction=0.1, seed=23)
+    for t in range(1, 10):
+        if t % 3 == 0:
+            st.sparse_average(t, 0.5); orc.sparse_average(t, 0.5)
+        else:
+            g, gd = grads_for(n, R, t, 23, False)
+            st.step(t, gd, 1e-3, 0.5); orc.step(t, g, 1e-3, 0.5)
+        for i in range(R):
+            assert rel_err(st.w[i].cpu().numpy(), orc.w(i)) < TOL_F32, (t, i)
+            assert rel_err(st.d[i].cpu().numpy(), orc.d(i)) < TOL_F32, (t, i)
+    assert st.read_flags() == 0
+
+
 @pytest.mark.parametrize("n", [1, 5, 1000, 1_000_003])
 @pytest.mark.parametrize("bf16", [False, True])
 def test_lookahead_alone(amlib, n, bf16):
