@@ -131,7 +131,7 @@ k_subset_write(SubsetKey key, uint64_t n, uint32_t ntiles, const uint32_t *__res
 // =============================================================================================
 // Fused step kernel
 // =============================================================================================
-enum : int { kOptSgdPlain = 0, kOptSgdMomentum = 1, kOptAdam = 2 };
+enum : int { kOptSgdPlain = 0, kOptSgdMomentum = 1, kOptAdam = 2, kOptNone = 3 };   // kOptNone: w^ = w (averaging only)
 enum : int { kFwdNone = 0, kFwdF32 = 1, kFwdBf16 = 2 };
 
 struct StepArgs {
@@ -203,6 +203,10 @@ __device__ __forceinline__ void local_step(const StepArgs &a, const GroupIn &in,
 {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
+        if (OPT == kOptNone) {                                 // averaging only: the caller's w is w^
+            w_hat.v[j] = in.w.v[j];
+            continue;
+        }
         const double gj = (double)in.g.v[j];                   // grad_scale is folded into b_m, b_v, c_g
         const double wo = (double)in.w.v[j];
         double step;                                           // what is subtracted besides the decay
@@ -237,20 +241,28 @@ struct GroupSubsets {
     uint32_t count_recv;                // received coordinates of the tile
     uint64_t run_send, run_recv;        // float offset, inside one replica's part of the slot, of the tile's lines
     uint32_t lines_send;                // whole lines the tile sends per replica
-    bool line_recv;                     // the 128-byte line of d holding the group receives something
+    bool line_recv;                     // the 128-byte line (of w, of d) holding the group receives something
 };
 
-// Issues the loads of replica i's operands for one group.
+// Issues the loads of replica i's dense operands for one group.
 template <int OPT, bool GRAD_BF16>
-__device__ __forceinline__ void load_group(const StepArgs &a, uint32_t i, uint64_t mu, int nvalid,
-                                           bool with_d, GroupIn &in)
+__device__ __forceinline__ void load_group(const StepArgs &a, uint32_t i, uint64_t mu, int nvalid, GroupIn &in)
 {
     in.w = load_f32x4(a.w[i], mu, nvalid);
     in.g = GRAD_BF16 ? load_bf16x4(static_cast<const uint16_t *>(a.g[i]), mu, nvalid)
                      : load_f32x4(static_cast<const float *>(a.g[i]), mu, nvalid);
     if (OPT != kOptSgdPlain) in.m = load_f32x4(a.m[i], mu, nvalid);
     if (OPT == kOptAdam) in.v = load_f32x4(a.v[i], mu, nvalid);
-    if (with_d) in.d = load_f32x4(a.d[i], mu, nvalid);
+}
+
+// What the averaging alone touches: the EMA entries of a line that receives, and (when there is no
+// optimizer pass that reads w anyway) the weights of a group that sends or whose line receives.
+template <int OPT>
+__device__ __forceinline__ void load_group_sparse(const StepArgs &a, uint32_t i, uint64_t mu, int nvalid,
+                                                  const GroupSubsets &s, GroupIn &in)
+{
+    if (a.ema && s.line_recv) in.d = load_f32x4(a.d[i], mu, nvalid);
+    if (OPT == kOptNone && (s.mask_send != 0u || s.line_recv)) in.w = load_f32x4(a.w[i], mu, nvalid);
 }
 
 // Replica i of one group, from loaded operands to stored results.  sent_lds: what replica i sent
@@ -295,10 +307,14 @@ __device__ __forceinline__ void step_replica(const StepArgs &a, uint32_t i, uint
                 ++c;
             }
     }
-    if (s.line_recv) store_f32x4(a.d[i], mu, nvalid, in.d);
+    if (a.ema && s.line_recv) store_f32x4(a.d[i], mu, nvalid, in.d);
 
+    if (OPT == kOptNone) {                                 // averaging only: rewrite just the lines that receive
+        if (s.line_recv) store_f32x4(a.w[i], mu, nvalid, w_new);
+        return;
+    }
     store_f32x4(a.w[i], mu, nvalid, w_new);
-    if (OPT != kOptSgdPlain) store_f32x4(a.m[i], mu, nvalid, m_new);
+    if (OPT == kOptSgdMomentum || OPT == kOptAdam) store_f32x4(a.m[i], mu, nvalid, m_new);
     if (OPT == kOptAdam) store_f32x4(a.v[i], mu, nvalid, v_new);
     if (FWD != kFwdNone) {
         F4 f = w_new;
@@ -344,8 +360,7 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, uint32_t tile, uint
 
     // first replica's dense operands go out before anything else waits on memory
     GroupIn in;
-    const bool have_first = wave < R;
-    if (have_first) load_group<OPT, GRAD_BF16>(a, wave, mu, nvalid, false, in);
+    if (OPT != kOptNone) load_group<OPT, GRAD_BF16>(a, wave, mu, nvalid, in);
 
     // ---- subsets: which of my 4 coordinates are sent now / received now, and where the tile's
     //      lines start.  A tile whose lines would pass the slot capacity is left out, at send and at
@@ -377,9 +392,9 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, uint32_t tile, uint
     }
     {
         const uint64_t any = __ballot(s.mask_recv != 0u);
-        s.line_recv = a.ema && (((any >> (lane & ~7u)) & 0xFFull) != 0ull);
+        s.line_recv = ((any >> (lane & ~7u)) & 0xFFull) != 0ull;
     }
-    if (have_first && s.line_recv) in.d = load_f32x4(a.d[wave], mu, nvalid);
+    load_group_sparse<OPT>(a, wave, mu, nvalid, s, in);
 
     if (a.do_next && wave == 0) {                           // one wave per tile sizes the next step's send
         uint32_t count;
@@ -401,7 +416,12 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, uint32_t tile, uint
                 if (s.count_recv) {
                     GroupIn pre;
                     F4 w_hat, m_new, v_new;
-                    if (i == wave) pre = in; else load_group<OPT, GRAD_BF16>(a, i, mu, nvalid, false, pre);
+                    if (i == wave) {
+                        pre = in;
+                    } else {
+                        if (OPT != kOptNone) load_group<OPT, GRAD_BF16>(a, i, mu, nvalid, pre);
+                        load_group_sparse<OPT>(a, i, mu, nvalid, s, pre);
+                    }
                     local_step<OPT>(a, pre, w_hat, m_new, v_new);
                     uint32_t c = s.rank_recv;
 #pragma unroll
@@ -430,7 +450,10 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, uint32_t tile, uint
 
     // ---- my replicas
     for (uint32_t i = wave; i < R; i += nwaves) {
-        if (i != wave) load_group<OPT, GRAD_BF16>(a, i, mu, nvalid, s.line_recv, in);
+        if (i != wave) {
+            if (OPT != kOptNone) load_group<OPT, GRAD_BF16>(a, i, mu, nvalid, in);
+            load_group_sparse<OPT>(a, i, mu, nvalid, s, in);
+        }
         step_replica<OPT, FWD>(a, i, mu, nvalid, lane, s, abar, in, sent_lds + i * kTileCoords, send_lds);
     }
 }
@@ -451,126 +474,6 @@ k_step(const StepArgs a)
         step_tile<OPT, GRAD_BF16, FWD, true>(a, tile, wave, nwaves, lane, sent_lds, send_lds);
     else
         step_tile<OPT, GRAD_BF16, FWD, false>(a, tile, wave, nwaves, lane, sent_lds, send_lds);
-}
-
-// =============================================================================================
-// Stand-alone sparse averaging (am_sparse_average): gather / average / scatter on the current w
-// =============================================================================================
-// One workgroup handles 4 tiles at a time, one per wave.  Each wave hashes its tile and compacts the
-// selected coordinates into an ascending index list in LDS.
-//   send:    the wave walks its lines of the slot ([replica][line][32]) with consecutive lanes on
-//            consecutive floats, gathering w_i[mu] for the list entries and zero for the tail of the
-//            last line, so that whole lines are written;
-//   receive: lanes are laid out as (coordinate, replica), lane = c * L + i with L = the power of
-//            two >= R, the replica mean is a butterfly over L neighbouring lanes, and each lane
-//            updates its own (coordinate, replica) entry of d and w.
-struct SparseArgs {
-    float *w[kMaxReplicas];
-    float *d[kMaxReplicas];
-    uint64_t n;
-    uint32_t ntiles;
-    uint32_t replicas;
-    uint32_t lanes_per_coord;                      // L
-    uint32_t do_send, do_recv, ema;
-    SubsetKey key_send, key_recv;
-    float *ring_send;
-    const float *ring_recv;
-    const uint32_t *send_local_off, *send_sb_base;
-    const uint32_t *recv_local_off, *recv_sb_base;
-    uint32_t cap_lines;
-    double lambda, one_minus_lambda;
-};
-
-// Hash the wave's tile and leave the ascending list of selected local coordinates (0..255) in idx.
-__device__ __forceinline__ uint32_t stage_tile_indices(const SubsetKey &key, uint64_t n, uint32_t tile,
-                                                       uint32_t lane, uint16_t *idx)
-{
-    const uint64_t group = (uint64_t)tile * 64u + lane;
-    const uint64_t mu = group * 4u;
-    const int nvalid = mu >= n ? 0 : (n - mu >= 4u ? 4 : (int)(n - mu));
-    const uint32_t mask = member_mask(key, group, nvalid);
-    uint32_t total;
-    uint32_t p = wave_prefix_mask4(mask, total);
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-        if ((mask >> j) & 1u) idx[p++] = (uint16_t)(lane * 4u + j);
-    return total;
-}
-
-__global__ void __launch_bounds__(256)
-k_sparse(const SparseArgs a)
-{
-    __shared__ uint16_t idx_lds[4][kTileCoords];
-    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
-    uint16_t *idx = idx_lds[wave];
-    const uint32_t R = a.replicas, L = a.lanes_per_coord;
-    const uint32_t coords_per_pass = 64u / L;
-    const uint32_t c_in_pass = lane / L, i = lane % L;
-    const bool lane_has_replica = i < R;
-    const double inv_r = 1.0 / (double)R;
-    const uint64_t slot_floats = (uint64_t)a.cap_lines * kLineFloats;
-    const uint32_t ngroups_of_tiles = (a.ntiles + 3u) / 4u;
-
-    for (uint32_t tg = blockIdx.x; tg < ngroups_of_tiles; tg += gridDim.x) {   // uniform per workgroup
-        const uint32_t tile = tg * 4u + wave;
-        const bool live = tile < a.ntiles;
-
-        // ---------------- send: ring[slot(t)][i][lines of the tile] <- w_i[mu] for mu in S^t
-        if (a.do_send) {
-            uint32_t count = 0;
-            if (live) count = stage_tile_indices(a.key_send, a.n, tile, lane, idx);
-            __syncthreads();
-            if (live) {
-                const uint32_t first = a.send_sb_base[tile / kTilesPerSuperblock] + a.send_local_off[tile];
-                const uint32_t run = (count + kLineFloats - 1u) / kLineFloats * kLineFloats;   // floats per replica
-                if ((uint64_t)first + run / kLineFloats <= a.cap_lines) {
-                    for (uint32_t e = lane; e < run * R; e += 64u) {
-                        const uint32_t r = e % run, rep = e / run;
-                        const float val = r < count ? a.w[rep][(uint64_t)tile * kTileCoords + idx[r]] : 0.f;
-                        a.ring_send[(uint64_t)rep * slot_floats + (uint64_t)first * kLineFloats + r] = val;
-                    }
-                }
-            }
-            __threadfence_block();          // tau = 0: the receive below reads what was just written
-            __syncthreads();
-        }
-
-        // ---------------- receive: mean of ring[slot(t - tau K)], EMA, scatter
-        if (a.do_recv) {
-            uint32_t count = 0;
-            if (live) count = stage_tile_indices(a.key_recv, a.n, tile, lane, idx);
-            __syncthreads();
-            if (live) {
-                const uint32_t first = a.recv_sb_base[tile / kTilesPerSuperblock] + a.recv_local_off[tile];
-                const uint32_t lines = (count + kLineFloats - 1u) / kLineFloats;
-                if ((uint64_t)first + lines > a.cap_lines) count = 0;                 // tile was left out at send
-                const float *__restrict__ src = a.ring_recv + (uint64_t)first * kLineFloats;
-                for (uint32_t c0 = 0; c0 < count; c0 += coords_per_pass) {      // uniform per wave
-                    const uint32_t c = c0 + c_in_pass;
-                    const bool on = c < count && lane_has_replica;
-                    float sent = 0.f;
-                    if (on) sent = src[(uint64_t)i * slot_floats + c];
-                    double sum = (double)sent;
-                    for (uint32_t off = 1; off < L; off <<= 1) sum += __shfl_xor(sum, (int)off);
-                    if (on) {
-                        const float abar = (float)(sum * inv_r);
-                        const uint64_t mu = (uint64_t)tile * kTileCoords + idx[c];
-                        float w_new = abar;
-                        if (a.ema) {
-                            const float w_hat = a.w[i][mu];
-                            float *__restrict__ dp = a.d[i] + mu;
-                            const float dn = (float)fma(a.one_minus_lambda, (double)*dp,
-                                                        a.lambda * ((double)w_hat - (double)sent));
-                            *dp = dn;
-                            w_new = (float)((double)abar + (double)dn);
-                        }
-                        a.w[i][mu] = w_new;
-                    }
-                }
-            }
-            __syncthreads();
-        }
-    }
 }
 
 // =============================================================================================

@@ -217,6 +217,31 @@ am_status launch_step_grad(am_state *st, const am::StepArgs &a)
     return st->cfg.grad_dtype == AM_BF16 ? launch_step_fwd<OPT, true>(st, a) : launch_step_fwd<OPT, false>(st, a);
 }
 
+// The averaging part of the kernel arguments for step t; launches the offsets pass when t sends.
+am_status fill_averaging(am_state *st, uint64_t t, float lambda_t, const Round &r, am::StepArgs &a)
+{
+    const am_config &c = st->cfg;
+    a.n = c.n; a.ntiles = st->lay.ntiles; a.replicas = c.replicas;
+    a.cap_lines = (uint32_t)st->lay.cap_lines;
+    a.lambda = (double)lambda_t; a.one_minus_lambda = 1.0 - (double)lambda_t;
+    a.ema = c.correction == AM_CORR_EMA;
+    a.do_send = r.send; a.do_recv = r.recv; a.same_slot = r.same_slot;
+    if (r.send) {
+        if (am_status s = launch_subset_offsets(st, t, r.slot_send, nullptr, true)) return s;
+        a.key_send = make_key(st, t);
+        a.ring_send = st->ring(r.slot_send);
+        a.send_local_off = st->meta_local(r.slot_send);
+        a.send_sb_base = st->meta_sb(r.slot_send);
+    }
+    if (r.recv) {
+        a.key_recv = make_key(st, r.step_recv);
+        a.ring_recv = st->ring(r.slot_recv);
+        a.recv_local_off = st->meta_local(r.slot_recv);
+        a.recv_sb_base = st->meta_sb(r.slot_recv);
+    }
+    return AM_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -324,10 +349,6 @@ am_status am_step(am_state *st, uint64_t t, const void *const *grads, float lr, 
         a.w[i] = st->w[i]; a.m[i] = st->m[i]; a.v[i] = st->v[i]; a.d[i] = st->d[i];
         a.fwd[i] = st->fwd[i]; a.g[i] = grads[i];
     }
-    a.n = c.n; a.ntiles = st->lay.ntiles; a.replicas = c.replicas;
-    a.cap_lines = (uint32_t)st->lay.cap_lines;
-    a.lambda = (double)lambda_t; a.one_minus_lambda = 1.0 - (double)lambda_t;
-    a.ema = c.correction == AM_CORR_EMA;
     a.lookahead = c.lookahead != 0; a.gamma = (double)c.gamma;
     const double gs = (double)grad_scale;        // folded into the coefficients that multiply g
 
@@ -355,20 +376,7 @@ am_status am_step(am_state *st, uint64_t t, const void *const *grads, float lr, 
     }
 
     const Round r = plan_round(st, t);
-    a.do_send = r.send; a.do_recv = r.recv; a.same_slot = r.same_slot;
-    if (r.send) {
-        if (am_status s = launch_subset_offsets(st, t, r.slot_send, nullptr, true)) return s;
-        a.key_send = make_key(st, t);
-        a.ring_send = st->ring(r.slot_send);
-        a.send_local_off = st->meta_local(r.slot_send);
-        a.send_sb_base = st->meta_sb(r.slot_send);
-    }
-    if (r.recv) {
-        a.key_recv = make_key(st, r.step_recv);
-        a.ring_recv = st->ring(r.slot_recv);
-        a.recv_local_off = st->meta_local(r.slot_recv);
-        a.recv_sb_base = st->meta_sb(r.slot_recv);
-    }
+    if (am_status s = fill_averaging(st, t, lambda_t, r, a)) return s;
 
     const bool do_next = (t + 1) % c.avg_interval == 0;      // the next step sends: size its tiles on the way
     a.do_next = do_next;
@@ -407,31 +415,17 @@ am_status am_sparse_average(am_state *st, uint64_t t, float lambda_t)
     if (!st) return fail(AM_EINVAL, "state is NULL");
     if (t != st->last_t + 1) return fail(AM_EORDER, "step %llu after step %llu", (unsigned long long)t, (unsigned long long)st->last_t);
     if (!(lambda_t >= 0.f && lambda_t <= 1.f)) return fail(AM_EINVAL, "lambda_t=%g not in [0, 1]", lambda_t);
-    const am_config &c = st->cfg;
     const Round r = plan_round(st, t);
     if (r.send) {
-        am::SparseArgs a;
+        // the fused kernel with the optimizer pass left out: w^ = w, only touched lines move
+        am::StepArgs a;
         std::memset(&a, 0, sizeof a);
-        for (uint32_t i = 0; i < c.replicas; ++i) { a.w[i] = st->w[i]; a.d[i] = st->d[i]; }
-        a.n = c.n; a.ntiles = st->lay.ntiles; a.replicas = c.replicas;
-        uint32_t L = 1;
-        while (L < c.replicas) L <<= 1;
-        a.lanes_per_coord = L;
-        a.do_send = 1; a.do_recv = r.recv; a.ema = c.correction == AM_CORR_EMA;
-        a.cap_lines = (uint32_t)st->lay.cap_lines;
-        a.lambda = (double)lambda_t; a.one_minus_lambda = 1.0 - (double)lambda_t;
-        if (am_status s = launch_subset_offsets(st, t, r.slot_send, nullptr, true)) return s;
-        a.key_send = make_key(st, t);
-        a.ring_send = st->ring(r.slot_send);
-        a.send_local_off = st->meta_local(r.slot_send);
-        a.send_sb_base = st->meta_sb(r.slot_send);
-        if (r.recv) {
-            a.key_recv = make_key(st, r.step_recv);
-            a.ring_recv = st->ring(r.slot_recv);
-            a.recv_local_off = st->meta_local(r.slot_recv);
-            a.recv_sb_base = st->meta_sb(r.slot_recv);
-        }
-        am::k_sparse<<<st->grid_sparse, 256, 0, st->stream>>>(a);
+        for (uint32_t i = 0; i < st->cfg.replicas; ++i) { a.w[i] = st->w[i]; a.d[i] = st->d[i]; }
+        if (am_status s = fill_averaging(st, t, lambda_t, r, a)) return s;
+        // little memory traffic per tile here, so fewer waves share a tile's hashing (measured best: 2)
+        const uint32_t waves = st->cfg.replicas < 2u ? st->cfg.replicas : 2u;
+        const size_t lds = (size_t)(st->cfg.replicas + waves) * am::kTileCoords * sizeof(float);
+        am::k_step<am::kOptNone, false, am::kFwdNone><<<dim3(st->lay.ntiles), dim3(64u * waves), lds, st->stream>>>(a);
         AM_HIP(hipGetLastError());
     }
     st->last_t = t;
