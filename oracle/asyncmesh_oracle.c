@@ -16,7 +16,9 @@
  *                        abar    = (1/R) sum_i w^_i^s[mu]            (old average; async sparse averaging eq.)
  *                        d_i[mu] = (1-lambda) d_i[mu] + lambda (w^_i^t[mu] - w^_i^s[mu])     (EMA equation)
  *                        w_i^t[mu] = abar + d_i[mu]                  (estimated average; corrected update)
- *                      (correction NONE: w_i^t[mu] = abar);  mu not in S^s: w_i^t[mu] = w^_i^t[mu]
+ *                      (correction NONE: w_i^t[mu] = abar;  correction EAGER, the eager-DiLoCo special case
+ *                       named after the estimated-average equations: d_i[mu] = (1/R)(w^_i^t[mu] - w^_i^s[mu]),
+ *                       no memory);  mu not in S^s: w_i^t[mu] = w^_i^t[mu]
  *   4. look-ahead      fwd_i^t = w_i^t + gamma (w^_i^t - w_i^{t-1})  (NAG-style extrapolation of the
  *                                                                    optimizer's last displacement)
  *
@@ -135,7 +137,7 @@ uint16_t amo_double_to_bf16(double x)
 /* state                                                                                       */
 /* ------------------------------------------------------------------------------------------ */
 enum { AMO_OPT_SGD = 0, AMO_OPT_ADAMW = 1, AMO_OPT_NADAMW = 2 };
-enum { AMO_CORR_NONE = 0, AMO_CORR_EMA = 1 };
+enum { AMO_CORR_NONE = 0, AMO_CORR_EMA = 1, AMO_CORR_EAGER = 2 };
 
 typedef struct {
     uint64_t n;            /* coordinates held by this oracle instance                      */
@@ -164,6 +166,7 @@ typedef struct {
     float ***kept;               /* [tau*K+1][R][n] copies of w^ (one per step) */
     uint32_t nkept;
     uint64_t last_t;
+    uint32_t delay_now;          /* the delay in force (<= c.delay, which sizes the buffer) */
     double mu_product;           /* NAdam's running product of momentum coefficients */
 } amo_state;
 
@@ -192,6 +195,7 @@ amo_state *amo_create(const amo_config *c)
     s->kept = (float ***)calloc(s->nkept, sizeof(float **));
     for (uint32_t k = 0; k < s->nkept; ++k) s->kept[k] = alloc_2d(R, c->n);
     s->last_t = 0;
+    s->delay_now = c->delay;
     s->mu_product = 1.0;
     return s;
 }
@@ -297,7 +301,7 @@ static void sparse_average(amo_state *s, uint64_t t, double lambda)
     for (uint32_t i = 0; i < R; ++i) memcpy(now[i], s->what[i], n * sizeof(float));
 
     /* receive: the average that was sent tau rounds (tau*K steps) ago arrives now */
-    const uint64_t lag = (uint64_t)c->delay * K;
+    const uint64_t lag = (uint64_t)s->delay_now * K;
     if (t < lag + 1) return;                          /* nothing was sent that long ago */
     const uint64_t sstep = t - lag;
     float **old = s->kept[sstep % s->nkept];
@@ -310,9 +314,12 @@ static void sparse_average(amo_state *s, uint64_t t, double lambda)
         for (uint32_t i = 0; i < R; ++i) sum += (double)old[i][k];
         const float abar = (float)(sum / (double)R);              /* old average, an fp32 message */
         for (uint32_t i = 0; i < R; ++i) {
-            if (c->correction == AMO_CORR_EMA) {
+            if (c->correction == AMO_CORR_EMA || c->correction == AMO_CORR_EAGER) {
                 const double staleness = (double)s->what[i][k] - (double)old[i][k];
-                s->d[i][k] = (float)((1.0 - lambda) * (double)s->d[i][k] + lambda * staleness);
+                if (c->correction == AMO_CORR_EMA)
+                    s->d[i][k] = (float)((1.0 - lambda) * (double)s->d[i][k] + lambda * staleness);
+                else
+                    s->d[i][k] = (float)(staleness / (double)R);
                 s->w[i][k] = (float)((double)abar + (double)s->d[i][k]);
             } else {
                 s->w[i][k] = abar;
@@ -371,6 +378,37 @@ void amo_lookahead(float *out, uint16_t *out_bf16, const float *w, const float *
         if (out) out[k] = (float)f;
         if (out_bf16) out_bf16[k] = amo_double_to_bf16(f);
     }
+}
+
+/* the delay in force from the next step on: 0 <= tau <= the delay the state was created with
+ * (late or early arrival of an average; the buffer keeps enough copies for the largest delay) */
+int amo_set_delay(amo_state *s, uint32_t tau)
+{
+    if (tau > s->c.delay) return -1;
+    s->delay_now = tau;
+    return 0;
+}
+
+/* variance over the replicas of the EMA estimates, (1/R) sum_i (d_i[mu] - mean_i d_i[mu])^2, as its
+ * mean and its maximum over the coordinates (the two curves of the paper's consensus figure) */
+void amo_ema_variance(const amo_state *s, double *mean_out, double *max_out)
+{
+    const uint32_t R = s->c.replicas;
+    double total = 0.0, worst = 0.0;
+    for (uint64_t k = 0; k < s->c.n; ++k) {
+        double mean = 0.0, var = 0.0;
+        for (uint32_t i = 0; i < R; ++i) mean += (double)s->d[i][k];
+        mean /= (double)R;
+        for (uint32_t i = 0; i < R; ++i) {
+            double e = (double)s->d[i][k] - mean;
+            var += e * e;
+        }
+        var /= (double)R;
+        total += var;
+        if (var > worst) worst = var;
+    }
+    *mean_out = s->c.n ? total / (double)s->c.n : 0.0;
+    *max_out = worst;
 }
 
 /* consensus error  sum_i || w_i - mean_i w_i ||^2  (diagnostic used by the invariants) */

@@ -17,7 +17,7 @@ _SRC = _HERE / "asyncmesh_oracle.c"
 _LIB = _HERE / "libasyncmesh_oracle.so"
 
 OPT_SGD, OPT_ADAMW, OPT_NADAMW = 0, 1, 2
-CORR_NONE, CORR_EMA = 0, 1
+CORR_NONE, CORR_EMA, CORR_EAGER = 0, 1, 2
 
 
 def build(force: bool = False) -> Path:
@@ -69,6 +69,8 @@ def lib():
         L.amo_sparse_average.argtypes = [C.c_void_p, C.c_uint64, C.c_double]; L.amo_sparse_average.restype = C.c_int
         L.amo_lookahead.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_double]
         L.amo_consensus_error.argtypes = [C.c_void_p]; L.amo_consensus_error.restype = C.c_double
+        L.amo_set_delay.argtypes = [C.c_void_p, C.c_uint32]; L.amo_set_delay.restype = C.c_int
+        L.amo_ema_variance.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_double)]
         _lib = L
     return _lib
 
@@ -188,6 +190,16 @@ class Oracle:
 
     def consensus_error(self) -> float:
         return float(lib().amo_consensus_error(self._h))
+
+    def ema_variance(self):
+        """(mean, max) over the coordinates of the variance of d_i over the replicas."""
+        a, b = C.c_double(0), C.c_double(0)
+        lib().amo_ema_variance(self._h, C.byref(a), C.byref(b))
+        return float(a.value), float(b.value)
+
+    def set_delay(self, tau: int):
+        if lib().amo_set_delay(self._h, tau) != 0:
+            raise ValueError(f"delay {tau} exceeds the delay the oracle was created with")
 
 
 def threads() -> int:

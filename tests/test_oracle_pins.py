@@ -397,6 +397,71 @@ def test_no_correction_is_plain_delayed_averaging():
         assert not any(np.any(orc.d(i)) for i in range(R))
 
 
+def test_eager_mode_is_fresh_own_plus_stale_others():
+    """Eager-DiLoCo special case (all parameters, d_i = (1/m)(w^_i^t - w^_i^{t-tau})): every replica
+    ends on the average in which its own contribution is fresh and the others' are tau rounds old."""
+    n, R, tau, lr = 700, 4, 2, O.f32(0.125)
+    w0 = si.stage_weights(n, seed=18)
+    orc = O.Oracle(n, R, delay=tau, fraction=1.0, optimizer=O.OPT_SGD, beta1=0.0, weight_decay=0.0,
+                   correction=O.CORR_EAGER)
+    orc.set_w(w0)
+    cur, whats = np.stack([w0] * R), {}
+    for t in range(1, 7):
+        g = np.stack(si.replica_grads(n, R, t, seed=18))
+        what = (cur.astype(np.float64) - lr * g.astype(np.float64)).astype(np.float32)
+        whats[t] = what
+        orc.step(t, list(g), lr)
+        got = np.stack([orc.w(i) for i in range(R)])
+        if t > tau:
+            old = whats[t - tau].astype(np.float64)
+            want = (old.sum(axis=0)[None, :] - old + what.astype(np.float64)) / R
+            assert np.max(np.abs(got - want)) < 2e-8
+        else:
+            assert np.array_equal(got, what)
+        cur = got
+
+
+def test_delay_can_change_at_run_time():
+    """A late average: with the delay lowered from 3 to 1 for one step, that step receives what was
+    sent one round ago; raised back, it receives the three-round-old average again."""
+    n, R, p, seed, lr = 900, 2, 0.5, 31, O.f32(0.125)
+    w0 = si.stage_weights(n, seed=19)
+    orc = O.Oracle(n, R, delay=3, fraction=p, seed=seed, optimizer=O.OPT_SGD, beta1=0.0, weight_decay=0.0,
+                   correction=O.CORR_NONE)
+    orc.set_w(w0)
+    cur, whats = np.stack([w0] * R), {}
+    delays = {1: 3, 2: 3, 3: 3, 4: 3, 5: 1, 6: 3, 7: 0, 8: 2}
+    for t in range(1, 9):
+        orc.set_delay(delays[t])
+        g = np.stack(si.replica_grads(n, R, t, seed=19))
+        what = (cur.astype(np.float64) - lr * g.astype(np.float64)).astype(np.float32)
+        whats[t] = what
+        want = what.copy()
+        s_ = t - delays[t]
+        if s_ >= 1:
+            S = O.subset(seed, s_, n, p).astype(np.int64)
+            want[:, S] = whats[s_][:, S].astype(np.float64).mean(axis=0).astype(np.float32)
+        orc.step(t, list(g), lr)
+        cur = np.stack([orc.w(i) for i in range(R)])
+        assert np.array_equal(cur, want), t
+    with pytest.raises(ValueError):
+        orc.set_delay(4)
+
+
+def test_ema_variance_diagnostic():
+    n, R = 3000, 5
+    orc = O.Oracle(n, R, delay=1, fraction=0.5, seed=2, optimizer=O.OPT_ADAMW)
+    orc.set_w(si.stage_weights(n, seed=20))
+    for t in range(1, 6):
+        orc.step(t, si.replica_grads(n, R, t, seed=20), 1e-3)
+    d = np.stack([orc.d(i) for i in range(R)]).astype(np.float64)
+    var = d.var(axis=0)                                   # population variance over the replicas
+    mean_, max_ = orc.ema_variance()
+    assert abs(mean_ - var.mean()) < 1e-12 * var.mean() + 1e-30 and abs(max_ - var.max()) < 1e-12 * var.max()
+    w = np.stack([orc.w(i) for i in range(R)]).astype(np.float64)
+    assert abs(orc.consensus_error() - np.sum((w - w.mean(axis=0)) ** 2)) < 1e-10 * orc.consensus_error()
+
+
 # --------------------------------------------------------------------------------------------
 # look-ahead
 # --------------------------------------------------------------------------------------------
