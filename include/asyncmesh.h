@@ -60,8 +60,10 @@ typedef enum {
 } am_opt;
 
 typedef enum {
-    AM_CORR_NONE = 0,   /* subset <- old average                 (asynchronous sparse averaging equation) */
-    AM_CORR_EMA  = 1    /* subset <- old average + EMA of staleness   (EMA equation + corrected update)    */
+    AM_CORR_NONE  = 0,  /* subset <- old average                 (asynchronous sparse averaging equation) */
+    AM_CORR_EMA   = 1,  /* subset <- old average + EMA of staleness   (EMA equation + corrected update)    */
+    AM_CORR_EAGER = 2   /* subset <- old average + (1/m)(w^_i^t - w^_i^{t-tau}), no memory: the eager-DiLoCo
+                           special case named at the end of the delay-correction section (with p = 1)      */
 } am_corr;
 
 typedef enum { AM_F32 = 0, AM_BF16 = 1 } am_dtype;
@@ -128,6 +130,17 @@ am_status am_sparse_average(am_state *st, uint64_t t, float lambda_t);
  * out (DEVICE, out_dtype) may alias neither input. */
 am_status am_lookahead(void *out, uint32_t out_dtype, const float *w, const float *w_prev,
                        uint64_t n, float gamma, void *hip_stream);
+
+/* The delay in force from the next step on: 0 <= tau <= the delay of the configuration (which sizes
+ * the ring).  Models an average that arrives late or early (appendix: the asynchronous set-up is
+ * simulated by buffering); a round may then be received twice or never.  Host value, no device work. */
+am_status am_set_delay(am_state *st, uint32_t tau);
+
+/* Diagnostics of the paper's consensus-error figure, enqueued on the stream, results in DEVICE
+ * memory (3 doubles): out[0] = sum_i ||w_i - mean_i w_i||^2 (consensus error, appendix notation),
+ * out[1] = mean and out[2] = max over the coordinates of the variance over the replicas of the EMA
+ * estimates d_i (0 when there is no d).  Deterministic (fixed reduction order). */
+am_status am_diagnostics(am_state *st, double *dev_out3);
 
 /* Materialise S^t in ascending order: dev_out[0 .. count) (DEVICE, uint64, room for `capacity`
  * indices; more are dropped) and *dev_count = |S^t| (DEVICE, one uint64).  Any t >= 0. */

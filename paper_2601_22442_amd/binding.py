@@ -16,12 +16,12 @@ _LIB_PATH = _PKG / "libasyncmesh.so"
 
 MAX_REPLICAS = 32
 OPT_SGD, OPT_ADAMW, OPT_NADAMW = 0, 1, 2
-CORR_NONE, CORR_EMA = 0, 1
+CORR_NONE, CORR_EMA, CORR_EAGER = 0, 1, 2
 F32, BF16 = 0, 1
 
 EXPORTS = (
     "am_workspace_bytes", "am_init_state", "am_step", "am_sparse_average", "am_lookahead",
-    "am_subset_indices", "am_read_flags", "am_set_profiling", "am_get_profile", "am_ring_info",
+    "am_subset_indices", "am_set_delay", "am_diagnostics", "am_read_flags", "am_set_profiling", "am_get_profile", "am_ring_info",
     "am_destroy", "am_last_error", "am_version",
 )
 
@@ -66,6 +66,8 @@ def _load():
     L.am_sparse_average.argtypes = [C.c_void_p, C.c_uint64, C.c_float]
     L.am_lookahead.argtypes = [C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p, C.c_uint64, C.c_float, C.c_void_p]
     L.am_subset_indices.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint64, C.c_void_p]
+    L.am_set_delay.argtypes = [C.c_void_p, C.c_uint32]
+    L.am_diagnostics.argtypes = [C.c_void_p, C.c_void_p]
     L.am_read_flags.argtypes = [C.c_void_p, C.POINTER(C.c_uint32)]
     L.am_set_profiling.argtypes = [C.c_void_p, C.c_int]
     L.am_get_profile.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_uint64)]
@@ -127,7 +129,7 @@ class Stage:
         f32 = dict(dtype=torch.float32, device=self.device)
         need_m = not (cfg.optimizer == OPT_SGD and cfg.beta1 == 0.0)
         need_v = cfg.optimizer != OPT_SGD
-        need_d = cfg.correction == CORR_EMA
+        need_d = cfg.correction != CORR_NONE
         need_fwd = bool(cfg.lookahead) or cfg.fwd_dtype == BF16
         if with_fwd is None:
             with_fwd = need_fwd
@@ -181,6 +183,16 @@ class Stage:
             _check(lib.am_subset_indices(self._handle, t, out.data_ptr(), cap, count.data_ptr()))
         k = int(count.item())
         return out[:min(k, cap)], k
+
+    def set_delay(self, tau: int):
+        _check(lib.am_set_delay(self._handle, tau))
+
+    def diagnostics(self):
+        """(consensus error, mean EMA variance, max EMA variance) as Python floats (synchronises)."""
+        out = torch.zeros(3, dtype=torch.float64, device=self.device)
+        with torch.cuda.device(self.device):
+            _check(lib.am_diagnostics(self._handle, out.data_ptr()))
+        return tuple(float(x) for x in out.cpu())
 
     def read_flags(self) -> int:
         f = C.c_uint32(0)

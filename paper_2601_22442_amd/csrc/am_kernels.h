@@ -145,7 +145,8 @@ struct StepArgs {
     uint32_t ntiles;
     uint32_t replicas;
     // averaging
-    uint32_t do_send, do_recv, ema, same_slot;     // same_slot: tau = 0, the average is of this step's w^
+    uint32_t do_send, do_recv, ema, same_slot;     // ema: a correction vector d is kept; same_slot: tau = 0,
+                                                   // the average is of this step's w^
     uint32_t do_next;                              // also count the lines each tile will send next step
     SubsetKey key_send, key_recv, key_next;
     uint32_t *next_lines;                          // [ntiles], written when do_next
@@ -154,7 +155,7 @@ struct StepArgs {
     const uint32_t *send_local_off, *send_sb_base; // first line of each tile = sb_base[tile >> 9] + local_off[tile]
     const uint32_t *recv_local_off, *recv_sb_base;
     uint32_t cap_lines;                            // lines (of 32 floats) per replica in a ring slot
-    double lambda, one_minus_lambda;
+    double coef_d, coef_s;                         // d <- coef_d d + coef_s (w^ - sent): EMA (1-lambda, lambda), eager (0, 1/R)
     // optimizer, every coefficient a per-step scalar evaluated once on the host in double:
     //   g  = grad_scale * g_raw                        (folded into b_m, b_v, c_g on the host)
     //   m' = a_m m + b_m g ;  v' = a_v v + b_v g^2
@@ -298,8 +299,8 @@ __device__ __forceinline__ void step_replica(const StepArgs &a, uint32_t i, uint
             if ((s.mask_recv >> j) & 1u) {
                 if (a.ema) {
                     const float sent = a.same_slot ? w_hat.v[j] : sent_lds[c];
-                    in.d.v[j] = (float)fma(a.one_minus_lambda, (double)in.d.v[j],
-                                           a.lambda * ((double)w_hat.v[j] - (double)sent));
+                    in.d.v[j] = (float)fma(a.coef_d, (double)in.d.v[j],
+                                           a.coef_s * ((double)w_hat.v[j] - (double)sent));
                     w_new.v[j] = (float)((double)abar[j] + (double)in.d.v[j]);
                 } else {
                     w_new.v[j] = abar[j];
@@ -496,6 +497,83 @@ k_lookahead(void *__restrict__ out, const float *__restrict__ w, const float *__
         if (OUT_BF16) store_bf16x4(static_cast<uint16_t *>(out), mu, nvalid, f);
         else store_f32x4(static_cast<float *>(out), mu, nvalid, f);
     }
+}
+
+// =============================================================================================
+// Diagnostics: consensus error and variance of the EMA estimates over the replicas
+// =============================================================================================
+struct DiagArgs {
+    const float *w[kMaxReplicas];
+    const float *d[kMaxReplicas];      // all NULL when there is no correction vector
+    uint64_t n;
+    uint32_t replicas;
+    uint32_t has_d;
+};
+
+// Workgroup b reduces the coordinates b, b + gridDim, ... (one coordinate per thread per pass) and
+// writes its three partial results; a fixed grid and a fixed order make the result reproducible.
+__global__ void __launch_bounds__(256)
+k_diag_partial(const DiagArgs a, double *__restrict__ partial)
+{
+    __shared__ double red[3][256];
+    double cons = 0., var_sum = 0., var_max = 0.;
+    const uint64_t stride = (uint64_t)gridDim.x * 256u;
+    const double inv_r = 1.0 / (double)a.replicas;
+    for (uint64_t mu = (uint64_t)blockIdx.x * 256u + threadIdx.x; mu < a.n; mu += stride) {
+        double mean = 0.;
+        for (uint32_t i = 0; i < a.replicas; ++i) mean += (double)a.w[i][mu];
+        mean *= inv_r;
+        for (uint32_t i = 0; i < a.replicas; ++i) { const double e = (double)a.w[i][mu] - mean; cons += e * e; }
+        if (a.has_d) {
+            double dm = 0., v = 0.;
+            for (uint32_t i = 0; i < a.replicas; ++i) dm += (double)a.d[i][mu];
+            dm *= inv_r;
+            for (uint32_t i = 0; i < a.replicas; ++i) { const double e = (double)a.d[i][mu] - dm; v += e * e; }
+            v *= inv_r;
+            var_sum += v;
+            var_max = v > var_max ? v : var_max;
+        }
+    }
+    red[0][threadIdx.x] = cons; red[1][threadIdx.x] = var_sum; red[2][threadIdx.x] = var_max;
+    __syncthreads();
+    for (uint32_t off = 128; off > 0; off >>= 1) {
+        if (threadIdx.x < off) {
+            red[0][threadIdx.x] += red[0][threadIdx.x + off];
+            red[1][threadIdx.x] += red[1][threadIdx.x + off];
+            const double o = red[2][threadIdx.x + off];
+            if (o > red[2][threadIdx.x]) red[2][threadIdx.x] = o;
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        partial[3 * blockIdx.x + 0] = red[0][0];
+        partial[3 * blockIdx.x + 1] = red[1][0];
+        partial[3 * blockIdx.x + 2] = red[2][0];
+    }
+}
+
+__global__ void __launch_bounds__(256)
+k_diag_final(const double *__restrict__ partial, uint32_t nblocks, uint64_t n, double *__restrict__ out3)
+{
+    __shared__ double red[3][256];
+    double cons = 0., var_sum = 0., var_max = 0.;
+    for (uint32_t b = threadIdx.x; b < nblocks; b += 256u) {
+        cons += partial[3 * b]; var_sum += partial[3 * b + 1];
+        const double o = partial[3 * b + 2];
+        var_max = o > var_max ? o : var_max;
+    }
+    red[0][threadIdx.x] = cons; red[1][threadIdx.x] = var_sum; red[2][threadIdx.x] = var_max;
+    __syncthreads();
+    for (uint32_t off = 128; off > 0; off >>= 1) {
+        if (threadIdx.x < off) {
+            red[0][threadIdx.x] += red[0][threadIdx.x + off];
+            red[1][threadIdx.x] += red[1][threadIdx.x + off];
+            const double o = red[2][threadIdx.x + off];
+            if (o > red[2][threadIdx.x]) red[2][threadIdx.x] = o;
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) { out3[0] = red[0][0]; out3[1] = red[1][0] / (double)n; out3[2] = red[2][0]; }
 }
 
 }  // namespace am

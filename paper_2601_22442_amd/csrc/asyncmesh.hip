@@ -70,10 +70,10 @@ uint64_t slot_capacity_lines(uint64_t ntiles, double p)
 struct Layout {
     uint32_t ntiles, nsb, slots;
     uint64_t cap_lines;
-    uint64_t off_flags, off_next, off_meta, meta_stride, meta_sb_off, off_ring, ring_stride, total;
+    uint64_t off_flags, off_reduce, off_next, off_meta, meta_stride, meta_sb_off, off_ring, ring_stride, total;
 };
 
-// workspace = [flags 256 B][next_lines u32[ntiles]][meta x (slots + 1)][ring values x slots]
+// workspace = [flags 256 B][reduction partials 3 x 1024 doubles][next_lines u32[ntiles]][meta x (slots + 1)][ring values x slots]
 //   meta    = local_off u32[ntiles] | sb_base u32[nsb + 1]         (the extra one serves am_subset_indices)
 //   ring    = R * cap_lines * 32 fp32: [replica][line][32]; a tile owns whole lines
 Layout make_layout(const am_config &c)
@@ -84,7 +84,8 @@ Layout make_layout(const am_config &c)
     L.slots = c.delay + 1;
     L.cap_lines = slot_capacity_lines(L.ntiles, c.fraction);
     L.off_flags = 0;
-    L.off_next = 256;
+    L.off_reduce = 256;
+    L.off_next = L.off_reduce + 3 * 1024 * 8;
     L.off_meta = L.off_next + round_up((uint64_t)L.ntiles * 4, 256);
     L.meta_sb_off = round_up((uint64_t)L.ntiles * 4, 256);
     L.meta_stride = L.meta_sb_off + round_up(((uint64_t)L.nsb + 1) * 4, 256);
@@ -103,7 +104,7 @@ am_status check_config(const am_config *c)
     if (c->delay > 4096) return fail(AM_EINVAL, "delay=%u is larger than 4096 rounds", c->delay);
     if (!(c->fraction > 0.0) || !(c->fraction <= 1.0)) return fail(AM_EINVAL, "fraction=%g not in (0, 1]", c->fraction);
     if (c->optimizer > AM_OPT_NADAMW) return fail(AM_EINVAL, "unknown optimizer %u", c->optimizer);
-    if (c->correction > AM_CORR_EMA) return fail(AM_EINVAL, "unknown correction %u", c->correction);
+    if (c->correction > AM_CORR_EAGER) return fail(AM_EINVAL, "unknown correction %u", c->correction);
     if (c->fwd_dtype > AM_BF16 || c->grad_dtype > AM_BF16) return fail(AM_EINVAL, "unknown dtype");
     if (!(c->beta1 >= 0.f && c->beta1 < 1.f)) return fail(AM_EINVAL, "beta1=%g not in [0, 1)", c->beta1);
     if (c->optimizer != AM_OPT_SGD && !(c->beta2 >= 0.f && c->beta2 < 1.f)) return fail(AM_EINVAL, "beta2=%g not in [0, 1)", c->beta2);
@@ -126,6 +127,7 @@ struct am_state {
     char *ws;
     uint64_t last_t;
     uint64_t next_lines_step;    // the step whose send subset next_lines() was sized for (0 = none)
+    uint32_t delay_now;          // the delay in force (<= cfg.delay, which sizes the ring)
     double mu_product;           // NAdam: running product of the momentum schedule
     uint64_t threshold;
     // profiling of the fused kernel
@@ -134,6 +136,7 @@ struct am_state {
     size_t ev_used;
 
     uint32_t *flags() const { return reinterpret_cast<uint32_t *>(ws + lay.off_flags); }
+    double *reduce_partials() const { return reinterpret_cast<double *>(ws + lay.off_reduce); }
     uint32_t *next_lines() const { return reinterpret_cast<uint32_t *>(ws + lay.off_next); }
     uint32_t *meta_local(uint32_t slot) const { return reinterpret_cast<uint32_t *>(ws + lay.off_meta + lay.meta_stride * slot); }
     uint32_t *meta_sb(uint32_t slot) const { return reinterpret_cast<uint32_t *>(ws + lay.off_meta + lay.meta_stride * slot + lay.meta_sb_off); }
@@ -182,15 +185,15 @@ struct Round {
 Round plan_round(const am_state *st, uint64_t t)
 {
     Round r{};
-    const uint64_t K = st->cfg.avg_interval, tau = st->cfg.delay;
+    const uint64_t K = st->cfg.avg_interval, depth = (uint64_t)st->cfg.delay + 1, tau = st->delay_now;
     if (t % K != 0) return r;
     const uint64_t round = t / K;
     r.send = true;
-    r.slot_send = (uint32_t)(round % (tau + 1));
+    r.slot_send = (uint32_t)(round % depth);
     if (t >= tau * K + 1) {                       // s = t - tau K >= 1: something was sent that long ago
         r.recv = true;
         r.step_recv = t - tau * K;
-        r.slot_recv = (uint32_t)((round - tau) % (tau + 1));
+        r.slot_recv = (uint32_t)((round - tau) % depth);
         r.same_slot = tau == 0;
     }
     return r;
@@ -223,8 +226,9 @@ am_status fill_averaging(am_state *st, uint64_t t, float lambda_t, const Round &
     const am_config &c = st->cfg;
     a.n = c.n; a.ntiles = st->lay.ntiles; a.replicas = c.replicas;
     a.cap_lines = (uint32_t)st->lay.cap_lines;
-    a.lambda = (double)lambda_t; a.one_minus_lambda = 1.0 - (double)lambda_t;
-    a.ema = c.correction == AM_CORR_EMA;
+    a.ema = c.correction != AM_CORR_NONE;
+    if (c.correction == AM_CORR_EAGER) { a.coef_d = 0.0; a.coef_s = 1.0 / (double)c.replicas; }
+    else { a.coef_d = 1.0 - (double)lambda_t; a.coef_s = (double)lambda_t; }
     a.do_send = r.send; a.do_recv = r.recv; a.same_slot = r.same_slot;
     if (r.send) {
         if (am_status s = launch_subset_offsets(st, t, r.slot_send, nullptr, true)) return s;
@@ -264,7 +268,7 @@ am_status am_init_state(const am_config *cfg, const am_buffers *buf, void *hip_s
     const uint32_t R = cfg->replicas;
     const bool need_m = !(cfg->optimizer == AM_OPT_SGD && cfg->beta1 == 0.f);
     const bool need_v = cfg->optimizer != AM_OPT_SGD;
-    const bool need_d = cfg->correction == AM_CORR_EMA;
+    const bool need_d = cfg->correction != AM_CORR_NONE;
     const bool need_fwd = cfg->lookahead != 0 || cfg->fwd_dtype == AM_BF16;
     if (!buf->w) return fail(AM_EINVAL, "buffers.w is NULL");
     if (need_m && !buf->m) return fail(AM_EINVAL, "buffers.m is NULL but the optimizer keeps a first moment");
@@ -295,6 +299,7 @@ am_status am_init_state(const am_config *cfg, const am_buffers *buf, void *hip_s
     st->ws = static_cast<char *>(buf->workspace);
     st->last_t = 0;
     st->next_lines_step = 0;
+    st->delay_now = cfg->delay;
     st->mu_product = 1.0;
     st->threshold = subset_threshold(cfg->fraction);
     st->profiling = false;
@@ -462,6 +467,31 @@ am_status am_subset_indices(am_state *st, uint64_t t, uint64_t *dev_out, uint64_
                                                                   st->meta_local(scratch), st->meta_sb(scratch), dev_out, capacity);
         AM_HIP(hipGetLastError());
     }
+    return AM_OK;
+}
+
+am_status am_set_delay(am_state *st, uint32_t tau)
+{
+    if (!st) return fail(AM_EINVAL, "state is NULL");
+    if (tau > st->cfg.delay) return fail(AM_EINVAL, "delay %u exceeds the ring depth the state was created with (%u)", tau, st->cfg.delay);
+    st->delay_now = tau;
+    return AM_OK;
+}
+
+am_status am_diagnostics(am_state *st, double *dev_out3)
+{
+    if (!st || !dev_out3) return fail(AM_EINVAL, "NULL argument");
+    if (!aligned(dev_out3, 8)) return fail(AM_EALIGN, "dev_out3 is not 8-byte aligned");
+    am::DiagArgs a;
+    std::memset(&a, 0, sizeof a);
+    for (uint32_t i = 0; i < st->cfg.replicas; ++i) { a.w[i] = st->w[i]; a.d[i] = st->d[i]; }
+    a.n = st->cfg.n; a.replicas = st->cfg.replicas; a.has_d = st->d[0] != nullptr;
+    const uint64_t want = (st->cfg.n + 255) / 256;
+    const uint32_t blocks = (uint32_t)(want < 1024 ? want : 1024);
+    am::k_diag_partial<<<blocks, 256, 0, st->stream>>>(a, st->reduce_partials());
+    AM_HIP(hipGetLastError());
+    am::k_diag_final<<<1, 256, 0, st->stream>>>(st->reduce_partials(), blocks, st->cfg.n, dev_out3);
+    AM_HIP(hipGetLastError());
     return AM_OK;
 }
 

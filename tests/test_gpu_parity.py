@@ -164,6 +164,41 @@ def test_optimizers_and_corrections(amlib, opt, b1, corr):
               correction=corr, lookahead=True, gamma=0.9, weight_decay=0.01)
 
 
+def test_eager_correction_mode(amlib):
+    run_steps(amlib, 25_013, 4, 9, delay=2, fraction=1.0, seed=4, correction=O.CORR_EAGER)
+    run_steps(amlib, 25_013, 3, 9, delay=1, avg_interval=2, fraction=0.3, seed=4, correction=O.CORR_EAGER,
+              lookahead=True, gamma=0.9)
+
+
+def test_delay_changed_at_run_time(amlib):
+    """Late and early averages: the delay in force changes from step to step within the ring's depth."""
+    n, R = 33_333, 4
+    st, orc = make_pair(amlib, n, R, delay=3, fraction=0.2, seed=6, lookahead=True, gamma=0.9)
+    delays = [3, 3, 3, 3, 1, 3, 0, 2, 2, 3, 0, 0, 1, 3]
+    for t, tau in enumerate(delays, start=1):
+        st.set_delay(tau); orc.set_delay(tau)
+        g, gd = grads_for(n, R, t, 6, False)
+        st.step(t, gd, 1e-3, 0.5); orc.step(t, g, 1e-3, 0.5)
+        compare(st, orc, f"t={t} tau={tau}")
+    with pytest.raises(amlib.AsyncMeshError):
+        st.set_delay(4)
+
+
+def test_diagnostics(amlib):
+    n, R = 123_457, 5
+    st, orc = make_pair(amlib, n, R, delay=1, fraction=0.3, seed=12)
+    for t in range(1, 6):
+        g, gd = grads_for(n, R, t, 12, False)
+        st.step(t, gd, 1e-3, 0.5); orc.step(t, g, 1e-3, 0.5)
+    cons, vmean, vmax = st.diagnostics()
+    ovm, ovx = orc.ema_variance()
+    assert abs(cons - orc.consensus_error()) < 1e-9 * orc.consensus_error()
+    assert abs(vmean - ovm) < 1e-9 * ovm and abs(vmax - ovx) < 1e-9 * ovx
+    assert st.diagnostics() == (cons, vmean, vmax)                 # fixed reduction order
+    st2, orc2 = make_pair(amlib, 1000, 2, delay=1, fraction=0.3, seed=12, correction=O.CORR_NONE)
+    assert st2.diagnostics() == (0.0, 0.0, 0.0)                    # identical replicas, no correction vector
+
+
 def test_lambda_and_grad_scale(amlib):
     run_steps(amlib, 12_345, 4, 6, lam=1.0, grad_scale=0.25, delay=1, fraction=0.3, seed=2)
     run_steps(amlib, 12_345, 4, 6, lam=0.01, delay=1, fraction=0.3, seed=2)
