@@ -76,9 +76,15 @@ uint64_t amo_threshold(double p)
     return (uint64_t)floor(p * 4294967296.0);
 }
 
-/* is global coordinate mu in the subset drawn for step s ? */
-int amo_member(uint64_t seed, uint64_t s, uint64_t mu, uint64_t threshold)
+/* is global coordinate mu in the subset drawn for step s ?
+ * granule 1: every coordinate is drawn on its own (the paper's sampling model).
+ * granule g > 1 (a variant, not the paper's): aligned blocks of g consecutive coordinates are drawn
+ * as a whole, block b = mu / g taking the place of the coordinate in the counter; every coordinate
+ * is still in the subset with probability p (all the sparse-averaging lemma uses), but coordinates
+ * of one block are no longer independent. */
+int amo_member(uint64_t seed, uint64_t s, uint64_t mu, uint64_t threshold, uint32_t granule)
 {
+    if (granule > 1) mu /= granule;
     uint64_t group = mu >> 2;
     uint32_t counter[4] = { (uint32_t)group, (uint32_t)(group >> 32), (uint32_t)s, (uint32_t)(s >> 32) };
     uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) };
@@ -89,12 +95,12 @@ int amo_member(uint64_t seed, uint64_t s, uint64_t mu, uint64_t threshold)
 
 /* ascending list of the members of S^s inside [mu0, mu0+n); returns how many there are
  * (all of them are counted even when out_capacity is too small to hold them) */
-uint64_t amo_subset(uint64_t seed, uint64_t s, uint64_t mu0, uint64_t n, double p,
+uint64_t amo_subset(uint64_t seed, uint64_t s, uint64_t mu0, uint64_t n, double p, uint32_t granule,
                     uint64_t *out, uint64_t out_capacity)
 {
     uint64_t T = amo_threshold(p), count = 0;
     for (uint64_t k = 0; k < n; ++k)
-        if (amo_member(seed, s, mu0 + k, T)) {
+        if (amo_member(seed, s, mu0 + k, T, granule)) {
             if (out && count < out_capacity) out[count] = mu0 + k;
             ++count;
         }
@@ -155,6 +161,8 @@ typedef struct {
     uint32_t fwd_bf16;     /* fwd stored as bfloat16 instead of fp32                        */
     uint32_t grad_bf16;    /* gradients arrive as bfloat16                                  */
     double   momentum_decay; /* NAdam's psi (0.004 in Dozat's schedule); NADAMW only        */
+    uint32_t granule;        /* subset drawn per coordinate (1) or per aligned block of g   */
+    uint32_t reserved_;
 } amo_config;
 
 typedef struct {
@@ -309,7 +317,7 @@ static void sparse_average(amo_state *s, uint64_t t, double lambda)
 
     #pragma omp parallel for schedule(static)
     for (uint64_t k = 0; k < n; ++k) {
-        if (!amo_member(c->seed, sstep, c->mu0 + k, T)) continue;
+        if (!amo_member(c->seed, sstep, c->mu0 + k, T, c->granule)) continue;
         double sum = 0.0;
         for (uint32_t i = 0; i < R; ++i) sum += (double)old[i][k];
         const float abar = (float)(sum / (double)R);              /* old average, an fp32 message */

@@ -75,6 +75,37 @@ def test_subset_statistics():
     assert abs(both - (n / 4) * p * p) < 6 * math.sqrt((n / 4) * p * p)
 
 
+def test_block_granule_variant_keeps_the_marginal_probability():
+    """Variant (not the paper's sampling): aligned blocks of 32 coordinates drawn as a whole.  Every
+    coordinate is still selected with probability p; blocks are all-or-nothing; block b uses the
+    generator exactly as coordinate b does in the per-coordinate scheme."""
+    n, p, seed, s = 64_000, 0.1, 7, 4
+    S = O.subset(seed, s, n, p, granule=32)
+    a = np.zeros(n, dtype=bool); a[S.astype(np.int64)] = True
+    blocks = a.reshape(-1, 32)
+    assert np.all(blocks.all(axis=1) | ~blocks.any(axis=1))
+    per_coord = O.subset(seed, s, n // 32, p)                     # "coordinates" = block numbers
+    assert np.array_equal(np.flatnonzero(blocks[:, 0]).astype(np.uint64), per_coord)
+    hits = np.zeros(n // 32)
+    for t in range(1, 201):
+        b = np.zeros(n, dtype=bool); b[O.subset(seed, t, n, p, granule=32).astype(np.int64)] = True
+        hits += b[::32]
+    assert abs(hits.mean() / 200 - p) < 5 * math.sqrt(p * (1 - p) / (200 * n / 32))
+    # the averaging itself is unchanged: subset coordinates take the mean (tau = 0)
+    R, lr = 3, O.f32(0.25)
+    w0 = np.stack([si.stage_weights(n, seed=60 + i) for i in range(R)])
+    orc = O.Oracle(n, R, delay=0, fraction=p, seed=seed, optimizer=O.OPT_SGD, beta1=0.0, weight_decay=0.0,
+                   subset_granule=32)
+    orc.set_w(w0)
+    g = np.stack(si.replica_grads(n, R, 1, seed=9))
+    what = (w0.astype(np.float64) - lr * g.astype(np.float64)).astype(np.float32)
+    want = what.copy()
+    S1 = O.subset(seed, 1, n, p, granule=32).astype(np.int64)
+    want[:, S1] = what[:, S1].astype(np.float64).mean(axis=0).astype(np.float32)
+    orc.step(1, list(g), lr)
+    assert np.array_equal(np.stack([orc.w(i) for i in range(R)]), want)
+
+
 # --------------------------------------------------------------------------------------------
 # bf16 helpers against a library conversion
 # --------------------------------------------------------------------------------------------
