@@ -93,6 +93,8 @@ def main():
     ap.add_argument("--fraction", type=float, default=None, help="override the workload's subset fraction p")
     ap.add_argument("--delay", type=int, default=None, help="override the workload's delay tau")
     ap.add_argument("--no-correction", action="store_true", help="plain delayed averaging (no EMA vector)")
+    ap.add_argument("--subset-granule", type=int, default=1, choices=(1, 32),
+                    help="1: coordinates drawn independently (the paper); 32: variant, whole 128-byte lines drawn")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (replicas are simulated as HBM-resident copies on it); "
@@ -115,6 +117,7 @@ def main():
 
     cfg = am.make_config(n, R, delay=tau, avg_interval=args.avg_interval, fraction=p, seed=0, optimizer=am.OPT_ADAMW,
                          correction=am.CORR_NONE if args.no_correction else am.CORR_EMA,
+                         subset_granule=args.subset_granule,
                          lookahead=w["lookahead"], gamma=0.9,
                          fwd_dtype=am.BF16 if w["bf16"] else am.F32,
                          grad_dtype=am.BF16 if w["bf16"] else am.F32)
@@ -167,7 +170,8 @@ def main():
         "config": {"workload": DESCRIPTION.get(args.workload, args.workload), "name": args.workload,
                    "n": n, "replicas": R, "delay": tau, "fraction": p, "lookahead": w["lookahead"],
                    "avg_interval": args.avg_interval,
-                   "correction": "none" if args.no_correction else "ema", "bf16": w["bf16"], "algorithmic_bytes_per_param": bpp},
+                   "correction": "none" if args.no_correction else "ema",
+                   "subset_granule": args.subset_granule, "bf16": w["bf16"], "algorithmic_bytes_per_param": bpp},
         "step_GBps": bytes_per_launch / (elapsed / args.steps) / 1e9,
         "step_frac_of_hbm_peak": bytes_per_launch / (elapsed / args.steps) / 1e9 / HBM_PEAK_GBPS,
         "roofline": {"kernel": "k_step", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS,

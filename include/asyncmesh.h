@@ -83,6 +83,11 @@ typedef struct {
     uint32_t fwd_dtype;      /* am_dtype of the fwd arrays                                               */
     uint32_t grad_dtype;     /* am_dtype of the gradient arrays                                          */
     double   momentum_decay; /* NADAMW only: psi of mu_t = beta1 (1 - 0.5 * 0.96^(t psi)); usual 0.004   */
+    uint32_t subset_granule; /* 1 (or 0): coordinates drawn independently, the paper's sampling model.
+                                32: VARIANT, not the paper's: aligned blocks of 32 coordinates (one
+                                128-byte line) drawn as a whole, block b in place of coordinate b in
+                                the generator; same inclusion probability p per coordinate.         */
+    uint32_t reserved;       /* 0                                                                        */
 } am_config;
 
 /* The subset: S^t = { mu in [0, n) : X(seed, t, mu) < floor(p * 2^32) }, X = word (mu & 3) of

@@ -46,12 +46,21 @@ struct SubsetKey {
     uint32_t seed_lo, seed_hi;   // Philox key
     uint32_t step_lo, step_hi;   // counter words 2, 3
     uint64_t threshold;          // floor(p 2^32); 2^32 selects everything
+    uint32_t by_line;            // 0: every coordinate drawn on its own; 1: aligned blocks of 32 drawn as a whole
+    uint32_t pad_;
 };
 
 // 4-bit membership mask of the coordinates 4*group .. 4*group+3 (bit j = coordinate 4*group+j),
 // restricted to the first nvalid of them.
 __device__ __forceinline__ uint32_t member_mask(const SubsetKey &k, uint64_t group, int nvalid)
 {
+    if (k.by_line) {
+        // block b = 32 coordinates = 8 groups takes the place of coordinate b in the generator
+        const uint64_t b = group >> 3, bg = b >> 2;
+        const U4 x = philox4x32_10((uint32_t)bg, (uint32_t)(bg >> 32), k.step_lo, k.step_hi, k.seed_lo, k.seed_hi);
+        const uint32_t word = (b & 3u) == 0u ? x.x0 : (b & 3u) == 1u ? x.x1 : (b & 3u) == 2u ? x.x2 : x.x3;
+        return ((uint64_t)word < k.threshold) ? ((1u << nvalid) - 1u) : 0u;
+    }
     const U4 x = philox4x32_10((uint32_t)group, (uint32_t)(group >> 32), k.step_lo, k.step_hi,
                                k.seed_lo, k.seed_hi);
     uint32_t m = 0;

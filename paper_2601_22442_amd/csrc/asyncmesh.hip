@@ -50,10 +50,15 @@ uint64_t subset_threshold(double p)
 // Lines (of 32 floats) one replica's part of a ring slot must hold.  Every tile of 256
 // coordinates owns ceil(X / 32) whole lines, X ~ Binomial(256, p) its number of selected
 // coordinates; the slot has room for the expected total plus twelve standard deviations.
-uint64_t slot_capacity_lines(uint64_t ntiles, double p)
+uint64_t slot_capacity_lines(uint64_t ntiles, double p, bool by_line)
 {
     const uint64_t all = ntiles * (am::kTileCoords / am::kLineFloats);
     if (p >= 1.0) return all;
+    if (by_line) {                       // every line of a tile is drawn as a whole: Binomial(8, p) lines
+        const double per = am::kTileCoords / am::kLineFloats;
+        const double cap = std::ceil((double)ntiles * per * p + 12.0 * std::sqrt((double)ntiles * per * p * (1.0 - p))) + 64.0;
+        return cap >= (double)all ? all : (uint64_t)cap;
+    }
     double mean = 0.0, sq = 0.0;
     const double lp = std::log(p), lq = std::log1p(-p), T = am::kTileCoords;
     for (int k = 0; k <= (int)am::kTileCoords; ++k) {
@@ -82,7 +87,7 @@ Layout make_layout(const am_config &c)
     L.ntiles = (uint32_t)((c.n + am::kTileCoords - 1) / am::kTileCoords);
     L.nsb = (L.ntiles + am::kTilesPerSuperblock - 1) / am::kTilesPerSuperblock;
     L.slots = c.delay + 1;
-    L.cap_lines = slot_capacity_lines(L.ntiles, c.fraction);
+    L.cap_lines = slot_capacity_lines(L.ntiles, c.fraction, c.subset_granule == 32);
     L.off_flags = 0;
     L.off_reduce = 256;
     L.off_next = L.off_reduce + 3 * 1024 * 8;
@@ -106,6 +111,7 @@ am_status check_config(const am_config *c)
     if (c->optimizer > AM_OPT_NADAMW) return fail(AM_EINVAL, "unknown optimizer %u", c->optimizer);
     if (c->correction > AM_CORR_EAGER) return fail(AM_EINVAL, "unknown correction %u", c->correction);
     if (c->fwd_dtype > AM_BF16 || c->grad_dtype > AM_BF16) return fail(AM_EINVAL, "unknown dtype");
+    if (c->subset_granule != 0 && c->subset_granule != 1 && c->subset_granule != 32) return fail(AM_EINVAL, "subset_granule=%u is not 1 or 32", c->subset_granule);
     if (!(c->beta1 >= 0.f && c->beta1 < 1.f)) return fail(AM_EINVAL, "beta1=%g not in [0, 1)", c->beta1);
     if (c->optimizer != AM_OPT_SGD && !(c->beta2 >= 0.f && c->beta2 < 1.f)) return fail(AM_EINVAL, "beta2=%g not in [0, 1)", c->beta2);
     if (c->optimizer != AM_OPT_SGD && !(c->eps >= 0.f)) return fail(AM_EINVAL, "eps=%g negative", c->eps);
@@ -153,6 +159,8 @@ am::SubsetKey make_key(const am_state *st, uint64_t step)
     k.step_lo = (uint32_t)step;
     k.step_hi = (uint32_t)(step >> 32);
     k.threshold = st->threshold;
+    k.by_line = st->cfg.subset_granule == 32 ? 1u : 0u;
+    k.pad_ = 0;
     return k;
 }
 

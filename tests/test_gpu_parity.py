@@ -164,6 +164,19 @@ def test_optimizers_and_corrections(amlib, opt, b1, corr):
               correction=corr, lookahead=True, gamma=0.9, weight_decay=0.01)
 
 
+def test_block_granule_variant(amlib):
+    """Variant sampling: aligned blocks of 32 coordinates drawn as a whole (indices and values)."""
+    am = amlib
+    n, p, seed = 300_007, 0.07, 5
+    st, orc = run_steps(am, n, 4, 8, delay=2, fraction=p, seed=seed, subset_granule=32, lookahead=True, gamma=0.9)
+    for t in (1, 5, (1 << 33) + 2):
+        idx, k = st.subset_indices(t)
+        want = O.subset(seed, t, n, p, granule=32)
+        assert k == want.size and np.array_equal(idx.cpu().numpy().astype(np.uint64), want)
+    run_steps(am, 1000, 3, 6, delay=0, fraction=0.3, seed=2, subset_granule=32)
+    run_steps(am, 4099, 8, 6, delay=1, fraction=1.0, seed=2, subset_granule=32)
+
+
 def test_eager_correction_mode(amlib):
     run_steps(amlib, 25_013, 4, 9, delay=2, fraction=1.0, seed=4, correction=O.CORR_EAGER)
     run_steps(amlib, 25_013, 3, 9, delay=1, avg_interval=2, fraction=0.3, seed=4, correction=O.CORR_EAGER,

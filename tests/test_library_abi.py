@@ -29,10 +29,10 @@ def test_every_declared_symbol_is_exported(amlib):
 
 def test_config_struct_matches_header_layout(amlib):
     from paper_2601_22442_amd.binding import Config
-    assert C.sizeof(Config) == 88
+    assert C.sizeof(Config) == 96
     assert Config.fraction.offset == 24 and Config.seed.offset == 32
     assert Config.beta1.offset == 40 and Config.gamma.offset == 56
-    assert Config.grad_dtype.offset == 72 and Config.momentum_decay.offset == 80
+    assert Config.grad_dtype.offset == 72 and Config.momentum_decay.offset == 80 and Config.subset_granule.offset == 88
 
 
 def test_workspace_bytes_and_capacity_formula(amlib):
@@ -57,7 +57,7 @@ def test_workspace_bytes_and_capacity_formula(amlib):
     (dict(n=0), "n="), (dict(n=2 ** 32), "n="), (dict(replicas=0), "replicas"), (dict(replicas=33), "replicas"),
     (dict(avg_interval=0), "avg_interval"), (dict(fraction=0.0), "fraction"), (dict(fraction=1.5), "fraction"),
     (dict(optimizer=7), "optimizer"), (dict(correction=5), "correction"), (dict(beta1=1.0), "beta1"),
-    (dict(fwd_dtype=3), "dtype"),
+    (dict(fwd_dtype=3), "dtype"), (dict(subset_granule=16), "granule"),
 ])
 def test_bad_configs_are_rejected(amlib, kw, needle):
     am = amlib
