@@ -139,6 +139,33 @@ uint16_t amo_double_to_bf16(double x)
     return sign | (uint16_t)(bits >> 16);
 }
 
+/* round-to-nearest-even of a double to the 8-bit float E4M3 (OCP "FN" flavour: 1 sign, 4 exponent
+ * bits with bias 7, 3 fraction bits, no infinity, largest finite value 448), saturating; returned
+ * as the value it represents */
+double amo_quantize_e4m3(double x)
+{
+    if (x != x) return x;
+    double ax = fabs(x);
+    if (ax == 0.0) return x;
+    int e;
+    (void)frexp(ax, &e);
+    int exp_unbiased = e - 1;
+    if (exp_unbiased < -6) exp_unbiased = -6;           /* subnormals: fixed quantum 2^-9 */
+    double quantum = ldexp(1.0, exp_unbiased - 3);
+    double r = nearbyint(ax / quantum) * quantum;
+    if (r > 448.0) r = 448.0;
+    return signbit(x) ? -r : r;
+}
+
+/* what a replica's value becomes on the wire: 0 = fp32 (unchanged), 1 = bfloat16, 2 = E4M3 */
+enum { AMO_MSG_F32 = 0, AMO_MSG_BF16 = 1, AMO_MSG_E4M3 = 2 };
+double amo_quantize_message(float x, uint32_t msg_dtype)
+{
+    if (msg_dtype == AMO_MSG_BF16) return (double)amo_bf16_to_float(amo_double_to_bf16((double)x));
+    if (msg_dtype == AMO_MSG_E4M3) return amo_quantize_e4m3((double)x);
+    return (double)x;
+}
+
 /* ------------------------------------------------------------------------------------------ */
 /* state                                                                                       */
 /* ------------------------------------------------------------------------------------------ */
@@ -162,7 +189,9 @@ typedef struct {
     uint32_t grad_bf16;    /* gradients arrive as bfloat16                                  */
     double   momentum_decay; /* NAdam's psi (0.004 in Dozat's schedule); NADAMW only        */
     uint32_t granule;        /* subset drawn per coordinate (1) or per aligned block of g   */
-    uint32_t reserved_;
+    uint32_t msg_dtype;      /* AMO_MSG_*: precision of the exchanged values (the compression
+                                experiment: the average is formed from quantised values; a
+                                replica's own staleness term uses its own exact old value)  */
 } amo_config;
 
 typedef struct {
@@ -319,7 +348,7 @@ static void sparse_average(amo_state *s, uint64_t t, double lambda)
     for (uint64_t k = 0; k < n; ++k) {
         if (!amo_member(c->seed, sstep, c->mu0 + k, T, c->granule)) continue;
         double sum = 0.0;
-        for (uint32_t i = 0; i < R; ++i) sum += (double)old[i][k];
+        for (uint32_t i = 0; i < R; ++i) sum += amo_quantize_message(old[i][k], c->msg_dtype);
         const float abar = (float)(sum / (double)R);              /* old average, an fp32 message */
         for (uint32_t i = 0; i < R; ++i) {
             if (c->correction == AMO_CORR_EMA || c->correction == AMO_CORR_EAGER) {

@@ -18,6 +18,7 @@ _LIB = _HERE / "libasyncmesh_oracle.so"
 
 OPT_SGD, OPT_ADAMW, OPT_NADAMW = 0, 1, 2
 CORR_NONE, CORR_EMA, CORR_EAGER = 0, 1, 2
+MSG_F32, MSG_BF16, MSG_E4M3 = 0, 1, 2
 
 
 def build(force: bool = False) -> Path:
@@ -40,7 +41,7 @@ class _Config(C.Structure):
         ("lookahead", C.c_uint32), ("correction", C.c_uint32),
         ("fwd_bf16", C.c_uint32), ("grad_bf16", C.c_uint32),
         ("momentum_decay", C.c_double),
-        ("granule", C.c_uint32), ("reserved_", C.c_uint32),
+        ("granule", C.c_uint32), ("msg_dtype", C.c_uint32),
     ]
 
 
@@ -70,6 +71,8 @@ def lib():
         L.amo_sparse_average.argtypes = [C.c_void_p, C.c_uint64, C.c_double]; L.amo_sparse_average.restype = C.c_int
         L.amo_lookahead.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_double]
         L.amo_consensus_error.argtypes = [C.c_void_p]; L.amo_consensus_error.restype = C.c_double
+        L.amo_quantize_e4m3.argtypes = [C.c_double]; L.amo_quantize_e4m3.restype = C.c_double
+        L.amo_quantize_message.argtypes = [C.c_float, C.c_uint32]; L.amo_quantize_message.restype = C.c_double
         L.amo_set_delay.argtypes = [C.c_void_p, C.c_uint32]; L.amo_set_delay.restype = C.c_int
         L.amo_ema_variance.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_double)]
         _lib = L
@@ -108,6 +111,14 @@ def subset(seed: int, s: int, n: int, p: float, mu0: int = 0, granule: int = 1) 
     return out
 
 
+def quantize_e4m3(x: float) -> float:
+    return float(lib().amo_quantize_e4m3(x))
+
+
+def quantize_message(x: float, msg_dtype: int) -> float:
+    return float(lib().amo_quantize_message(x, msg_dtype))
+
+
 def double_to_bf16(x: float) -> int:
     return int(lib().amo_double_to_bf16(x))
 
@@ -134,13 +145,13 @@ class Oracle:
     def __init__(self, n, replicas, delay=0, avg_interval=1, fraction=0.05, seed=0,
                  optimizer=OPT_ADAMW, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01,
                  lookahead=False, gamma=0.0, correction=CORR_EMA, fwd_bf16=False, grad_bf16=False,
-                 momentum_decay=0.004, mu0=0, subset_granule=1):
+                 momentum_decay=0.004, mu0=0, subset_granule=1, msg_dtype=MSG_F32):
         self.cfg = _Config(
             n=n, mu0=mu0, replicas=replicas, delay=delay, avg_interval=avg_interval, optimizer=optimizer,
             fraction=fraction, seed=seed, beta1=f32(beta1), beta2=f32(beta2), eps=f32(eps),
             weight_decay=f32(weight_decay), gamma=f32(gamma), lookahead=int(bool(lookahead)),
             correction=correction, fwd_bf16=int(bool(fwd_bf16)), grad_bf16=int(bool(grad_bf16)),
-            momentum_decay=momentum_decay, granule=subset_granule)
+            momentum_decay=momentum_decay, granule=subset_granule, msg_dtype=msg_dtype)
         self.n, self.R = n, replicas
         self._h = lib().amo_create(C.byref(self.cfg))
         if not self._h:

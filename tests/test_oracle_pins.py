@@ -127,6 +127,46 @@ def test_bf16_rounding_matches_library():
     assert O.double_to_bf16(1.0 + 2.0 ** -8 + 2.0 ** -40) == 0x3F81
 
 
+def test_e4m3_rounding_matches_library():
+    rng = np.random.default_rng(6)
+    x = np.concatenate([rng.standard_normal(3000).astype(np.float32) * np.float32(0.02),
+                        rng.standard_normal(1000).astype(np.float32),
+                        rng.uniform(-440, 440, 500).astype(np.float32),
+                        np.array([0.0, 2.0 ** -9, 2.0 ** -10, 3 * 2.0 ** -10, 2.0 ** -6, 0.0175, 448.0, 1.0625, 1.1875],
+                                 dtype=np.float32)])
+    want = torch.from_numpy(x).to(torch.float8_e4m3fn).to(torch.float32).numpy()
+    got = np.array([O.quantize_e4m3(float(v)) for v in x], dtype=np.float32)
+    assert np.array_equal(got, want)
+    assert O.quantize_e4m3(1000.0) == 448.0 and O.quantize_e4m3(-1e9) == -448.0        # saturating
+    assert O.quantize_message(0.3, O.MSG_F32) == float(np.float32(0.3))
+    assert O.quantize_message(0.3, O.MSG_BF16) == O.bf16_to_float(O.double_to_bf16(float(np.float32(0.3))))
+
+
+def test_quantised_message_only_touches_the_average():
+    """Compression experiment: the average is formed from quantised values; everything a replica
+    knows locally (its own old value in the staleness term) stays exact."""
+    n, R, tau, lr, lam = 1200, 3, 1, O.f32(0.125), O.f32(0.5)
+    w0 = si.stage_weights(n, seed=40)
+    for msg, quant in ((O.MSG_BF16, lambda a: si.bf16_bits_to_f32(si.to_bf16_bits(a))),
+                       (O.MSG_E4M3, lambda a: torch.from_numpy(a).to(torch.float8_e4m3fn).to(torch.float32).numpy())):
+        orc = O.Oracle(n, R, delay=tau, fraction=1.0, optimizer=O.OPT_SGD, beta1=0.0, weight_decay=0.0, msg_dtype=msg)
+        orc.set_w(w0)
+        cur, whats, d = np.stack([w0] * R), {}, np.zeros((R, n), np.float32)
+        for t in range(1, 5):
+            g = np.stack(si.replica_grads(n, R, t, seed=40))
+            what = (cur.astype(np.float64) - lr * g.astype(np.float64)).astype(np.float32)
+            whats[t] = what
+            want = what.copy()
+            if t > tau:
+                old = whats[t - tau]
+                abar = np.stack([quant(np.ascontiguousarray(old[i])) for i in range(R)]).astype(np.float64).mean(axis=0).astype(np.float32)
+                d = ((1 - lam) * d.astype(np.float64) + lam * (what.astype(np.float64) - old.astype(np.float64))).astype(np.float32)
+                want = (abar.astype(np.float64)[None, :] + d.astype(np.float64)).astype(np.float32)
+            orc.step(t, list(g), lr, lam=lam)
+            cur = np.stack([orc.w(i) for i in range(R)])
+            assert np.array_equal(cur, want), (msg, t)
+
+
 # --------------------------------------------------------------------------------------------
 # local step alone == a stand-alone optimizer run (library routine)
 # --------------------------------------------------------------------------------------------
