@@ -68,6 +68,15 @@ typedef enum {
 
 typedef enum { AM_F32 = 0, AM_BF16 = 1 } am_dtype;
 
+/* Precision of the values put on the wire (the paper's compression experiment: quantising the
+ * exchanged subset).  The old average is formed from the quantised values (accumulated exactly,
+ * rounded to fp32); a replica's own staleness term uses its own exact old value. */
+typedef enum {
+    AM_MSG_F32  = 0,
+    AM_MSG_BF16 = 1,    /* round to nearest even                                                     */
+    AM_MSG_E4M3 = 2     /* 8-bit float 1-4-3, bias 7, no infinity, max 448; nearest even, saturating */
+} am_msg;
+
 typedef struct {
     uint64_t n;              /* d_j: parameters of the stage, per replica; 1 <= n < 2^32 - 2^20          */
     uint32_t replicas;       /* m = R, 1 .. AM_MAX_REPLICAS                                              */
@@ -87,7 +96,7 @@ typedef struct {
                                 32: VARIANT, not the paper's: aligned blocks of 32 coordinates (one
                                 128-byte line) drawn as a whole, block b in place of coordinate b in
                                 the generator; same inclusion probability p per coordinate.         */
-    uint32_t reserved;       /* 0                                                                        */
+    uint32_t msg_dtype;      /* am_msg: precision of the exchanged subset values                        */
 } am_config;
 
 /* The subset: S^t = { mu in [0, n) : X(seed, t, mu) < floor(p * 2^32) }, X = word (mu & 3) of

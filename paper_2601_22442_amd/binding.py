@@ -18,6 +18,7 @@ MAX_REPLICAS = 32
 OPT_SGD, OPT_ADAMW, OPT_NADAMW = 0, 1, 2
 CORR_NONE, CORR_EMA, CORR_EAGER = 0, 1, 2
 F32, BF16 = 0, 1
+MSG_F32, MSG_BF16, MSG_E4M3 = 0, 1, 2
 
 EXPORTS = (
     "am_workspace_bytes", "am_init_state", "am_step", "am_sparse_average", "am_lookahead",
@@ -42,7 +43,7 @@ class Config(C.Structure):
         ("gamma", C.c_float),
         ("lookahead", C.c_uint32), ("correction", C.c_uint32), ("fwd_dtype", C.c_uint32), ("grad_dtype", C.c_uint32),
         ("momentum_decay", C.c_double),
-        ("subset_granule", C.c_uint32), ("reserved", C.c_uint32),
+        ("subset_granule", C.c_uint32), ("msg_dtype", C.c_uint32),
     ]
 
 
@@ -98,12 +99,12 @@ def version() -> str:
 def make_config(n, replicas, delay=0, avg_interval=1, fraction=0.05, seed=0, optimizer=OPT_ADAMW,
                 beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01, lookahead=False, gamma=0.0,
                 correction=CORR_EMA, fwd_dtype=F32, grad_dtype=F32, momentum_decay=0.004,
-                subset_granule=1) -> Config:
+                subset_granule=1, msg_dtype=MSG_F32) -> Config:
     return Config(n=n, replicas=replicas, delay=delay, avg_interval=avg_interval, optimizer=optimizer,
                   fraction=fraction, seed=seed, beta1=beta1, beta2=beta2, eps=eps, weight_decay=weight_decay,
                   gamma=gamma, lookahead=int(bool(lookahead)), correction=correction,
                   fwd_dtype=fwd_dtype, grad_dtype=grad_dtype, momentum_decay=momentum_decay,
-                  subset_granule=subset_granule, reserved=0)
+                  subset_granule=subset_granule, msg_dtype=msg_dtype)
 
 
 def workspace_bytes(cfg: Config) -> int:

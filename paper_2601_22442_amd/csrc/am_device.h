@@ -137,6 +137,25 @@ __device__ __forceinline__ uint16_t f32_to_bf16_bits(float f)
     return __builtin_bit_cast(uint16_t, b);
 }
 
+// What a value becomes on the wire: 0 = fp32, 1 = bfloat16, 2 = E4M3 (1-4-3, bias 7, no infinity,
+// largest finite 448; round to nearest even, saturating).  x / quantum is exact in fp32 (quantum is
+// a power of two), so rintf gives the correctly rounded result.
+__device__ __forceinline__ float quantize_message(float x, uint32_t msg_dtype)
+{
+    if (msg_dtype == 1u) return bf16_bits_to_f32(f32_to_bf16_bits(x));
+    if (msg_dtype == 2u) {
+        const float ax = fabsf(x);
+        if (!(ax > 0.0f)) return x;                                   // zero (and NaN) unchanged
+        int e = (int)((__float_as_uint(ax) >> 23) & 0xFFu) - 127;      // floor(log2 ax) for normal ax
+        e = e < -6 ? -6 : e;                                           // subnormal range: quantum 2^-9
+        const float quantum = __uint_as_float((uint32_t)(e - 3 + 127) << 23);
+        float r = rintf(ax / quantum) * quantum;
+        r = r > 448.0f ? 448.0f : r;
+        return copysignf(r, x);
+    }
+    return x;
+}
+
 __device__ __forceinline__ F4 load_bf16x4(const uint16_t *__restrict__ p, uint64_t mu, int nvalid)
 {
     F4 r;

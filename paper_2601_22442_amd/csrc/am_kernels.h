@@ -148,6 +148,7 @@ struct StepArgs {
     uint32_t do_send, do_recv, ema, same_slot;     // ema: a correction vector d is kept; same_slot: tau = 0,
                                                    // the average is of this step's w^
     uint32_t do_next;                              // also count the lines each tile will send next step
+    uint32_t msg_dtype;                            // precision of the exchanged values: 0 fp32, 1 bf16, 2 E4M3
     SubsetKey key_send, key_recv, key_next;
     uint32_t *next_lines;                          // [ntiles], written when do_next
     float *ring_send;                              // slot written now: [replica][line][32]
@@ -442,7 +443,7 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, uint32_t tile, uint
             for (int j = 0; j < 4; ++j)
                 if ((s.mask_recv >> j) & 1u) {
                     double sum = 0.;
-                    for (uint32_t i = 0; i < R; ++i) sum += (double)sent_lds[i * kTileCoords + c];
+                    for (uint32_t i = 0; i < R; ++i) sum += (double)quantize_message(sent_lds[i * kTileCoords + c], a.msg_dtype);
                     abar[j] = (float)(sum * inv_r);
                     ++c;
                 }

@@ -111,6 +111,7 @@ am_status check_config(const am_config *c)
     if (c->optimizer > AM_OPT_NADAMW) return fail(AM_EINVAL, "unknown optimizer %u", c->optimizer);
     if (c->correction > AM_CORR_EAGER) return fail(AM_EINVAL, "unknown correction %u", c->correction);
     if (c->fwd_dtype > AM_BF16 || c->grad_dtype > AM_BF16) return fail(AM_EINVAL, "unknown dtype");
+    if (c->msg_dtype > AM_MSG_E4M3) return fail(AM_EINVAL, "unknown msg_dtype %u", c->msg_dtype);
     if (c->subset_granule != 0 && c->subset_granule != 1 && c->subset_granule != 32) return fail(AM_EINVAL, "subset_granule=%u is not 1 or 32", c->subset_granule);
     if (!(c->beta1 >= 0.f && c->beta1 < 1.f)) return fail(AM_EINVAL, "beta1=%g not in [0, 1)", c->beta1);
     if (c->optimizer != AM_OPT_SGD && !(c->beta2 >= 0.f && c->beta2 < 1.f)) return fail(AM_EINVAL, "beta2=%g not in [0, 1)", c->beta2);
@@ -235,6 +236,7 @@ am_status fill_averaging(am_state *st, uint64_t t, float lambda_t, const Round &
     a.n = c.n; a.ntiles = st->lay.ntiles; a.replicas = c.replicas;
     a.cap_lines = (uint32_t)st->lay.cap_lines;
     a.ema = c.correction != AM_CORR_NONE;
+    a.msg_dtype = c.msg_dtype;
     if (c.correction == AM_CORR_EAGER) { a.coef_d = 0.0; a.coef_s = 1.0 / (double)c.replicas; }
     else { a.coef_d = 1.0 - (double)lambda_t; a.coef_s = (double)lambda_t; }
     a.do_send = r.send; a.do_recv = r.recv; a.same_slot = r.same_slot;

@@ -177,6 +177,12 @@ def test_block_granule_variant(amlib):
     run_steps(am, 4099, 8, 6, delay=1, fraction=1.0, seed=2, subset_granule=32)
 
 
+@pytest.mark.parametrize("msg", [O.MSG_BF16, O.MSG_E4M3])
+@pytest.mark.parametrize("tau", [0, 2])
+def test_quantised_exchange(amlib, msg, tau):
+    run_steps(amlib, 60_013, 4, 3 * (tau + 1) + 2, delay=tau, fraction=0.2, seed=14, msg_dtype=msg, lookahead=True, gamma=0.9)
+
+
 def test_eager_correction_mode(amlib):
     run_steps(amlib, 25_013, 4, 9, delay=2, fraction=1.0, seed=4, correction=O.CORR_EAGER)
     run_steps(amlib, 25_013, 3, 9, delay=1, avg_interval=2, fraction=0.3, seed=4, correction=O.CORR_EAGER,
