@@ -265,7 +265,10 @@ static double grad_value(const amo_state *s, const void *g, uint64_t k, double g
     return grad_scale * raw;
 }
 
-static void local_step(amo_state *s, uint64_t t, const void *const *grads, double lr, double grad_scale)
+/* replica_scale: NULL, or one more factor per replica on top of grad_scale (each replica clips by
+ * its own gradient norm) */
+static void local_step(amo_state *s, uint64_t t, const void *const *grads, double lr, double grad_scale,
+                       const float *replica_scale)
 {
     const amo_config *c = &s->c;
     const double b1 = c->beta1, b2 = c->beta2, eps = c->eps, wd = c->weight_decay;
@@ -283,7 +286,7 @@ static void local_step(amo_state *s, uint64_t t, const void *const *grads, doubl
         const void *g_i = grads[i];
         #pragma omp parallel for schedule(static)
         for (uint64_t k = 0; k < c->n; ++k) {
-            const double g = grad_value(s, g_i, k, grad_scale);
+            const double g = grad_value(s, g_i, k, replica_scale ? grad_scale * (double)replica_scale[i] : grad_scale);
             const double w_old = (double)w[k];
             wb[k] = w[k];
             double w_hat;
@@ -384,10 +387,21 @@ static void look_ahead(amo_state *s)
 
 /* one full step (1.-4.) ; grads = R pointers to n fp32 (or bf16) values ; returns 0, or -1 when
  * t is not last_t + 1 */
+int amo_step_scaled(amo_state *s, uint64_t t, const void *const *grads, double lr, double lambda,
+                    double grad_scale, const float *replica_scale)
+{
+    if (t != s->last_t + 1) return -1;
+    local_step(s, t, grads, lr, grad_scale, replica_scale);
+    sparse_average(s, t, lambda);
+    look_ahead(s);
+    s->last_t = t;
+    return 0;
+}
+
 int amo_step(amo_state *s, uint64_t t, const void *const *grads, double lr, double lambda, double grad_scale)
 {
     if (t != s->last_t + 1) return -1;
-    local_step(s, t, grads, lr, grad_scale);
+    local_step(s, t, grads, lr, grad_scale, NULL);
     sparse_average(s, t, lambda);
     look_ahead(s);
     s->last_t = t;
@@ -461,6 +475,18 @@ double amo_consensus_error(const amo_state *s)
             double e = (double)s->w[i][k] - mean;
             total += e * e;
         }
+    }
+    return total;
+}
+
+/* sum of squares of one gradient array (the stage's share of a replica's squared gradient norm,
+ * what global-norm clipping needs from every stage) */
+double amo_grad_sqnorm(const void *g, uint64_t n, uint32_t is_bf16)
+{
+    double total = 0.0;
+    for (uint64_t k = 0; k < n; ++k) {
+        double x = is_bf16 ? (double)amo_bf16_to_float(((const uint16_t *)g)[k]) : (double)((const float *)g)[k];
+        total += x * x;
     }
     return total;
 }

@@ -68,6 +68,9 @@ def lib():
             f.restype = C.POINTER(C.c_float)
         L.amo_step.argtypes = [C.c_void_p, C.c_uint64, C.POINTER(C.c_void_p), C.c_double, C.c_double, C.c_double]
         L.amo_step.restype = C.c_int
+        L.amo_step_scaled.argtypes = [C.c_void_p, C.c_uint64, C.POINTER(C.c_void_p), C.c_double, C.c_double, C.c_double, C.c_void_p]
+        L.amo_step_scaled.restype = C.c_int
+        L.amo_grad_sqnorm.argtypes = [C.c_void_p, C.c_uint64, C.c_uint32]; L.amo_grad_sqnorm.restype = C.c_double
         L.amo_sparse_average.argtypes = [C.c_void_p, C.c_uint64, C.c_double]; L.amo_sparse_average.restype = C.c_int
         L.amo_lookahead.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_double]
         L.amo_consensus_error.argtypes = [C.c_void_p]; L.amo_consensus_error.restype = C.c_double
@@ -117,6 +120,12 @@ def quantize_e4m3(x: float) -> float:
 
 def quantize_message(x: float, msg_dtype: int) -> float:
     return float(lib().amo_quantize_message(x, msg_dtype))
+
+
+def grad_sqnorm(g: np.ndarray) -> float:
+    """Sum of squares of a gradient array (fp32, or bf16 given as uint16 bit patterns)."""
+    g = np.ascontiguousarray(g)
+    return float(lib().amo_grad_sqnorm(g.ctypes.data, g.size, int(g.dtype == np.uint16)))
 
 
 def double_to_bf16(x: float) -> int:
@@ -186,12 +195,17 @@ class Oracle:
         for i in range(self.R):
             self.w(i)[:] = w0 if w0.ndim == 1 else w0[i]
 
-    def step(self, t, grads, lr, lam=0.5, grad_scale=1.0):
+    def step(self, t, grads, lr, lam=0.5, grad_scale=1.0, replica_scale=None):
         want = np.uint16 if self.cfg.grad_bf16 else np.float32
         keep = [np.ascontiguousarray(g, dtype=want) for g in grads]
         assert len(keep) == self.R and all(g.size == self.n for g in keep)
         ptrs = (C.c_void_p * self.R)(*[g.ctypes.data for g in keep])
-        rc = lib().amo_step(self._h, t, ptrs, f32(lr), f32(lam), f32(grad_scale))
+        if replica_scale is not None:
+            rs = np.ascontiguousarray(replica_scale, dtype=np.float32)
+            assert rs.size == self.R
+            rc = lib().amo_step_scaled(self._h, t, ptrs, f32(lr), f32(lam), f32(grad_scale), rs.ctypes.data)
+        else:
+            rc = lib().amo_step(self._h, t, ptrs, f32(lr), f32(lam), f32(grad_scale))
         if rc != 0:
             raise ValueError(f"oracle step out of order: t={t}")
 

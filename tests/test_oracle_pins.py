@@ -243,6 +243,25 @@ def test_grad_scale_and_bf16_grads():
     assert np.array_equal(c.w(0), e.w(0))
 
 
+def test_per_replica_scale_and_gradient_norm():
+    """Clipping support: a per-replica factor equals pre-scaled gradients; the squared norm is the
+    plain sum of squares."""
+    n, R = 700, 3
+    w0 = si.stage_weights(n, seed=50)
+    g = si.replica_grads(n, R, 1, seed=50)
+    scales = np.array([0.5, 0.25, 2.0], dtype=np.float32)           # dyadic: pre-scaling is exact
+    a = O.Oracle(n, R, fraction=EMPTY_P, optimizer=O.OPT_ADAMW)
+    b = O.Oracle(n, R, fraction=EMPTY_P, optimizer=O.OPT_ADAMW)
+    a.set_w(w0); b.set_w(w0)
+    a.step(1, g, 1e-3, replica_scale=scales)
+    b.step(1, [g[i] * scales[i] for i in range(R)], 1e-3)
+    for i in range(R):
+        assert np.array_equal(a.w(i), b.w(i)) and np.array_equal(a.v(i), b.v(i))
+    assert abs(O.grad_sqnorm(g[0]) - float(np.sum(g[0].astype(np.float64) ** 2))) < 1e-12 * O.grad_sqnorm(g[0])
+    gb = si.to_bf16_bits(g[1])
+    assert abs(O.grad_sqnorm(gb) - float(np.sum(si.bf16_bits_to_f32(gb).astype(np.float64) ** 2))) < 1e-12 * O.grad_sqnorm(gb)
+
+
 # --------------------------------------------------------------------------------------------
 # synchronous special cases of the averaging (tau = 0)
 # --------------------------------------------------------------------------------------------
