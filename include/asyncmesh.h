@@ -136,6 +136,17 @@ am_status am_init_state(const am_config *cfg, const am_buffers *buf, void *hip_s
 am_status am_step(am_state *st, uint64_t t, const void *const *grads,
                   float lr, float lambda_t, float grad_scale);
 
+/* am_step with one more gradient factor per replica, read from DEVICE memory (R floats) by the
+ * kernel: g_i <- grad_scale * replica_scale[i] * g_i.  For global-norm clipping (norm 1 in the
+ * paper's set-up) without a host round trip: am_grad_sqnorm gives the stage's share of each
+ * replica's squared norm, the caller turns the norms of all stages into factors on the device. */
+am_status am_step_scaled(am_state *st, uint64_t t, const void *const *grads, float lr, float lambda_t,
+                         float grad_scale, const float *dev_replica_scale);
+
+/* dev_out[i] (DEVICE, R doubles) = sum over the stage of g_i[mu]^2.  grads as for am_step.
+ * Deterministic (fixed reduction order). */
+am_status am_grad_sqnorm(am_state *st, const void *const *grads, double *dev_out);
+
 /* Parts (2)-(3) alone, acting on the current w, which plays the role of w^ (for callers that run
  * their own optimizer).  Counts as step t.  m, v, fwd are not touched. */
 am_status am_sparse_average(am_state *st, uint64_t t, float lambda_t);

@@ -21,7 +21,8 @@ F32, BF16 = 0, 1
 MSG_F32, MSG_BF16, MSG_E4M3 = 0, 1, 2
 
 EXPORTS = (
-    "am_workspace_bytes", "am_init_state", "am_step", "am_sparse_average", "am_lookahead",
+    "am_workspace_bytes", "am_init_state", "am_step", "am_step_scaled", "am_grad_sqnorm", "am_sparse_average",
+    "am_lookahead",
     "am_subset_indices", "am_set_delay", "am_diagnostics", "am_read_flags", "am_set_profiling", "am_get_profile", "am_ring_info",
     "am_destroy", "am_last_error", "am_version",
 )
@@ -65,6 +66,8 @@ def _load():
     L.am_workspace_bytes.argtypes = [C.POINTER(Config), C.POINTER(C.c_uint64)]
     L.am_init_state.argtypes = [C.POINTER(Config), C.POINTER(Buffers), C.c_void_p, C.POINTER(C.c_void_p)]
     L.am_step.argtypes = [C.c_void_p, C.c_uint64, C.POINTER(C.c_void_p), C.c_float, C.c_float, C.c_float]
+    L.am_step_scaled.argtypes = [C.c_void_p, C.c_uint64, C.POINTER(C.c_void_p), C.c_float, C.c_float, C.c_float, C.c_void_p]
+    L.am_grad_sqnorm.argtypes = [C.c_void_p, C.POINTER(C.c_void_p), C.c_void_p]
     L.am_sparse_average.argtypes = [C.c_void_p, C.c_uint64, C.c_float]
     L.am_lookahead.argtypes = [C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p, C.c_uint64, C.c_float, C.c_void_p]
     L.am_subset_indices.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint64, C.c_void_p]
@@ -174,6 +177,23 @@ class Stage:
         table = _ptr_table(grads)
         with torch.cuda.device(self.device):
             _check(lib.am_step(self._handle, t, table, lr, lambda_t, grad_scale))
+
+    def step_scaled(self, t: int, grads, lr: float, lambda_t: float, grad_scale: float, replica_scale: torch.Tensor):
+        """am_step_scaled: replica_scale is a device tensor of R fp32 factors."""
+        assert len(grads) == self.R and replica_scale.is_cuda and replica_scale.dtype == torch.float32
+        assert replica_scale.numel() == self.R and replica_scale.is_contiguous()
+        table = _ptr_table(grads)
+        with torch.cuda.device(self.device):
+            _check(lib.am_step_scaled(self._handle, t, table, lr, lambda_t, grad_scale, replica_scale.data_ptr()))
+
+    def grad_sqnorm(self, grads) -> torch.Tensor:
+        """am_grad_sqnorm: device tensor of R doubles, sum of squares of each replica's gradient."""
+        assert len(grads) == self.R
+        out = torch.empty(self.R, dtype=torch.float64, device=self.device)
+        table = _ptr_table(grads)
+        with torch.cuda.device(self.device):
+            _check(lib.am_grad_sqnorm(self._handle, table, out.data_ptr()))
+        return out
 
     def sparse_average(self, t: int, lambda_t: float = 0.5):
         with torch.cuda.device(self.device):

@@ -165,6 +165,7 @@ struct StepArgs {
     double a_m, b_m, a_v, b_v, c_wd, c_g, c_m, c_v, eps;
     uint32_t lookahead;
     double gamma;
+    const float *replica_scale;                    // NULL, or one more gradient factor per replica (DEVICE)
 };
 
 // Precision.  State is fp32 in memory (the method's precision).  The accumulating expressions
@@ -201,15 +202,17 @@ struct GroupIn {
 
 // Local optimizer step on one group, from loaded operands.
 template <int OPT>
-__device__ __forceinline__ void local_step(const StepArgs &a, const GroupIn &in, F4 &w_hat, F4 &m_new, F4 &v_new)
+__device__ __forceinline__ void local_step(const StepArgs &a, uint32_t i, const GroupIn &in,
+                                           F4 &w_hat, F4 &m_new, F4 &v_new)
 {
+    const double rs = (OPT != kOptNone && a.replica_scale) ? (double)a.replica_scale[i] : 1.0;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         if (OPT == kOptNone) {                                 // averaging only: the caller's w is w^
             w_hat.v[j] = in.w.v[j];
             continue;
         }
-        const double gj = (double)in.g.v[j];                   // grad_scale is folded into b_m, b_v, c_g
+        const double gj = rs * (double)in.g.v[j];              // grad_scale is folded into b_m, b_v, c_g
         const double wo = (double)in.w.v[j];
         double step;                                           // what is subtracted besides the decay
         if (OPT == kOptSgdPlain) {
@@ -275,7 +278,7 @@ __device__ __forceinline__ void step_replica(const StepArgs &a, uint32_t i, uint
                                              const float *sent_lds, float *send_lds)
 {
     F4 w_hat, m_new, v_new;
-    local_step<OPT>(a, in, w_hat, m_new, v_new);
+    local_step<OPT>(a, i, in, w_hat, m_new, v_new);
 
     if (s.lines_send) {
         // send: the tile's w^ values are gathered in LDS (the tail of the last line stays zero) and
@@ -424,7 +427,7 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, uint32_t tile, uint
                         if (OPT != kOptNone) load_group<OPT, GRAD_BF16>(a, i, mu, nvalid, pre);
                         load_group_sparse<OPT>(a, i, mu, nvalid, s, pre);
                     }
-                    local_step<OPT>(a, pre, w_hat, m_new, v_new);
+                    local_step<OPT>(a, i, pre, w_hat, m_new, v_new);
                     uint32_t c = s.rank_recv;
 #pragma unroll
                     for (int j = 0; j < 4; ++j)
@@ -575,6 +578,58 @@ k_diag_final(const double *__restrict__ partial, uint32_t nblocks, uint64_t n, d
         __syncthreads();
     }
     if (threadIdx.x == 0) { out3[0] = red[0][0]; out3[1] = red[1][0] / (double)n; out3[2] = red[2][0]; }
+}
+
+// =============================================================================================
+// Squared gradient norms (the stage's share of each replica's global norm, for clipping)
+// =============================================================================================
+struct NormArgs {
+    const void *g[kMaxReplicas];
+    uint64_t n;
+    uint32_t replicas;
+    uint32_t is_bf16;
+};
+
+// grid = (blocks, replicas); block (b, i) sums the squares of groups b, b + blocks, ... of replica i
+__global__ void __launch_bounds__(256)
+k_sqnorm_partial(const NormArgs a, double *__restrict__ partial)
+{
+    __shared__ double red[256];
+    const uint32_t i = blockIdx.y;
+    const uint64_t ngroups = (a.n + 3u) / 4u;
+    const uint64_t stride = (uint64_t)gridDim.x * 256u;
+    double acc = 0.;
+    for (uint64_t group = (uint64_t)blockIdx.x * 256u + threadIdx.x; group < ngroups; group += stride) {
+        const uint64_t mu = group * 4u;
+        const int nvalid = a.n - mu >= 4u ? 4 : (int)(a.n - mu);
+        const F4 g = a.is_bf16 ? load_bf16x4(static_cast<const uint16_t *>(a.g[i]), mu, nvalid)
+                               : load_f32x4(static_cast<const float *>(a.g[i]), mu, nvalid);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc += (double)g.v[j] * (double)g.v[j];     // tail entries are 0
+    }
+    red[threadIdx.x] = acc;
+    __syncthreads();
+    for (uint32_t off = 128; off > 0; off >>= 1) {
+        if (threadIdx.x < off) red[threadIdx.x] += red[threadIdx.x + off];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) partial[(uint64_t)i * gridDim.x + blockIdx.x] = red[0];
+}
+
+// one block per replica: fixed-order sum of its partials
+__global__ void __launch_bounds__(256)
+k_sqnorm_final(const double *__restrict__ partial, uint32_t nblocks, double *__restrict__ out)
+{
+    __shared__ double red[256];
+    double acc = 0.;
+    for (uint32_t b = threadIdx.x; b < nblocks; b += 256u) acc += partial[(uint64_t)blockIdx.x * nblocks + b];
+    red[threadIdx.x] = acc;
+    __syncthreads();
+    for (uint32_t off = 128; off > 0; off >>= 1) {
+        if (threadIdx.x < off) red[threadIdx.x] += red[threadIdx.x + off];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) out[blockIdx.x] = red[0];
 }
 
 }  // namespace am

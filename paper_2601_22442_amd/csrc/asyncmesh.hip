@@ -78,7 +78,7 @@ struct Layout {
     uint64_t off_flags, off_reduce, off_next, off_meta, meta_stride, meta_sb_off, off_ring, ring_stride, total;
 };
 
-// workspace = [flags 256 B][reduction partials 3 x 1024 doubles][next_lines u32[ntiles]][meta x (slots + 1)][ring values x slots]
+// workspace = [flags 256 B][reduction partials 32 x 1024 doubles][next_lines u32[ntiles]][meta x (slots + 1)][ring values x slots]
 //   meta    = local_off u32[ntiles] | sb_base u32[nsb + 1]         (the extra one serves am_subset_indices)
 //   ring    = R * cap_lines * 32 fp32: [replica][line][32]; a tile owns whole lines
 Layout make_layout(const am_config &c)
@@ -90,7 +90,7 @@ Layout make_layout(const am_config &c)
     L.cap_lines = slot_capacity_lines(L.ntiles, c.fraction, c.subset_granule == 32);
     L.off_flags = 0;
     L.off_reduce = 256;
-    L.off_next = L.off_reduce + 3 * 1024 * 8;
+    L.off_next = L.off_reduce + (uint64_t)AM_MAX_REPLICAS * 1024 * 8;
     L.off_meta = L.off_next + round_up((uint64_t)L.ntiles * 4, 256);
     L.meta_sb_off = round_up((uint64_t)L.ntiles * 4, 256);
     L.meta_stride = L.meta_sb_off + round_up(((uint64_t)L.nsb + 1) * 4, 256);
@@ -346,7 +346,37 @@ am_status am_init_state(const am_config *cfg, const am_buffers *buf, void *hip_s
 
 am_status am_step(am_state *st, uint64_t t, const void *const *grads, float lr, float lambda_t, float grad_scale)
 {
+    return am_step_scaled(st, t, grads, lr, lambda_t, grad_scale, nullptr);
+}
+
+am_status am_grad_sqnorm(am_state *st, const void *const *grads, double *dev_out)
+{
+    if (!st || !grads || !dev_out) return fail(AM_EINVAL, "NULL argument");
+    if (!aligned(dev_out, 8)) return fail(AM_EALIGN, "dev_out is not 8-byte aligned");
+    const am_config &c = st->cfg;
+    const uintptr_t galign = c.grad_dtype == AM_BF16 ? 8 : 16;
+    am::NormArgs a;
+    std::memset(&a, 0, sizeof a);
+    for (uint32_t i = 0; i < c.replicas; ++i) {
+        if (!grads[i]) return fail(AM_EINVAL, "grads[%u] is NULL", i);
+        if (!aligned(grads[i], galign)) return fail(AM_EALIGN, "grads[%u] is not %u-byte aligned", i, (unsigned)galign);
+        a.g[i] = grads[i];
+    }
+    a.n = c.n; a.replicas = c.replicas; a.is_bf16 = c.grad_dtype == AM_BF16;
+    const uint64_t want = ((c.n + 3) / 4 + 255) / 256;
+    const uint32_t blocks = (uint32_t)(want < 1024 ? want : 1024);
+    am::k_sqnorm_partial<<<dim3(blocks, c.replicas), 256, 0, st->stream>>>(a, st->reduce_partials());
+    AM_HIP(hipGetLastError());
+    am::k_sqnorm_final<<<c.replicas, 256, 0, st->stream>>>(st->reduce_partials(), blocks, dev_out);
+    AM_HIP(hipGetLastError());
+    return AM_OK;
+}
+
+am_status am_step_scaled(am_state *st, uint64_t t, const void *const *grads, float lr, float lambda_t,
+                         float grad_scale, const float *dev_replica_scale)
+{
     if (!st) return fail(AM_EINVAL, "state is NULL");
+    if (!aligned(dev_replica_scale, 4)) return fail(AM_EALIGN, "dev_replica_scale is not 4-byte aligned");
     if (!grads) return fail(AM_EINVAL, "grads is NULL");
     if (t != st->last_t + 1) return fail(AM_EORDER, "step %llu after step %llu", (unsigned long long)t, (unsigned long long)st->last_t);
     if (!(lambda_t >= 0.f && lambda_t <= 1.f)) return fail(AM_EINVAL, "lambda_t=%g not in [0, 1]", lambda_t);
@@ -365,6 +395,7 @@ am_status am_step(am_state *st, uint64_t t, const void *const *grads, float lr, 
         a.fwd[i] = st->fwd[i]; a.g[i] = grads[i];
     }
     a.lookahead = c.lookahead != 0; a.gamma = (double)c.gamma;
+    a.replica_scale = dev_replica_scale;
     const double gs = (double)grad_scale;        // folded into the coefficients that multiply g
 
     // per-step scalars, evaluated once in double

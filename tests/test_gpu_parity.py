@@ -183,6 +183,27 @@ def test_quantised_exchange(amlib, msg, tau):
     run_steps(amlib, 60_013, 4, 3 * (tau + 1) + 2, delay=tau, fraction=0.2, seed=14, msg_dtype=msg, lookahead=True, gamma=0.9)
 
 
+@pytest.mark.parametrize("bf16", [False, True])
+def test_clipping_by_each_replica_s_own_norm(amlib, bf16):
+    """Global-norm clipping at 1 without leaving the device: squared norms from am_grad_sqnorm, factors
+    min(1, 1/norm) formed on the device, applied per replica by am_step_scaled."""
+    n, R = 90_001, 4
+    st, orc = make_pair(amlib, n, R, delay=1, fraction=0.1, seed=33, grad_bf16=bf16, lookahead=True, gamma=0.9)
+    for t in range(1, 6):
+        g, gd = grads_for(n, R, t, 33, bf16)
+        g = [x * (np.float32(40.0 * (i + 1)) if not bf16 else 1) for i, x in enumerate(g)]      # norms around 1
+        if not bf16:
+            gd = [torch.from_numpy(x).cuda() for x in g]
+        sq = st.grad_sqnorm(gd)
+        want = np.array([O.grad_sqnorm(x) for x in g])
+        assert np.max(np.abs(sq.cpu().numpy() - want) / want) < 1e-12
+        scale = torch.clamp(1.0 / sq.sqrt(), max=1.0).to(torch.float32)
+        st.step_scaled(t, gd, 1e-3, 0.5, 1.0, scale)
+        orc.step(t, g, 1e-3, 0.5, 1.0, replica_scale=scale.cpu().numpy())
+        compare(st, orc, f"clipping t={t}")
+    assert bf16 or float(scale.min()) < 1.0                      # clipping was active
+
+
 def test_eager_correction_mode(amlib):
     run_steps(amlib, 25_013, 4, 9, delay=2, fraction=1.0, seed=4, correction=O.CORR_EAGER)
     run_steps(amlib, 25_013, 3, 9, delay=1, avg_interval=2, fraction=0.3, seed=4, correction=O.CORR_EAGER,
