@@ -278,24 +278,34 @@ def test_replicas_apart_from_the_start(amlib):
 # --------------------------------------------------------------------------------------------
 # full-size stage, sampled: the 125M-parameter configuration in the benchmark's launch shape
 # --------------------------------------------------------------------------------------------
+def _free_hbm() -> int:
+    """Free device memory after giving back what earlier tests left in torch's caching allocator."""
+    import gc
+    gc.collect()
+    torch.cuda.empty_cache()
+    return torch.cuda.mem_get_info()[0]
+
+
 def _tiled_dev(pool_dev, n, offset):
     reps = (n + offset) // pool_dev.numel() + 2
     return pool_dev.repeat(reps)[offset:offset + n].clone()
 
 
-def _full_size_case(am, n, R, tau, p, steps, windows, bf16=False, lookahead=True, seed=0):
+def _full_size_case(am, n, R, tau, p, steps, windows, bf16=False, lookahead=True, seed=0, optimizer=O.OPT_ADAMW,
+                    beta1=0.9):
     """Run `steps` fused steps of a full-size stage in the launch shape the benchmark times and compare
     windows of it with oracle instances that evaluate just those coordinate ranges (exact: the
     method is coordinate-wise given (seed, step, global coordinate))."""
     pool_n = 1 << 20
     w_pool = si.stage_weights(pool_n, seed)
     cfg = am.make_config(n, R, delay=tau, fraction=p, seed=seed, lookahead=lookahead, gamma=0.9,
+                         optimizer=optimizer, beta1=beta1,
                          fwd_dtype=am.BF16 if bf16 else am.F32, grad_dtype=am.BF16 if bf16 else am.F32)
     st = am.init_state(cfg, _tiled_dev(torch.from_numpy(w_pool).cuda(), n, 0))
     oracles = []
     for lo, ln in windows:
         orc = O.Oracle(ln, R, delay=tau, fraction=p, seed=seed, lookahead=lookahead, gamma=0.9, mu0=lo,
-                       fwd_bf16=bf16, grad_bf16=bf16)
+                       optimizer=optimizer, beta1=beta1, fwd_bf16=bf16, grad_bf16=bf16)
         orc.set_w(si.tiled(w_pool, ln, lo))
         oracles.append(orc)
     for t in range(1, steps + 1):
@@ -317,6 +327,8 @@ def _full_size_case(am, n, R, tau, p, steps, windows, bf16=False, lookahead=True
     for (lo, ln), orc in zip(windows, oracles):
         for i in range(R):
             for name in ("w", "m", "v", "d", "fwd"):
+                if getattr(st, name) is None:
+                    continue
                 got = getattr(st, name)[i][lo:lo + ln].float().cpu().numpy()
                 e = rel_err(got, getattr(orc, name)(i))
                 tol = TOL_BF16 if (bf16 and name == "fwd") else TOL_F32
@@ -348,10 +360,21 @@ def test_full_size_bf16_stage_on_sampled_windows(amlib):
 def test_full_size_1b_stage_on_sampled_windows(amlib):
     """10^9 fp32 params on one stage, R=8, staleness 4, 10 %, look-ahead + EMA (needs ~215 GB of HBM)."""
     n = 1_000_000_000
-    free, _ = torch.cuda.mem_get_info()
-    if free < 230e9:
+    if _free_hbm() < 230e9:
         pytest.skip("not enough free HBM for the 1B-parameter stage")
     _full_size_case(amlib, n, 8, 4, 0.10, 6, [(0, 40_000), (2 ** 29 - 20_000, 40_000), (n - 40_003, 40_003)])
+
+
+def test_largest_stage_the_library_accepts(amlib):
+    """n just under 2^32 - 2^20 (the documented limit): 64-bit addressing, 16.7 M tiles, windows at the
+    start, across 2^31 and at the very end (ragged tail).  Plain SGD, two replicas (about 120 GB)."""
+    n = (1 << 32) - (1 << 20) - 5
+    if _free_hbm() < 140e9:
+        pytest.skip("not enough free HBM for the largest stage")
+    _full_size_case(amlib, n, 2, 1, 0.002, 3, [(0, 30_000), ((1 << 31) - 15_000, 30_000), (n - 30_001, 30_001)],
+                    lookahead=False, optimizer=O.OPT_SGD, beta1=0.0)
+    with pytest.raises(amlib.AsyncMeshError):
+        amlib.workspace_bytes(amlib.make_config(n + 5, 2))
 
 
 # --------------------------------------------------------------------------------------------
