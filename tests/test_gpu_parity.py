@@ -265,6 +265,31 @@ def test_config_bf16_stage_reduced(amlib):
               grad_bf16=True)
 
 
+def test_wide_dynamic_range(amlib):
+    """Gradients over 24 decades (second moments down into the fp32 subnormals), weights over 8: the
+    refined square root / quotient and the fp64 accumulations must still land on the oracle's values."""
+    n, R, seed = 65_537, 3, 77
+    rng = np.random.default_rng(seed)
+    w0 = (rng.standard_normal(n) * 10.0 ** rng.uniform(-6, 2, n)).astype(np.float32)
+    st, orc = make_pair(amlib, n, R, w0=w0, delay=1, fraction=0.3, seed=seed, lookahead=True, gamma=0.9)
+    for t in range(1, 7):
+        g = [(rng.standard_normal(n) * 10.0 ** rng.uniform(-21, 3, n)).astype(np.float32) for _ in range(R)]
+        if t == 3:
+            g[0][::7] = 0.0                                     # exact zeros: v stays where it decays to
+        gd = [torch.from_numpy(x).cuda() for x in g]
+        st.step(t, gd, 1e-3, 0.5); orc.step(t, g, 1e-3, 0.5)
+        for i in range(R):
+            for name in ("w", "m", "v", "d", "fwd"):
+                got = getattr(st, name)[i].cpu().numpy(); ref = getattr(orc, name)(i)
+                assert np.all(np.isfinite(got)) and np.all(np.isfinite(ref))
+                # element-wise relative error with a floor of one fp32 subnormal step
+                err = np.abs(got.astype(np.float64) - ref.astype(np.float64)) / (np.abs(ref.astype(np.float64)) + 1.5e-45)
+                if name in ("m", "v"):
+                    assert np.max(err) < 1e-6, (t, i, name, float(np.max(err)))
+                else:
+                    assert rel_err(got, ref) < TOL_F32, (t, i, name)
+
+
 def test_replicas_apart_from_the_start(amlib):
     n, R = 9_001, 4
     w0 = np.stack([si.stage_weights(n, 40 + i) for i in range(R)])
