@@ -4,3 +4,4 @@ from .binding import (  # noqa: F401
     BF16, CORR_EAGER, CORR_EMA, CORR_NONE, F32, MAX_REPLICAS, MSG_BF16, MSG_E4M3, MSG_F32, OPT_ADAMW, OPT_NADAMW, OPT_SGD,
     AsyncMeshError, Config, Stage, init_state, lookahead, make_config, version, workspace_bytes,
 )
+from .schedules import ema_lambda, learning_rate  # noqa: F401,E402

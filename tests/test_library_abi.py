@@ -91,3 +91,18 @@ def test_init_rejects_bad_buffers_before_touching_the_device(amlib):
     assert B.lib.am_step(None, 1, None, 0.1, 0.5, 1.0) == -1
     assert B.lib.am_lookahead(None, 0, None, None, 4, 0.5, None) == -1
     assert B.lib.am_destroy(None) == 0
+
+
+def test_schedules_of_the_paper_s_setup(amlib):
+    am = amlib
+    T = 30_000
+    assert am.ema_lambda(1, T) == 0.5 and am.ema_lambda(1000, T) == 0.5
+    assert abs(am.ema_lambda(T, T) - 0.01) < 1e-15
+    assert abs(am.ema_lambda((1000 + T) // 2, T) - 0.255) < 1e-12             # cosine midpoint
+    lam = [am.ema_lambda(t, T) for t in range(1, T + 1)]
+    assert all(a >= b for a, b in zip(lam, lam[1:])) and 0.01 <= min(lam)
+    assert am.learning_rate(0, T) == 1e-7 and abs(am.learning_rate(3000, T) - 3e-4) < 1e-18
+    assert abs(am.learning_rate(1500, T) - (1e-7 + 3e-4) / 2) < 1e-15
+    assert abs(am.learning_rate(T, T) - 3e-5) < 1e-18
+    lr = [am.learning_rate(t, T) for t in range(3000, T + 1)]
+    assert all(a >= b for a, b in zip(lr, lr[1:]))
