@@ -6,13 +6,8 @@
 namespace am {
 
 // =============================================================================================
-// Subset offsets:   k_subset_count  ->  k_subset_scan
+// Subset offsets:   k_subset_count (or k_subset_offsets)  ->  k_subset_scan
 // =============================================================================================
-// One workgroup (4 waves) per superblock of 512 tiles.  Pure integer hashing, no array reads.
-// A tile's size is its number of selected coordinates (unit = 1: packed index lists) or that
-// number rounded up to whole 128-byte lines of 32 floats (unit = 32: ring slots, where every tile
-// owns whole lines).  Writes, per tile, the summed size of the tiles of the same superblock before
-// it (local_off) and, per superblock, its total (sb_sum).
 // cnt[512] (LDS) holds the sizes of the tiles of superblock blockIdx.x: write their exclusive
 // prefix to local_off and their total to sb_sum.  Called by all 256 threads after a barrier.
 __device__ __forceinline__ void scan_superblock(const uint32_t *cnt, uint32_t *wave_tot, uint32_t ntiles,
@@ -39,6 +34,11 @@ __device__ __forceinline__ void scan_superblock(const uint32_t *cnt, uint32_t *w
     if (threadIdx.x == 255) sb_sum[blockIdx.x] = base + incl;
 }
 
+// One workgroup (4 waves) per superblock of 512 tiles.  Pure integer hashing, no array reads.
+// A tile's size is its number of selected coordinates (unit = 1: packed index lists) or that
+// number rounded up to whole 128-byte lines of 32 floats (unit = 32: ring slots, where every tile
+// owns whole lines).  Writes, per tile, the summed size of the tiles of the same superblock before
+// it (local_off) and, per superblock, its total (sb_sum).
 __global__ void __launch_bounds__(256)
 k_subset_count(SubsetKey key, uint64_t n, uint32_t ntiles, uint32_t unit,
                uint32_t *__restrict__ local_off, uint32_t *__restrict__ sb_sum)
