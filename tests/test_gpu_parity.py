@@ -485,6 +485,31 @@ def test_step_order_and_argument_errors(amlib):
     assert slots == 2 and 4 * 32 <= cap <= 4 * 256           # 4 tiles, between 1 and 8 lines each
 
 
+def test_runs_on_the_stream_given_at_init(amlib):
+    """All work goes to the stream that was current at init_state (here a side stream)."""
+    n, R = 50_021, 4
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        st, orc = make_pair(amlib, n, R, delay=1, fraction=0.1, seed=9, lookahead=True, gamma=0.9)
+        for t in range(1, 6):
+            g, gd = grads_for(n, R, t, 9, False)
+            st.step(t, gd, 1e-3, 0.5); orc.step(t, g, 1e-3, 0.5)
+        side.synchronize()
+        compare(st, orc, "side stream")
+
+
+def test_two_states_do_not_interfere(amlib):
+    n, R = 30_011, 3
+    a, oa = make_pair(amlib, n, R, delay=1, fraction=0.2, seed=1)
+    b, ob = make_pair(amlib, n + 77, R + 1, delay=2, fraction=0.05, seed=2, lookahead=True, gamma=0.5)
+    for t in range(1, 7):
+        ga, gda = grads_for(n, R, t, 1, False)
+        gb, gdb = grads_for(n + 77, R + 1, t, 2, False)
+        a.step(t, gda, 1e-3, 0.5); b.step(t, gdb, 2e-3, 0.25)
+        oa.step(t, ga, 1e-3, 0.5); ob.step(t, gb, 2e-3, 0.25)
+    compare(a, oa, "state a"); compare(b, ob, "state b")
+
+
 def test_kernel_profiling_hooks(amlib):
     am = amlib
     n, R = 200_000, 2
