@@ -48,37 +48,83 @@ def tiled_on_device(torch, pool, n, offset):
     return pool.repeat(reps)[offset:offset + n].clone()
 
 
-def cpu_baseline(w, seconds_target=12.0):
-    """The oracle as it stands, on the host cores, on a slice of the same workload."""
+def sample_windows(n):
+    """Coordinate ranges on which the oracle replays the run: the whole stage when it is small, else its
+    head, an unaligned stretch in the middle and its tail."""
+    ln = 2_000_000
+    if n <= 3 * ln:
+        return [(0, n)]
+    return [(0, ln), (n // 2 - ln // 2 + 3, ln), (n - ln, ln)]
+
+
+def rel_err(got, ref):
+    """max |got - ref| over max(|ref|, rms(ref)), the measure the parity tests use."""
     import numpy as np
+    ref = ref.astype(np.float64)
+    scale = np.maximum(np.abs(ref), np.sqrt(np.mean(ref * ref)) if ref.size else 0.0)
+    scale = np.where(scale > 0, scale, 1.0)
+    return float(np.max(np.abs(got.astype(np.float64) - ref) / scale)) if ref.size else 0.0
+
+
+def cpu_baseline(w, args, st, gsets, steps_done, w_pool, seconds_target=12.0):
+    """The oracle as it stands, on the host cores, on windows of the same run: it replays the
+    steps_done steps the GPU has just made on those coordinate ranges with the same inputs (the
+    method is coordinate-wise given (seed, step, global coordinate), so a window is exact), is
+    compared with the GPU's state there, and then keeps stepping until about seconds_target of
+    timed work is done."""
+    import numpy as np
+    import torch
 
     import synth_inputs as si
     from oracle import oracle as O
 
-    R, tau, p = w["R"], w["tau"], w["p"]
-    ln = min(w["n"], 2_000_000)
-    orc = O.Oracle(ln, R, delay=tau, fraction=p, seed=0, lookahead=w["lookahead"], gamma=0.9,
-                   fwd_bf16=w["bf16"], grad_bf16=w["bf16"], mu0=0)
-    orc.set_w(si.stage_weights(ln, 0))
-    grads = si.replica_grads(ln, R, 1, 0)
-    if w["bf16"]:
-        grads = [si.to_bf16_bits(g) for g in grads]
-    t_used, done = 0.0, 0
-    t = 0
+    n, R, tau, p, bf16 = w["n"], w["R"], w["tau"], w["p"], w["bf16"]
+    windows = sample_windows(n)
+    oracles, grads = [], []
+    for lo, ln in windows:
+        orc = O.Oracle(ln, R, delay=tau, avg_interval=args.avg_interval, fraction=p, seed=0, lookahead=w["lookahead"],
+                       gamma=0.9, fwd_bf16=bf16, grad_bf16=bf16, mu0=lo, subset_granule=args.subset_granule,
+                       correction=O.CORR_NONE if args.no_correction else O.CORR_EMA)
+        orc.set_w(si.tiled(w_pool, ln, lo))
+        oracles.append(orc)
+        per_set = []
+        for gs in gsets:
+            sl = [g[lo:lo + ln] for g in gs]
+            per_set.append([(x.view(torch.int16).cpu().numpy().view(np.uint16) if bf16 else x.cpu().numpy()) for x in sl])
+        grads.append(per_set)
+    nsets = len(gsets)
+    coords = sum(ln for _, ln in windows)
+    t_used, done, t, worst = 0.0, 0, 0, None
     while True:
         t += 1
         t0 = time.perf_counter()
-        orc.step(t, grads, 3e-4, 0.5)
+        for orc, per_set in zip(oracles, grads):
+            orc.step(t, per_set[t % nsets], 3e-4, 0.5)
         dt = time.perf_counter() - t0
-        if t > tau + 1:                       # count only steps where send and receive are both live
+        if t > tau * args.avg_interval + 1:       # count only steps after the ring has filled
             t_used += dt
             done += 1
-        if t_used > seconds_target or t > 2000:
+        if t == steps_done:
+            worst = 0.0
+            for (lo, ln), orc in zip(windows, oracles):
+                for i in range(R):
+                    for name in ("w", "m", "v", "d", "fwd"):
+                        dev = getattr(st, name)
+                        if dev is None:
+                            continue
+                        e = rel_err(dev[i][lo:lo + ln].float().cpu().numpy(), getattr(orc, name)(i))
+                        tol = 1e-2 if (bf16 and name == "fwd") else 1e-6
+                        if e >= tol:
+                            raise SystemExit(f"bench.py: GPU and oracle disagree on {name}[{i}] in window {lo}: {e:.3e}")
+                        if not (bf16 and name == "fwd"):
+                            worst = max(worst, e)
+        if t >= steps_done and (t_used > seconds_target or t > steps_done + 2000):
             break
     return {
-        "value": R * ln * done / t_used, "unit": "params/s", "cores": O.threads(), "kind": "oracle",
-        "sample": f"first {ln} coordinates of the stage, all {R} replicas, {done} steps after start-up "
-                  f"({t_used:.1f} s of CPU time)",
+        "value": R * coords * done / t_used, "unit": "params/s", "cores": O.threads(), "kind": "oracle",
+        "sample": f"{len(windows)} windows ({coords} coordinates) of the stage, all {R} replicas, {done} steps after "
+                  f"start-up ({t_used:.1f} s of CPU time), same inputs as the GPU run",
+        "parity": {"steps_compared": steps_done, "windows": windows, "max_rel_err_fp32": worst, "tol_fp32": 1e-6},
     }
 
 
@@ -122,7 +168,8 @@ def main():
                          fwd_dtype=am.BF16 if w["bf16"] else am.F32,
                          grad_dtype=am.BF16 if w["bf16"] else am.F32)
     pool_n = 1 << 20
-    w_pool = torch.from_numpy(si.stage_weights(pool_n, 0)).to(dev)
+    w_pool_host = si.stage_weights(pool_n, 0)
+    w_pool = torch.from_numpy(w_pool_host).to(dev)
     st = am.init_state(cfg, tiled_on_device(torch, w_pool, n, 0))
     # two gradient sets per replica, cycled (traffic per step is unchanged); one set where two do not fit
     gsets = []
@@ -179,8 +226,7 @@ def main():
                      "kernel_ms": kernel_s * 1e3, "algorithmic_bytes_per_launch": bytes_per_launch},
     }
     if not args.skip_cpu:
-        del st, gsets
-        out["cpu_baseline"] = cpu_baseline(w)
+        out["cpu_baseline"] = cpu_baseline(w, args, st, gsets, t, w_pool_host)
     print(json.dumps(out))
 
 
