@@ -93,14 +93,45 @@ int amo_member(uint64_t seed, uint64_t s, uint64_t mu, uint64_t threshold, uint3
     return (uint64_t)x[mu & 3] < threshold;
 }
 
+/* Stratified VARIANT of the sampling (not the paper's independent draws; the exact-size alternative
+ * that keeps the marginal inclusion probability, which is all the sparse-averaging lemma uses):
+ * the coordinates are cut into aligned blocks of B = round(1/p) and exactly one coordinate of every
+ * block is in S^s, at offset floor(X B / 2^32) inside the block, X the generator word that
+ * coordinate number b = mu / B would get.  So |S^s| = ceil-or-floor(n / B) exactly and every
+ * coordinate is in S^s with probability 1/B (up to B / 2^32). */
+uint64_t amo_block_size(double p)
+{
+    if (!(p > 0.0)) return 0;
+    const long long B = llround(1.0 / p);
+    return B < 1 ? 1 : (uint64_t)B;
+}
+
+int amo_member_stratified(uint64_t seed, uint64_t s, uint64_t mu, uint64_t B)
+{
+    const uint64_t b = mu / B, group = b >> 2;
+    uint32_t counter[4] = { (uint32_t)group, (uint32_t)(group >> 32), (uint32_t)s, (uint32_t)(s >> 32) };
+    uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) };
+    uint32_t x[4];
+    amo_philox4x32_10(counter, key, x);
+    return mu - b * B == (((uint64_t)x[b & 3] * B) >> 32);
+}
+
+/* the sampling rule in force: independent draws (per coordinate or per aligned block of
+ * `granule`), or the stratified variant */
+static int in_subset(uint64_t seed, uint64_t s, uint64_t mu, double p, uint32_t granule, uint32_t stratified)
+{
+    if (stratified) return amo_member_stratified(seed, s, mu, amo_block_size(p));
+    return amo_member(seed, s, mu, amo_threshold(p), granule);
+}
+
 /* ascending list of the members of S^s inside [mu0, mu0+n); returns how many there are
  * (all of them are counted even when out_capacity is too small to hold them) */
 uint64_t amo_subset(uint64_t seed, uint64_t s, uint64_t mu0, uint64_t n, double p, uint32_t granule,
-                    uint64_t *out, uint64_t out_capacity)
+                    uint32_t stratified, uint64_t *out, uint64_t out_capacity)
 {
-    uint64_t T = amo_threshold(p), count = 0;
+    uint64_t count = 0;
     for (uint64_t k = 0; k < n; ++k)
-        if (amo_member(seed, s, mu0 + k, T, granule)) {
+        if (in_subset(seed, s, mu0 + k, p, granule, stratified)) {
             if (out && count < out_capacity) out[count] = mu0 + k;
             ++count;
         }
@@ -192,6 +223,8 @@ typedef struct {
     uint32_t msg_dtype;      /* AMO_MSG_*: precision of the exchanged values (the compression
                                 experiment: the average is formed from quantised values; a
                                 replica's own staleness term uses its own exact old value)  */
+    uint32_t stratified;     /* 1: the stratified sampling variant (one coordinate per block) */
+    uint32_t reserved;
 } amo_config;
 
 typedef struct {
@@ -345,11 +378,10 @@ static void sparse_average(amo_state *s, uint64_t t, double lambda)
     if (t < lag + 1) return;                          /* nothing was sent that long ago */
     const uint64_t sstep = t - lag;
     float **old = s->kept[sstep % s->nkept];
-    const uint64_t T = amo_threshold(c->fraction);
 
     #pragma omp parallel for schedule(static)
     for (uint64_t k = 0; k < n; ++k) {
-        if (!amo_member(c->seed, sstep, c->mu0 + k, T, c->granule)) continue;
+        if (!in_subset(c->seed, sstep, c->mu0 + k, c->fraction, c->granule, c->stratified)) continue;
         double sum = 0.0;
         for (uint32_t i = 0; i < R; ++i) sum += amo_quantize_message(old[i][k], c->msg_dtype);
         const float abar = (float)(sum / (double)R);              /* old average, an fp32 message */

@@ -42,6 +42,7 @@ class _Config(C.Structure):
         ("fwd_bf16", C.c_uint32), ("grad_bf16", C.c_uint32),
         ("momentum_decay", C.c_double),
         ("granule", C.c_uint32), ("msg_dtype", C.c_uint32),
+        ("stratified", C.c_uint32), ("reserved", C.c_uint32),
     ]
 
 
@@ -56,8 +57,11 @@ def lib():
         L.amo_philox4x32_10.argtypes = [C.POINTER(C.c_uint32), C.POINTER(C.c_uint32), C.POINTER(C.c_uint32)]
         L.amo_threshold.argtypes = [C.c_double]; L.amo_threshold.restype = C.c_uint64
         L.amo_member.argtypes = [C.c_uint64, C.c_uint64, C.c_uint64, C.c_uint64, C.c_uint32]; L.amo_member.restype = C.c_int
-        L.amo_subset.argtypes = [C.c_uint64, C.c_uint64, C.c_uint64, C.c_uint64, C.c_double, C.c_uint32, C.c_void_p, C.c_uint64]
+        L.amo_subset.argtypes = [C.c_uint64, C.c_uint64, C.c_uint64, C.c_uint64, C.c_double, C.c_uint32, C.c_uint32,
+                                 C.c_void_p, C.c_uint64]
         L.amo_subset.restype = C.c_uint64
+        L.amo_block_size.argtypes = [C.c_double]; L.amo_block_size.restype = C.c_uint64
+        L.amo_member_stratified.argtypes = [C.c_uint64] * 4; L.amo_member_stratified.restype = C.c_int
         L.amo_bf16_to_float.argtypes = [C.c_uint16]; L.amo_bf16_to_float.restype = C.c_float
         L.amo_double_to_bf16.argtypes = [C.c_double]; L.amo_double_to_bf16.restype = C.c_uint16
         L.amo_create.argtypes = [C.POINTER(_Config)]; L.amo_create.restype = C.c_void_p
@@ -104,13 +108,22 @@ def member(seed: int, s: int, mu: int, p: float, granule: int = 1) -> bool:
     return bool(lib().amo_member(seed, s, mu, threshold(p), granule))
 
 
-def subset(seed: int, s: int, n: int, p: float, mu0: int = 0, granule: int = 1) -> np.ndarray:
+def block_size(p: float) -> int:
+    """B = round(1/p) of the stratified sampling variant."""
+    return int(lib().amo_block_size(p))
+
+
+def member_stratified(seed: int, s: int, mu: int, p: float) -> bool:
+    return bool(lib().amo_member_stratified(seed, s, mu, block_size(p)))
+
+
+def subset(seed: int, s: int, n: int, p: float, mu0: int = 0, granule: int = 1, stratified: bool = False) -> np.ndarray:
     """Ascending global indices of S^s inside [mu0, mu0+n)."""
     L = lib()
-    count = L.amo_subset(seed, s, mu0, n, p, granule, None, 0)
+    count = L.amo_subset(seed, s, mu0, n, p, granule, int(stratified), None, 0)
     out = np.empty(count, dtype=np.uint64)
     if count:
-        L.amo_subset(seed, s, mu0, n, p, granule, out.ctypes.data, count)
+        L.amo_subset(seed, s, mu0, n, p, granule, int(stratified), out.ctypes.data, count)
     return out
 
 
@@ -154,13 +167,14 @@ class Oracle:
     def __init__(self, n, replicas, delay=0, avg_interval=1, fraction=0.05, seed=0,
                  optimizer=OPT_ADAMW, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01,
                  lookahead=False, gamma=0.0, correction=CORR_EMA, fwd_bf16=False, grad_bf16=False,
-                 momentum_decay=0.004, mu0=0, subset_granule=1, msg_dtype=MSG_F32):
+                 momentum_decay=0.004, mu0=0, subset_granule=1, msg_dtype=MSG_F32, stratified=False):
         self.cfg = _Config(
             n=n, mu0=mu0, replicas=replicas, delay=delay, avg_interval=avg_interval, optimizer=optimizer,
             fraction=fraction, seed=seed, beta1=f32(beta1), beta2=f32(beta2), eps=f32(eps),
             weight_decay=f32(weight_decay), gamma=f32(gamma), lookahead=int(bool(lookahead)),
             correction=correction, fwd_bf16=int(bool(fwd_bf16)), grad_bf16=int(bool(grad_bf16)),
-            momentum_decay=momentum_decay, granule=subset_granule, msg_dtype=msg_dtype)
+            momentum_decay=momentum_decay, granule=subset_granule, msg_dtype=msg_dtype,
+            stratified=int(bool(stratified)), reserved=0)
         self.n, self.R = n, replicas
         self._h = lib().amo_create(C.byref(self.cfg))
         if not self._h:

@@ -106,6 +106,48 @@ def test_block_granule_variant_keeps_the_marginal_probability():
     assert np.array_equal(np.stack([orc.w(i) for i in range(R)]), want)
 
 
+def test_stratified_variant_has_exact_size_and_the_marginal_probability():
+    """Variant (not the paper's independent draws): one coordinate out of every aligned block of
+    B = round(1/p).  Exact size, offsets written out from the generator word of block b, every
+    offset equally likely, and the averaging itself unchanged."""
+    assert [O.block_size(p) for p in (1.0, 0.5, 0.3, 0.05, 0.01, 1e-3)] == [1, 2, 3, 20, 100, 1000]
+    seed, s, p = 21, 6, 0.05
+    B = 20
+    for n in (20 * 500, 20 * 500 + 7):
+        S = O.subset(seed, s, n, p, stratified=True).astype(np.int64)
+        full = n // B
+        assert np.array_equal(S[:full] // B, np.arange(full))            # exactly one per full block
+        assert S.size in (full, full + (1 if n % B else 0))              # the cut block may or may not reach its member
+        for b in (0, 1, 2, 3, 4, 77, full - 1):                          # offset = floor(X_b B / 2^32)
+            g = b >> 2
+            x = O.philox4x32_10((g, 0, s, 0), (seed, 0))
+            assert S[b] - b * B == (x[b & 3] * B) >> 32
+        lo, ln = 4099, 3001                                              # a slice sees the same global subset
+        assert np.array_equal(O.subset(seed, s, ln, p, mu0=lo, stratified=True).astype(np.int64), S[(S >= lo) & (S < lo + ln)])
+    assert np.array_equal(O.subset(3, 9, 777, 1.0, stratified=True), np.arange(777, dtype=np.uint64))   # B = 1: everything
+    # offsets are uniform over the block: chi-square over 20 cells, 40 steps x 5000 blocks
+    n = B * 5000
+    cells = np.zeros(B)
+    for t in range(1, 41):
+        cells += np.bincount(O.subset(seed, t, n, p, stratified=True).astype(np.int64) % B, minlength=B)
+    expect = 40 * 5000 / B
+    chi2 = float(np.sum((cells - expect) ** 2 / expect))
+    assert chi2 < 60.0                                                   # 19 degrees of freedom: P(chi2 > 60) ~ 4e-6
+    assert not np.array_equal(O.subset(seed, 1, n, p, stratified=True), O.subset(seed, 2, n, p, stratified=True))
+    # subset coordinates take the mean (tau = 0), the rest keep the local step
+    R, lr, n = 3, O.f32(0.25), 10_007
+    w0 = np.stack([si.stage_weights(n, seed=70 + i) for i in range(R)])
+    orc = O.Oracle(n, R, delay=0, fraction=p, seed=seed, optimizer=O.OPT_SGD, beta1=0.0, weight_decay=0.0, stratified=True)
+    orc.set_w(w0)
+    g = np.stack(si.replica_grads(n, R, 1, seed=10))
+    what = (w0.astype(np.float64) - lr * g.astype(np.float64)).astype(np.float32)
+    want = what.copy()
+    S1 = O.subset(seed, 1, n, p, stratified=True).astype(np.int64)
+    want[:, S1] = what[:, S1].astype(np.float64).mean(axis=0).astype(np.float32)
+    orc.step(1, list(g), lr)
+    assert np.array_equal(np.stack([orc.w(i) for i in range(R)]), want)
+
+
 # --------------------------------------------------------------------------------------------
 # bf16 helpers against a library conversion
 # --------------------------------------------------------------------------------------------
