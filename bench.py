@@ -84,6 +84,7 @@ def cpu_baseline(w, args, st, gsets, steps_done, w_pool, seconds_target=12.0):
     for lo, ln in windows:
         orc = O.Oracle(ln, R, delay=tau, avg_interval=args.avg_interval, fraction=p, seed=0, lookahead=w["lookahead"],
                        gamma=0.9, fwd_bf16=bf16, grad_bf16=bf16, mu0=lo, subset_granule=args.subset_granule,
+                       subset_kind=O.SUBSET_STRATIFIED if args.subset_kind == "stratified" else O.SUBSET_BERNOULLI,
                        correction=O.CORR_NONE if args.no_correction else O.CORR_EMA)
         orc.set_w(si.tiled(w_pool, ln, lo))
         oracles.append(orc)
@@ -141,6 +142,8 @@ def main():
     ap.add_argument("--no-correction", action="store_true", help="plain delayed averaging (no EMA vector)")
     ap.add_argument("--subset-granule", type=int, default=1, choices=(1, 32),
                     help="1: coordinates drawn independently (the paper); 32: variant, whole 128-byte lines drawn")
+    ap.add_argument("--subset-kind", default="bernoulli", choices=("bernoulli", "stratified"),
+                    help="bernoulli: independent draws (the paper); stratified: variant, one coordinate per block of round(1/p)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (replicas are simulated as HBM-resident copies on it); "
@@ -164,6 +167,7 @@ def main():
     cfg = am.make_config(n, R, delay=tau, avg_interval=args.avg_interval, fraction=p, seed=0, optimizer=am.OPT_ADAMW,
                          correction=am.CORR_NONE if args.no_correction else am.CORR_EMA,
                          subset_granule=args.subset_granule,
+                         subset_kind=am.SUBSET_STRATIFIED if args.subset_kind == "stratified" else am.SUBSET_BERNOULLI,
                          lookahead=w["lookahead"], gamma=0.9,
                          fwd_dtype=am.BF16 if w["bf16"] else am.F32,
                          grad_dtype=am.BF16 if w["bf16"] else am.F32)
@@ -218,7 +222,7 @@ def main():
                    "n": n, "replicas": R, "delay": tau, "fraction": p, "lookahead": w["lookahead"],
                    "avg_interval": args.avg_interval,
                    "correction": "none" if args.no_correction else "ema",
-                   "subset_granule": args.subset_granule, "bf16": w["bf16"], "algorithmic_bytes_per_param": bpp},
+                   "subset_granule": args.subset_granule, "subset_kind": args.subset_kind, "bf16": w["bf16"], "algorithmic_bytes_per_param": bpp},
         "step_GBps": bytes_per_launch / (elapsed / args.steps) / 1e9,
         "step_frac_of_hbm_peak": bytes_per_launch / (elapsed / args.steps) / 1e9 / HBM_PEAK_GBPS,
         "roofline": {"kernel": "k_step", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS,

@@ -77,6 +77,18 @@ typedef enum {
     AM_MSG_E4M3 = 2     /* 8-bit float 1-4-3, bias 7, no infinity, max 448; nearest even, saturating */
 } am_msg;
 
+/* How the subset S^t is drawn.  BERNOULLI is the paper's sampling model (Section 3.2; the
+ * sparse-averaging lemma of the appendix: every element in the subset with probability p,
+ * independently).  STRATIFIED is a VARIANT with an exact subset size: the coordinates are cut into
+ * aligned blocks of B = round(1/p) and exactly one coordinate of every block is in S^t, at offset
+ * floor(X_b B / 2^32), X_b the generator word that coordinate number b = mu / B would get in the
+ * Bernoulli scheme.  Every coordinate is in S^t with probability 1/B (the marginal the lemma's
+ * proof uses), |S^t| = n / B up to the cut last block, and no ring slot can overflow. */
+typedef enum {
+    AM_SUBSET_BERNOULLI  = 0,
+    AM_SUBSET_STRATIFIED = 1
+} am_subset;
+
 typedef struct {
     uint64_t n;              /* d_j: parameters of the stage, per replica; 1 <= n < 2^32 - 2^20          */
     uint32_t replicas;       /* m = R, 1 .. AM_MAX_REPLICAS                                              */
@@ -97,6 +109,8 @@ typedef struct {
                                 128-byte line) drawn as a whole, block b in place of coordinate b in
                                 the generator; same inclusion probability p per coordinate.         */
     uint32_t msg_dtype;      /* am_msg: precision of the exchanged subset values                        */
+    uint32_t subset_kind;    /* am_subset: how S^t is drawn                                             */
+    uint32_t reserved;       /* set to 0                                                                */
 } am_config;
 
 /* The subset: S^t = { mu in [0, n) : X(seed, t, mu) < floor(p * 2^32) }, X = word (mu & 3) of

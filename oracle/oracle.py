@@ -18,6 +18,7 @@ _LIB = _HERE / "libasyncmesh_oracle.so"
 
 OPT_SGD, OPT_ADAMW, OPT_NADAMW = 0, 1, 2
 CORR_NONE, CORR_EMA, CORR_EAGER = 0, 1, 2
+SUBSET_BERNOULLI, SUBSET_STRATIFIED = 0, 1
 MSG_F32, MSG_BF16, MSG_E4M3 = 0, 1, 2
 
 
@@ -167,14 +168,14 @@ class Oracle:
     def __init__(self, n, replicas, delay=0, avg_interval=1, fraction=0.05, seed=0,
                  optimizer=OPT_ADAMW, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01,
                  lookahead=False, gamma=0.0, correction=CORR_EMA, fwd_bf16=False, grad_bf16=False,
-                 momentum_decay=0.004, mu0=0, subset_granule=1, msg_dtype=MSG_F32, stratified=False):
+                 momentum_decay=0.004, mu0=0, subset_granule=1, msg_dtype=MSG_F32, subset_kind=SUBSET_BERNOULLI):
         self.cfg = _Config(
             n=n, mu0=mu0, replicas=replicas, delay=delay, avg_interval=avg_interval, optimizer=optimizer,
             fraction=fraction, seed=seed, beta1=f32(beta1), beta2=f32(beta2), eps=f32(eps),
             weight_decay=f32(weight_decay), gamma=f32(gamma), lookahead=int(bool(lookahead)),
             correction=correction, fwd_bf16=int(bool(fwd_bf16)), grad_bf16=int(bool(grad_bf16)),
             momentum_decay=momentum_decay, granule=subset_granule, msg_dtype=msg_dtype,
-            stratified=int(bool(stratified)), reserved=0)
+            stratified=int(subset_kind == SUBSET_STRATIFIED), reserved=0)
         self.n, self.R = n, replicas
         self._h = lib().amo_create(C.byref(self.cfg))
         if not self._h:

@@ -19,6 +19,7 @@ OPT_SGD, OPT_ADAMW, OPT_NADAMW = 0, 1, 2
 CORR_NONE, CORR_EMA, CORR_EAGER = 0, 1, 2
 F32, BF16 = 0, 1
 MSG_F32, MSG_BF16, MSG_E4M3 = 0, 1, 2
+SUBSET_BERNOULLI, SUBSET_STRATIFIED = 0, 1
 
 EXPORTS = (
     "am_workspace_bytes", "am_init_state", "am_step", "am_step_scaled", "am_grad_sqnorm", "am_sparse_average",
@@ -45,6 +46,7 @@ class Config(C.Structure):
         ("lookahead", C.c_uint32), ("correction", C.c_uint32), ("fwd_dtype", C.c_uint32), ("grad_dtype", C.c_uint32),
         ("momentum_decay", C.c_double),
         ("subset_granule", C.c_uint32), ("msg_dtype", C.c_uint32),
+        ("subset_kind", C.c_uint32), ("reserved", C.c_uint32),
     ]
 
 
@@ -102,12 +104,12 @@ def version() -> str:
 def make_config(n, replicas, delay=0, avg_interval=1, fraction=0.05, seed=0, optimizer=OPT_ADAMW,
                 beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01, lookahead=False, gamma=0.0,
                 correction=CORR_EMA, fwd_dtype=F32, grad_dtype=F32, momentum_decay=0.004,
-                subset_granule=1, msg_dtype=MSG_F32) -> Config:
+                subset_granule=1, msg_dtype=MSG_F32, subset_kind=SUBSET_BERNOULLI) -> Config:
     return Config(n=n, replicas=replicas, delay=delay, avg_interval=avg_interval, optimizer=optimizer,
                   fraction=fraction, seed=seed, beta1=beta1, beta2=beta2, eps=eps, weight_decay=weight_decay,
                   gamma=gamma, lookahead=int(bool(lookahead)), correction=correction,
                   fwd_dtype=fwd_dtype, grad_dtype=grad_dtype, momentum_decay=momentum_decay,
-                  subset_granule=subset_granule, msg_dtype=msg_dtype)
+                  subset_granule=subset_granule, msg_dtype=msg_dtype, subset_kind=subset_kind, reserved=0)
 
 
 def workspace_bytes(cfg: Config) -> int:

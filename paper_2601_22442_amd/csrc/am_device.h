@@ -46,15 +46,46 @@ struct SubsetKey {
     uint32_t seed_lo, seed_hi;   // Philox key
     uint32_t step_lo, step_hi;   // counter words 2, 3
     uint64_t threshold;          // floor(p 2^32); 2^32 selects everything
-    uint32_t by_line;            // 0: every coordinate drawn on its own; 1: aligned blocks of 32 drawn as a whole
-    uint32_t pad_;
+    uint32_t mode;               // kDrawCoordinate, kDrawLine or kDrawStratified
+    uint32_t block;              // kDrawStratified: B, the block length
 };
+constexpr uint32_t kDrawCoordinate = 0;   // every coordinate drawn on its own
+constexpr uint32_t kDrawLine = 1;         // aligned blocks of 32 coordinates drawn as a whole
+constexpr uint32_t kDrawStratified = 2;   // exactly one coordinate of every aligned block of B
 
 // 4-bit membership mask of the coordinates 4*group .. 4*group+3 (bit j = coordinate 4*group+j),
 // restricted to the first nvalid of them.
 __device__ __forceinline__ uint32_t member_mask(const SubsetKey &k, uint64_t group, int nvalid)
 {
-    if (k.by_line) {
+    if (k.mode == kDrawStratified) {
+        // coordinate mu is selected iff mu - b B == floor(X_b B / 2^32), b = mu / B, X_b the word
+        // coordinate number b would get.  The four coordinates of a group lie in at most four
+        // consecutive blocks, hence in at most two generator counters.
+        const uint32_t B = k.block, mu0 = (uint32_t)(group << 2);
+        uint32_t b = mu0 / B, r = mu0 - b * B;
+        uint32_t b_last = b, r_last = r;                      // block of the group's last coordinate
+#pragma unroll
+        for (int j = 0; j < 3; ++j)
+            if (++r_last == B) { r_last = 0; ++b_last; }
+        const uint32_t c_first = b >> 2, c_last = b_last >> 2;
+        const U4 xa = philox4x32_10(c_first, 0u, k.step_lo, k.step_hi, k.seed_lo, k.seed_hi);
+        U4 xb = xa;
+        if (c_last != c_first) xb = philox4x32_10(c_last, 0u, k.step_lo, k.step_hi, k.seed_lo, k.seed_hi);
+        uint32_t m = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const bool first = (b >> 2) == c_first;
+            const uint32_t w0 = first ? xa.x0 : xb.x0, w1 = first ? xa.x1 : xb.x1;
+            const uint32_t w2 = first ? xa.x2 : xb.x2, w3 = first ? xa.x3 : xb.x3;
+            const uint32_t q = b & 3u;
+            const uint32_t word = q == 0u ? w0 : q == 1u ? w1 : q == 2u ? w2 : w3;
+            const uint32_t pick = (uint32_t)(((uint64_t)word * B) >> 32);
+            m |= (r == pick) ? (1u << j) : 0u;
+            if (++r == B) { r = 0; ++b; }
+        }
+        return m & ((1u << nvalid) - 1u);
+    }
+    if (k.mode == kDrawLine) {
         // block b = 32 coordinates = 8 groups takes the place of coordinate b in the generator
         const uint64_t b = group >> 3, bg = b >> 2;
         const U4 x = philox4x32_10((uint32_t)bg, (uint32_t)(bg >> 32), k.step_lo, k.step_hi, k.seed_lo, k.seed_hi);

@@ -5,6 +5,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -47,13 +48,24 @@ uint64_t subset_threshold(double p)
     return (uint64_t)std::floor(p * 4294967296.0);
 }
 
+// B = round(1/p) of the stratified sampling variant
+uint64_t stratified_block(double p)
+{
+    const long long B = std::llround(1.0 / p);
+    return B < 1 ? 1 : (uint64_t)B;
+}
+
 // Lines (of 32 floats) one replica's part of a ring slot must hold.  Every tile of 256
 // coordinates owns ceil(X / 32) whole lines, X ~ Binomial(256, p) its number of selected
 // coordinates; the slot has room for the expected total plus twelve standard deviations.
-uint64_t slot_capacity_lines(uint64_t ntiles, double p, bool by_line)
+uint64_t slot_capacity_lines(uint64_t ntiles, double p, bool by_line, uint64_t block)
 {
     const uint64_t all = ntiles * (am::kTileCoords / am::kLineFloats);
     if (p >= 1.0) return all;
+    if (block) {                         // stratified: a tile meets at most floor(255 / B) + 2 blocks, one member each: no chance involved
+        const uint64_t members = std::min<uint64_t>(am::kTileCoords, (am::kTileCoords - 1) / block + 2);
+        return std::min(all, ntiles * ((members + am::kLineFloats - 1) / am::kLineFloats));
+    }
     if (by_line) {                       // every line of a tile is drawn as a whole: Binomial(8, p) lines
         const double per = am::kTileCoords / am::kLineFloats;
         const double cap = std::ceil((double)ntiles * per * p + 12.0 * std::sqrt((double)ntiles * per * p * (1.0 - p))) + 64.0;
@@ -87,7 +99,8 @@ Layout make_layout(const am_config &c)
     L.ntiles = (uint32_t)((c.n + am::kTileCoords - 1) / am::kTileCoords);
     L.nsb = (L.ntiles + am::kTilesPerSuperblock - 1) / am::kTilesPerSuperblock;
     L.slots = c.delay + 1;
-    L.cap_lines = slot_capacity_lines(L.ntiles, c.fraction, c.subset_granule == 32);
+    L.cap_lines = slot_capacity_lines(L.ntiles, c.fraction, c.subset_granule == 32,
+                                      c.subset_kind == AM_SUBSET_STRATIFIED ? stratified_block(c.fraction) : 0);
     L.off_flags = 0;
     L.off_reduce = 256;
     L.off_next = L.off_reduce + (uint64_t)AM_MAX_REPLICAS * 1024 * 8;
@@ -113,6 +126,9 @@ am_status check_config(const am_config *c)
     if (c->fwd_dtype > AM_BF16 || c->grad_dtype > AM_BF16) return fail(AM_EINVAL, "unknown dtype");
     if (c->msg_dtype > AM_MSG_E4M3) return fail(AM_EINVAL, "unknown msg_dtype %u", c->msg_dtype);
     if (c->subset_granule != 0 && c->subset_granule != 1 && c->subset_granule != 32) return fail(AM_EINVAL, "subset_granule=%u is not 1 or 32", c->subset_granule);
+    if (c->subset_kind > AM_SUBSET_STRATIFIED) return fail(AM_EINVAL, "unknown subset_kind %u", c->subset_kind);
+    if (c->subset_kind == AM_SUBSET_STRATIFIED && c->subset_granule == 32) return fail(AM_EINVAL, "the stratified subset has no line-granular form (subset_granule must be 1)");
+    if (c->subset_kind == AM_SUBSET_STRATIFIED && stratified_block(c->fraction) > (1ull << 31)) return fail(AM_EINVAL, "fraction=%g gives a block longer than 2^31", c->fraction);
     if (!(c->beta1 >= 0.f && c->beta1 < 1.f)) return fail(AM_EINVAL, "beta1=%g not in [0, 1)", c->beta1);
     if (c->optimizer != AM_OPT_SGD && !(c->beta2 >= 0.f && c->beta2 < 1.f)) return fail(AM_EINVAL, "beta2=%g not in [0, 1)", c->beta2);
     if (c->optimizer != AM_OPT_SGD && !(c->eps >= 0.f)) return fail(AM_EINVAL, "eps=%g negative", c->eps);
@@ -160,8 +176,9 @@ am::SubsetKey make_key(const am_state *st, uint64_t step)
     k.step_lo = (uint32_t)step;
     k.step_hi = (uint32_t)(step >> 32);
     k.threshold = st->threshold;
-    k.by_line = st->cfg.subset_granule == 32 ? 1u : 0u;
-    k.pad_ = 0;
+    k.mode = st->cfg.subset_kind == AM_SUBSET_STRATIFIED ? am::kDrawStratified
+           : st->cfg.subset_granule == 32 ? am::kDrawLine : am::kDrawCoordinate;
+    k.block = st->cfg.subset_kind == AM_SUBSET_STRATIFIED ? (uint32_t)stratified_block(st->cfg.fraction) : 0u;
     return k;
 }
 

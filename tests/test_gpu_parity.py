@@ -176,6 +176,38 @@ def test_block_granule_variant(amlib):
     run_steps(am, 1000, 3, 6, delay=0, fraction=0.3, seed=2, subset_granule=32)
     run_steps(am, 4099, 8, 6, delay=1, fraction=1.0, seed=2, subset_granule=32)
 
+@pytest.mark.parametrize("p", [0.05, 0.3, 1.0 / 256, 1.0 / 1000, 1.0])
+def test_stratified_variant(amlib, p):
+    """Variant sampling: exactly one coordinate of every aligned block of round(1/p) (indices bit-exact,
+    state to the fp32 bar); block lengths below, at and above the tile length, and a cut last block."""
+    am = amlib
+    n, seed = 300_007, 5
+    st, orc = run_steps(am, n, 4, 8, delay=2, fraction=p, seed=seed, subset_kind=am.SUBSET_STRATIFIED,
+                        lookahead=True, gamma=0.9)
+    B = O.block_size(p)
+    for t in (1, 5, (1 << 33) + 2):
+        idx, k = st.subset_indices(t)
+        want = O.subset(seed, t, n, p, stratified=True)
+        assert k == want.size and np.array_equal(idx.cpu().numpy().astype(np.uint64), want)
+        assert n // B <= k <= n // B + 1
+    run_steps(am, 1000, 3, 6, delay=0, fraction=p, seed=2, subset_kind=am.SUBSET_STRATIFIED)
+    run_steps(am, 4099, 8, 6, delay=1, fraction=p, seed=2, subset_kind=am.SUBSET_STRATIFIED, correction=am.CORR_NONE)
+
+
+def test_stratified_variant_sparse_average_entry(amlib):
+    am = amlib
+    n, R, p = 77_003, 4, 0.05
+    st, orc = make_pair(am, n, R, delay=1, fraction=p, seed=8, subset_kind=am.SUBSET_STRATIFIED)
+    rng = np.random.default_rng(5)
+    for t in range(1, 6):
+        w = [(orc.w(i) + rng.normal(0, 1e-3, n).astype(np.float32)) for i in range(R)]
+        for i in range(R):
+            orc.w(i)[:] = w[i]
+            st.w[i].copy_(torch.from_numpy(w[i]))
+        st.sparse_average(t, 0.5); orc.sparse_average(t, 0.5)
+    compare(st, orc, "stratified sparse_average")
+
+
 
 @pytest.mark.parametrize("msg", [O.MSG_BF16, O.MSG_E4M3])
 @pytest.mark.parametrize("tau", [0, 2])

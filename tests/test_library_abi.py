@@ -29,10 +29,11 @@ def test_every_declared_symbol_is_exported(amlib):
 
 def test_config_struct_matches_header_layout(amlib):
     from paper_2601_22442_amd.binding import Config
-    assert C.sizeof(Config) == 96
+    assert C.sizeof(Config) == 104
     assert Config.fraction.offset == 24 and Config.seed.offset == 32
     assert Config.beta1.offset == 40 and Config.gamma.offset == 56
     assert Config.grad_dtype.offset == 72 and Config.momentum_decay.offset == 80 and Config.subset_granule.offset == 88
+    assert Config.msg_dtype.offset == 92 and Config.subset_kind.offset == 96
 
 
 def test_workspace_bytes_and_capacity_formula(amlib):
@@ -49,6 +50,10 @@ def test_workspace_bytes_and_capacity_formula(amlib):
     ring = (tau + 1) * cap_lines * 32 * R * 4
     b = am.workspace_bytes(am.make_config(n, R, delay=tau, fraction=p))
     assert ring < b < ring * 1.01 + (1 << 20)                     # plus the small offset tables
+    # stratified variant: a tile meets at most floor(255/20) + 2 = 14 blocks -> one line per tile, no margin needed
+    bs = am.workspace_bytes(am.make_config(n, R, delay=tau, fraction=p, subset_kind=am.SUBSET_STRATIFIED))
+    ring_s = (tau + 1) * ntiles * 32 * R * 4
+    assert ring_s <= bs < ring_s + (64 << 20)
     full = am.workspace_bytes(am.make_config(1000, 2, delay=0, fraction=1.0))
     assert full >= 4 * 256 * 2 * 4                                 # p = 1: every tile owns all its 8 lines
 
@@ -58,6 +63,8 @@ def test_workspace_bytes_and_capacity_formula(amlib):
     (dict(avg_interval=0), "avg_interval"), (dict(fraction=0.0), "fraction"), (dict(fraction=1.5), "fraction"),
     (dict(optimizer=7), "optimizer"), (dict(correction=5), "correction"), (dict(beta1=1.0), "beta1"),
     (dict(fwd_dtype=3), "dtype"), (dict(subset_granule=16), "granule"),
+    (dict(subset_kind=2), "subset_kind"), (dict(subset_kind=1, subset_granule=32), "stratified"),
+    (dict(subset_kind=1, fraction=1e-10), "block"),
 ])
 def test_bad_configs_are_rejected(amlib, kw, needle):
     am = amlib

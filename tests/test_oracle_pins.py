@@ -137,7 +137,8 @@ def test_stratified_variant_has_exact_size_and_the_marginal_probability():
     # subset coordinates take the mean (tau = 0), the rest keep the local step
     R, lr, n = 3, O.f32(0.25), 10_007
     w0 = np.stack([si.stage_weights(n, seed=70 + i) for i in range(R)])
-    orc = O.Oracle(n, R, delay=0, fraction=p, seed=seed, optimizer=O.OPT_SGD, beta1=0.0, weight_decay=0.0, stratified=True)
+    orc = O.Oracle(n, R, delay=0, fraction=p, seed=seed, optimizer=O.OPT_SGD, beta1=0.0, weight_decay=0.0,
+                   subset_kind=O.SUBSET_STRATIFIED)
     orc.set_w(w0)
     g = np.stack(si.replica_grads(n, R, 1, seed=10))
     what = (w0.astype(np.float64) - lr * g.astype(np.float64)).astype(np.float32)
