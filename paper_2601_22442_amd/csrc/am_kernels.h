@@ -363,9 +363,13 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, uint32_t tile, uint
     const int nvalid = FULL ? 4 : (mu >= a.n ? 0 : (a.n - mu >= 4u ? 4 : (int)(a.n - mu)));
     const uint64_t slot_floats = (uint64_t)a.cap_lines * kLineFloats;      // per replica
 
+    // Averaging alone moves little per replica, so a wave keeps the loads of four of its replicas in
+    // flight together; with the optimizer pass one replica's operands fill the registers.
+    constexpr uint32_t DEPTH = OPT == kOptNone ? 4u : 1u;
+
     // first replica's dense operands go out before anything else waits on memory
-    GroupIn in;
-    if (OPT != kOptNone) load_group<OPT, GRAD_BF16>(a, wave, mu, nvalid, in);
+    GroupIn in[DEPTH];
+    if (OPT != kOptNone) load_group<OPT, GRAD_BF16>(a, wave, mu, nvalid, in[0]);
 
     // ---- subsets: which of my 4 coordinates are sent now / received now, and where the tile's
     //      lines start.  A tile whose lines would pass the slot capacity is left out, at send and at
@@ -399,7 +403,9 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, uint32_t tile, uint
         const uint64_t any = __ballot(s.mask_recv != 0u);
         s.line_recv = ((any >> (lane & ~7u)) & 0xFFull) != 0ull;
     }
-    load_group_sparse<OPT>(a, wave, mu, nvalid, s, in);
+#pragma unroll
+    for (uint32_t k = 0; k < DEPTH; ++k)
+        if (wave + k * nwaves < R) load_group_sparse<OPT>(a, wave + k * nwaves, mu, nvalid, s, in[k]);
 
     if (a.do_next && wave == 0) {                           // one wave per tile sizes the next step's send
         uint32_t count;
@@ -422,7 +428,7 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, uint32_t tile, uint
                     GroupIn pre;
                     F4 w_hat, m_new, v_new;
                     if (i == wave) {
-                        pre = in;
+                        pre = in[0];
                     } else {
                         if (OPT != kOptNone) load_group<OPT, GRAD_BF16>(a, i, mu, nvalid, pre);
                         load_group_sparse<OPT>(a, i, mu, nvalid, s, pre);
@@ -454,12 +460,22 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, uint32_t tile, uint
     }
 
     // ---- my replicas
-    for (uint32_t i = wave; i < R; i += nwaves) {
-        if (i != wave) {
-            if (OPT != kOptNone) load_group<OPT, GRAD_BF16>(a, i, mu, nvalid, in);
-            load_group_sparse<OPT>(a, i, mu, nvalid, s, in);
+    for (uint32_t base = wave; base < R; base += DEPTH * nwaves) {
+        if (base != wave) {
+#pragma unroll
+            for (uint32_t k = 0; k < DEPTH; ++k) {
+                const uint32_t i = base + k * nwaves;
+                if (i < R) {
+                    if (OPT != kOptNone) load_group<OPT, GRAD_BF16>(a, i, mu, nvalid, in[k]);
+                    load_group_sparse<OPT>(a, i, mu, nvalid, s, in[k]);
+                }
+            }
         }
-        step_replica<OPT, FWD>(a, i, mu, nvalid, lane, s, abar, in, sent_lds + i * kTileCoords, send_lds);
+#pragma unroll
+        for (uint32_t k = 0; k < DEPTH; ++k) {
+            const uint32_t i = base + k * nwaves;
+            if (i < R) step_replica<OPT, FWD>(a, i, mu, nvalid, lane, s, abar, in[k], sent_lds + i * kTileCoords, send_lds);
+        }
     }
 }
 

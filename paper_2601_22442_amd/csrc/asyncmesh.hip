@@ -485,7 +485,7 @@ am_status am_sparse_average(am_state *st, uint64_t t, float lambda_t)
         std::memset(&a, 0, sizeof a);
         for (uint32_t i = 0; i < st->cfg.replicas; ++i) { a.w[i] = st->w[i]; a.d[i] = st->d[i]; }
         if (am_status s = fill_averaging(st, t, lambda_t, r, a)) return s;
-        // little memory traffic per tile here, so fewer waves share a tile's hashing (measured best: 2)
+        // every wave hashes the tile's subsets itself and little memory moves per tile: two waves measured best
         const uint32_t waves = st->cfg.replicas < 2u ? st->cfg.replicas : 2u;
         const size_t lds = (size_t)(st->cfg.replicas + waves) * am::kTileCoords * sizeof(float);
         am::k_step<am::kOptNone, false, am::kFwdNone><<<dim3(st->lay.ntiles), dim3(64u * waves), lds, st->stream>>>(a);
