@@ -200,6 +200,29 @@ am_status am_get_profile(am_state *st, double *out_kernel_ms, uint64_t *out_laun
  * host values, no device work. */
 am_status am_ring_info(const am_state *st, uint64_t *out_capacity, uint32_t *out_slots);
 
+/* Checkpoints.  Everything on the device is the caller's (w, m, v, d, fwd and the workspace, which
+ * holds the delay ring of the appendix' "buffering" and the subset offset tables); what the library
+ * itself remembers between steps is this small host record.  To checkpoint: let the stream drain,
+ * copy the arrays and the workspace, call am_export_state.  To resume: put the bytes back (any
+ * addresses, same alignment rules), and call am_resume_state instead of am_init_state; it clears
+ * nothing.  S^t is a pure function of (seed, t), so there is no generator state to save.  The
+ * record is refused (AM_EINVAL) when the config differs from the one it was exported under in a
+ * field that shapes the ring or the subsets (n, replicas, delay, avg_interval, optimizer,
+ * fraction, seed, subset_granule, subset_kind).  Host-only calls apart from what am_init_state does. */
+typedef struct {
+    uint64_t magic;             /* layout version of this record                                */
+    uint64_t config_digest;
+    uint64_t last_t;            /* the last step made                                           */
+    uint64_t next_lines_step;   /* the step whose send subset is already sized in the workspace */
+    double   mu_product;        /* NADAMW: running product of the momentum schedule             */
+    uint32_t delay_now;         /* the delay in force (am_set_delay)                            */
+    uint32_t reserved;
+} am_snapshot;
+
+am_status am_export_state(const am_state *st, am_snapshot *out);
+am_status am_resume_state(const am_config *cfg, const am_buffers *buf, void *hip_stream,
+                          const am_snapshot *snapshot, am_state **out);
+
 am_status am_destroy(am_state *st);
 
 const char *am_last_error(void);      /* message of the last failing call on this thread */

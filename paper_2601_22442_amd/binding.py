@@ -25,6 +25,7 @@ EXPORTS = (
     "am_workspace_bytes", "am_init_state", "am_step", "am_step_scaled", "am_grad_sqnorm", "am_sparse_average",
     "am_lookahead",
     "am_subset_indices", "am_set_delay", "am_diagnostics", "am_read_flags", "am_set_profiling", "am_get_profile", "am_ring_info",
+    "am_export_state", "am_resume_state",
     "am_destroy", "am_last_error", "am_version",
 )
 
@@ -59,6 +60,15 @@ class Buffers(C.Structure):
     ]
 
 
+class Snapshot(C.Structure):
+    """Mirror of am_snapshot: what the library itself remembers between steps."""
+    _fields_ = [
+        ("magic", C.c_uint64), ("config_digest", C.c_uint64), ("last_t", C.c_uint64),
+        ("next_lines_step", C.c_uint64), ("mu_product", C.c_double),
+        ("delay_now", C.c_uint32), ("reserved", C.c_uint32),
+    ]
+
+
 def _load():
     if not _LIB_PATH.exists():
         raise ImportError(
@@ -79,6 +89,8 @@ def _load():
     L.am_set_profiling.argtypes = [C.c_void_p, C.c_int]
     L.am_get_profile.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_uint64)]
     L.am_ring_info.argtypes = [C.c_void_p, C.POINTER(C.c_uint64), C.POINTER(C.c_uint32)]
+    L.am_export_state.argtypes = [C.c_void_p, C.POINTER(Snapshot)]
+    L.am_resume_state.argtypes = [C.POINTER(Config), C.POINTER(Buffers), C.c_void_p, C.POINTER(Snapshot), C.POINTER(C.c_void_p)]
     L.am_destroy.argtypes = [C.c_void_p]
     for name in EXPORTS:
         getattr(L, name).restype = C.c_int
@@ -154,7 +166,26 @@ class Stage:
         self._handle = C.c_void_p(None)
         self._init()
 
-    def _init(self):
+    @classmethod
+    def resume(cls, cfg: Config, snapshot: Snapshot, w, m, v, d, fwd, workspace, device="cuda:0"):
+        """A stage bound to arrays whose bytes were restored from a checkpoint (am_resume_state);
+        nothing is cleared.  m, v, d, fwd are lists of tensors or None, as the config needs."""
+        self = cls.__new__(cls)
+        self.cfg, self.device = cfg, torch.device(device)
+        self.n, self.R = int(cfg.n), int(cfg.replicas)
+        self.w, self.m, self.v, self.d, self.fwd, self.workspace = w, m, v, d, fwd, workspace
+        self._handle = C.c_void_p(None)
+        self._init(snapshot)
+        return self
+
+    def export_state(self) -> Snapshot:
+        """The library's own record for a checkpoint (am_export_state).  The caller lets the stream
+        drain and saves w, m, v, d, (fwd) and the workspace alongside it."""
+        snap = Snapshot()
+        _check(lib.am_export_state(self._handle, C.byref(snap)))
+        return snap
+
+    def _init(self, snapshot: Snapshot | None = None):
         bufs = Buffers()
         self._tables = {}
         for name in ("w", "m", "v", "d", "fwd"):
@@ -165,7 +196,11 @@ class Stage:
         bufs.workspace = self.workspace.data_ptr()
         bufs.workspace_bytes = self.workspace.numel()
         with torch.cuda.device(self.device):
-            _check(lib.am_init_state(C.byref(self.cfg), C.byref(bufs), _stream_handle(self.device), C.byref(self._handle)))
+            if snapshot is None:
+                _check(lib.am_init_state(C.byref(self.cfg), C.byref(bufs), _stream_handle(self.device), C.byref(self._handle)))
+            else:
+                _check(lib.am_resume_state(C.byref(self.cfg), C.byref(bufs), _stream_handle(self.device),
+                                           C.byref(snapshot), C.byref(self._handle)))
 
     def set_w(self, w0: torch.Tensor):
         """Copy the starting weights in: one row for all replicas (1-D) or one row per replica (2-D)."""

@@ -288,7 +288,27 @@ am_status am_workspace_bytes(const am_config *cfg, uint64_t *out_bytes)
     return AM_OK;
 }
 
-am_status am_init_state(const am_config *cfg, const am_buffers *buf, void *hip_stream, am_state **out)
+}  // extern "C"
+
+namespace {
+
+constexpr uint64_t kSnapshotMagic = 0x414D534E41503031ull;     // "AMSNAP01"
+
+// digest (FNV-1a) of the config fields that shape the ring and the subsets
+uint64_t config_digest(const am_config &c)
+{
+    uint64_t fraction_bits;
+    std::memcpy(&fraction_bits, &c.fraction, sizeof fraction_bits);
+    const uint64_t words[] = { c.n, c.replicas, c.delay, c.avg_interval, c.optimizer, fraction_bits, c.seed,
+                               c.subset_granule == 32 ? 32u : 1u, c.subset_kind };
+    uint64_t h = 0xCBF29CE484222325ull;
+    for (uint64_t w : words)
+        for (int b = 0; b < 8; ++b) { h ^= (w >> (8 * b)) & 0xFFu; h *= 0x100000001B3ull; }
+    return h;
+}
+
+// validates config and buffers and builds the host-side state; clears nothing on the device
+am_status create_state(const am_config *cfg, const am_buffers *buf, void *hip_stream, am_state **out)
 {
     if (am_status s = check_config(cfg)) return s;
     if (!buf || !out) return fail(AM_EINVAL, "buffers / out is NULL");
@@ -347,6 +367,22 @@ am_status am_init_state(const am_config *cfg, const am_buffers *buf, void *hip_s
     const uint32_t tile_groups = (lay.ntiles + 3) / 4;
     const uint32_t want = (uint32_t)cus * 8u;
     st->grid_sparse = tile_groups < want ? tile_groups : want;
+    *out = st;
+    return AM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+am_status am_init_state(const am_config *cfg, const am_buffers *buf, void *hip_stream, am_state **out)
+{
+    am_state *st = nullptr;
+    if (am_status s = create_state(cfg, buf, hip_stream, &st)) return s;
+    const uint32_t R = cfg->replicas;
+    const bool need_m = st->m[0] != nullptr, need_v = st->v[0] != nullptr, need_d = st->d[0] != nullptr;
+    const Layout &lay = st->lay;
+    hipError_t e = hipSuccess;
 
     // d^0 = 0 and zero moments; clear flags, offsets and ring
     const size_t bytes = (size_t)cfg->n * sizeof(float);
@@ -357,6 +393,38 @@ am_status am_init_state(const am_config *cfg, const am_buffers *buf, void *hip_s
     }
     if (e == hipSuccess) e = hipMemsetAsync(st->ws, 0, lay.total, st->stream);
     if (e != hipSuccess) { delete st; return fail(AM_EHIP, "hipMemsetAsync: %s", hipGetErrorString(e)); }
+    *out = st;
+    return AM_OK;
+}
+
+am_status am_export_state(const am_state *st, am_snapshot *out)
+{
+    if (!st || !out) return fail(AM_EINVAL, "NULL argument");
+    out->magic = kSnapshotMagic;
+    out->config_digest = config_digest(st->cfg);
+    out->last_t = st->last_t;
+    out->next_lines_step = st->next_lines_step;
+    out->mu_product = st->mu_product;
+    out->delay_now = st->delay_now;
+    out->reserved = 0;
+    return AM_OK;
+}
+
+am_status am_resume_state(const am_config *cfg, const am_buffers *buf, void *hip_stream,
+                          const am_snapshot *snapshot, am_state **out)
+{
+    if (am_status s = check_config(cfg)) return s;
+    if (!snapshot) return fail(AM_EINVAL, "snapshot is NULL");
+    if (snapshot->magic != kSnapshotMagic) return fail(AM_EINVAL, "snapshot has an unknown layout (magic %016llx)", (unsigned long long)snapshot->magic);
+    if (snapshot->config_digest != config_digest(*cfg)) return fail(AM_EINVAL, "snapshot was exported under a different config (n, replicas, delay, avg_interval, optimizer, fraction, seed or subset rule differ)");
+    if (snapshot->delay_now > cfg->delay) return fail(AM_EINVAL, "snapshot delay %u exceeds the configured delay %u", snapshot->delay_now, cfg->delay);
+    if (!(snapshot->mu_product >= 0.0 && snapshot->mu_product <= 1.0)) return fail(AM_EINVAL, "snapshot mu_product=%g not in [0, 1]", snapshot->mu_product);
+    am_state *st = nullptr;
+    if (am_status s = create_state(cfg, buf, hip_stream, &st)) return s;
+    st->last_t = snapshot->last_t;
+    st->next_lines_step = snapshot->next_lines_step;
+    st->mu_product = snapshot->mu_product;
+    st->delay_now = snapshot->delay_now;
     *out = st;
     return AM_OK;
 }

@@ -542,6 +542,42 @@ def test_two_states_do_not_interfere(amlib):
     compare(a, oa, "state a"); compare(b, ob, "state b")
 
 
+@pytest.mark.parametrize("opt,K", [(O.OPT_NADAMW, 1), (O.OPT_ADAMW, 2)])
+def test_checkpoint_and_resume(amlib, opt, K):
+    """A run that is checkpointed after step 5 and resumed on other memory continues bit for bit as
+    the uninterrupted run does (and both agree with the oracle)."""
+    am = amlib
+    n, R, tau, seed, total = 60_017, 4, 2, 31, 13
+    kw = dict(delay=tau, avg_interval=K, fraction=0.1, seed=seed, optimizer=opt, lookahead=(opt != O.OPT_NADAMW), gamma=0.9)
+    a, orc = make_pair(am, n, R, **kw)
+    saved = None
+    for t in range(1, total + 1):
+        g, gd = grads_for(n, R, t, seed, False)
+        a.step(t, gd, 1e-3, 0.5); orc.step(t, g, 1e-3, 0.5)
+        if t == 3:
+            a.set_delay(1); orc.set_delay(1)
+        if t == 5:
+            torch.cuda.synchronize()
+            clone = lambda ts: None if ts is None else [x.clone() for x in ts]
+            saved = (a.export_state(), clone(a.w), clone(a.m), clone(a.v), clone(a.d), clone(a.fwd), a.workspace.clone())
+    compare(a, orc, "uninterrupted")
+    snap, w, m, v, d, fwd, ws = saved
+    assert snap.last_t == 5 and snap.delay_now == 1
+    b = am.Stage.resume(a.cfg, snap, w, m, v, d, fwd, ws)
+    with pytest.raises(am.AsyncMeshError):
+        b.step(5, grads_for(n, R, 5, seed, False)[1], 1e-3, 0.5)           # the step counter came back too
+    for t in range(6, total + 1):
+        b.step(t, grads_for(n, R, t, seed, False)[1], 1e-3, 0.5)
+    torch.cuda.synchronize()
+    for name in ("w", "m", "v", "d", "fwd"):
+        if getattr(a, name) is not None:
+            for i in range(R):
+                assert torch.equal(getattr(a, name)[i], getattr(b, name)[i]), (name, i)
+    other = am.make_config(n, R, **dict(kw, seed=seed + 1))
+    with pytest.raises(am.AsyncMeshError):
+        am.Stage.resume(other, snap, w, m, v, d, fwd, ws)
+
+
 def test_kernel_profiling_hooks(amlib):
     am = amlib
     n, R = 200_000, 2

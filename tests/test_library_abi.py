@@ -113,3 +113,22 @@ def test_schedules_of_the_paper_s_setup(amlib):
     assert abs(am.learning_rate(T, T) - 3e-5) < 1e-18
     lr = [am.learning_rate(t, T) for t in range(3000, T + 1)]
     assert all(a >= b for a, b in zip(lr, lr[1:]))
+
+
+def test_snapshot_record_layout_and_checks(amlib):
+    """am_resume_state looks at the record before it looks at the device."""
+    am = amlib
+    from paper_2601_22442_amd import binding as B
+    assert C.sizeof(B.Snapshot) == 48 and B.Snapshot.mu_product.offset == 32 and B.Snapshot.delay_now.offset == 40
+    cfg = am.make_config(1000, 2, delay=1, fraction=0.1)
+    h = C.c_void_p(None)
+    bufs = B.Buffers()
+    assert B.lib.am_export_state(None, C.byref(B.Snapshot())) == -1
+    snap = B.Snapshot(magic=123)
+    assert B.lib.am_resume_state(C.byref(cfg), C.byref(bufs), None, C.byref(snap), C.byref(h)) == -1
+    assert "layout" in B.lib.am_last_error().decode()
+    snap = B.Snapshot(magic=0x414D534E41503031, config_digest=1)
+    assert B.lib.am_resume_state(C.byref(cfg), C.byref(bufs), None, C.byref(snap), C.byref(h)) == -1
+    assert "different config" in B.lib.am_last_error().decode()
+    assert B.lib.am_resume_state(C.byref(cfg), C.byref(bufs), None, None, C.byref(h)) == -1
+    assert not h.value
