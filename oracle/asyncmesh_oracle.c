@@ -237,7 +237,10 @@ typedef struct {
     uint32_t nkept;
     uint64_t last_t;
     uint32_t delay_now;          /* the delay in force (<= c.delay, which sizes the buffer) */
-    double mu_product;           /* NAdam's running product of momentum coefficients */
+    /* per replica, because replicas of unequal speed make unequal numbers of local steps
+     * (heterogeneous set-up of the experiments): */
+    uint64_t *opt_steps;         /* [R] optimizer steps made so far = the t of the bias corrections */
+    double *mu_product;          /* [R] NAdam's running product of momentum coefficients */
 } amo_state;
 
 static float **alloc_2d(uint32_t R, uint64_t n)
@@ -266,7 +269,9 @@ amo_state *amo_create(const amo_config *c)
     for (uint32_t k = 0; k < s->nkept; ++k) s->kept[k] = alloc_2d(R, c->n);
     s->last_t = 0;
     s->delay_now = c->delay;
-    s->mu_product = 1.0;
+    s->opt_steps = (uint64_t *)calloc(R ? R : 1, sizeof(uint64_t));
+    s->mu_product = (double *)calloc(R ? R : 1, sizeof(double));
+    for (uint32_t i = 0; i < R; ++i) s->mu_product[i] = 1.0;
     return s;
 }
 
@@ -278,6 +283,8 @@ void amo_destroy(amo_state *s)
     free_2d(s->what, R); free_2d(s->w_before, R);
     for (uint32_t k = 0; k < s->nkept; ++k) free_2d(s->kept[k], R);
     free(s->kept);
+    free(s->opt_steps);
+    free(s->mu_product);
     free(s);
 }
 
@@ -299,24 +306,36 @@ static double grad_value(const amo_state *s, const void *g, uint64_t k, double g
 }
 
 /* replica_scale: NULL, or one more factor per replica on top of grad_scale (each replica clips by
- * its own gradient norm) */
+ * its own gradient norm).
+ * active: NULL = every replica steps and its optimizer step count becomes t (the homogeneous
+ * set-up); else bit i says whether replica i makes a local step in this tick.  A replica that does
+ * not step keeps w, m, v (w^ = w) and its step count; one that does counts one more step.  This
+ * is the heterogeneous set-up of the experiments (Sec. "Heterogeneous setup": faster devices make
+ * more iterations between two averaging steps), simulated in lock-step ticks. */
 static void local_step(amo_state *s, uint64_t t, const void *const *grads, double lr, double grad_scale,
-                       const float *replica_scale)
+                       const float *replica_scale, const uint32_t *active)
 {
     const amo_config *c = &s->c;
     const double b1 = c->beta1, b2 = c->beta2, eps = c->eps, wd = c->weight_decay;
-    /* per-step scalars, evaluated once */
-    const double bc1 = 1.0 - pow(b1, (double)t);       /* Adam bias corrections */
-    const double bc2 = 1.0 - pow(b2, (double)t);
-    /* NAdam (Dozat) momentum schedule: mu_t = beta1 (1 - 0.5 * 0.96^(t psi)) */
-    const double mu_t  = b1 * (1.0 - 0.5 * pow(0.96, (double)t * c->momentum_decay));
-    const double mu_t1 = b1 * (1.0 - 0.5 * pow(0.96, (double)(t + 1) * c->momentum_decay));
-    const double mu_prod = s->mu_product * mu_t;       /* prod_{k<=t} mu_k */
-    if (c->optimizer == AMO_OPT_NADAMW) s->mu_product = mu_prod;
 
     for (uint32_t i = 0; i < c->replicas; ++i) {
         float *w = s->w[i], *m = s->m[i], *v = s->v[i], *what = s->what[i], *wb = s->w_before[i];
         const void *g_i = grads[i];
+        if (active && !((*active >> i) & 1u)) {          /* no local step in this tick */
+            memcpy(what, w, c->n * sizeof(float));
+            memcpy(wb, w, c->n * sizeof(float));
+            continue;
+        }
+        const uint64_t steps = active ? s->opt_steps[i] + 1 : t;
+        s->opt_steps[i] = steps;
+        /* per-step scalars, evaluated once */
+        const double bc1 = 1.0 - pow(b1, (double)steps);       /* Adam bias corrections */
+        const double bc2 = 1.0 - pow(b2, (double)steps);
+        /* NAdam (Dozat) momentum schedule: mu_t = beta1 (1 - 0.5 * 0.96^(t psi)) */
+        const double mu_t  = b1 * (1.0 - 0.5 * pow(0.96, (double)steps * c->momentum_decay));
+        const double mu_t1 = b1 * (1.0 - 0.5 * pow(0.96, (double)(steps + 1) * c->momentum_decay));
+        const double mu_prod = s->mu_product[i] * mu_t;        /* prod_{k<=t} mu_k */
+        if (c->optimizer == AMO_OPT_NADAMW) s->mu_product[i] = mu_prod;
         #pragma omp parallel for schedule(static)
         for (uint64_t k = 0; k < c->n; ++k) {
             const double g = grad_value(s, g_i, k, replica_scale ? grad_scale * (double)replica_scale[i] : grad_scale);
@@ -423,7 +442,20 @@ int amo_step_scaled(amo_state *s, uint64_t t, const void *const *grads, double l
                     double grad_scale, const float *replica_scale)
 {
     if (t != s->last_t + 1) return -1;
-    local_step(s, t, grads, lr, grad_scale, replica_scale);
+    local_step(s, t, grads, lr, grad_scale, replica_scale, NULL);
+    sparse_average(s, t, lambda);
+    look_ahead(s);
+    s->last_t = t;
+    return 0;
+}
+
+/* one tick of the heterogeneous set-up: only the replicas whose bit is set make a local step
+ * (grads[i] of the others is not read and may be NULL); everything else as in amo_step_scaled */
+int amo_step_masked(amo_state *s, uint64_t t, const void *const *grads, double lr, double lambda,
+                    double grad_scale, const float *replica_scale, uint32_t active)
+{
+    if (t != s->last_t + 1) return -1;
+    local_step(s, t, grads, lr, grad_scale, replica_scale, &active);
     sparse_average(s, t, lambda);
     look_ahead(s);
     s->last_t = t;
@@ -433,7 +465,7 @@ int amo_step_scaled(amo_state *s, uint64_t t, const void *const *grads, double l
 int amo_step(amo_state *s, uint64_t t, const void *const *grads, double lr, double lambda, double grad_scale)
 {
     if (t != s->last_t + 1) return -1;
-    local_step(s, t, grads, lr, grad_scale, NULL);
+    local_step(s, t, grads, lr, grad_scale, NULL, NULL);
     sparse_average(s, t, lambda);
     look_ahead(s);
     s->last_t = t;

@@ -75,6 +75,9 @@ def lib():
         L.amo_step.restype = C.c_int
         L.amo_step_scaled.argtypes = [C.c_void_p, C.c_uint64, C.POINTER(C.c_void_p), C.c_double, C.c_double, C.c_double, C.c_void_p]
         L.amo_step_scaled.restype = C.c_int
+        L.amo_step_masked.argtypes = [C.c_void_p, C.c_uint64, C.POINTER(C.c_void_p), C.c_double, C.c_double, C.c_double,
+                                      C.c_void_p, C.c_uint32]
+        L.amo_step_masked.restype = C.c_int
         L.amo_grad_sqnorm.argtypes = [C.c_void_p, C.c_uint64, C.c_uint32]; L.amo_grad_sqnorm.restype = C.c_double
         L.amo_sparse_average.argtypes = [C.c_void_p, C.c_uint64, C.c_double]; L.amo_sparse_average.restype = C.c_int
         L.amo_lookahead.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_double]
@@ -221,6 +224,20 @@ class Oracle:
             rc = lib().amo_step_scaled(self._h, t, ptrs, f32(lr), f32(lam), f32(grad_scale), rs.ctypes.data)
         else:
             rc = lib().amo_step(self._h, t, ptrs, f32(lr), f32(lam), f32(grad_scale))
+        if rc != 0:
+            raise ValueError(f"oracle step out of order: t={t}")
+
+    def step_masked(self, t, grads, lr, lam, active: int, grad_scale=1.0, replica_scale=None):
+        """One tick of the heterogeneous set-up: replica i makes a local step iff bit i of `active`
+        is set (grads[i] of the others may be None)."""
+        want = np.uint16 if self.cfg.grad_bf16 else np.float32
+        keep = [None if g is None else np.ascontiguousarray(g, dtype=want) for g in grads]
+        assert len(keep) == self.R and all(g is None or g.size == self.n for g in keep)
+        assert all(keep[i] is not None for i in range(self.R) if (active >> i) & 1)
+        ptrs = (C.c_void_p * self.R)(*[None if g is None else g.ctypes.data for g in keep])
+        rs = None if replica_scale is None else np.ascontiguousarray(replica_scale, dtype=np.float32)
+        rc = lib().amo_step_masked(self._h, t, ptrs, f32(lr), f32(lam), f32(grad_scale),
+                                   None if rs is None else rs.ctypes.data, active)
         if rc != 0:
             raise ValueError(f"oracle step out of order: t={t}")
 

@@ -256,6 +256,68 @@ def test_local_step_equals_library_optimizer(name):
         assert not np.any(orc.d(i))
 
 
+@pytest.mark.parametrize("name", ["adamw", "nadamw"])
+def test_replicas_of_unequal_speed_each_follow_their_own_optimizer_run(name):
+    """Heterogeneous set-up: a replica that steps in only some ticks is, with averaging off, a
+    stand-alone library optimizer run over just the gradients of its own steps (own step count in
+    the bias corrections, own momentum schedule), and an idle tick leaves it untouched."""
+    n, R, ticks, lr = 2000, 3, 12, 3e-3
+    b1, b2, eps = O.f32(0.9), O.f32(0.999), O.f32(1e-8)
+    w0 = si.stage_weights(n, seed=4)
+    grads = [si.replica_grads(n, R, t, seed=4) for t in range(1, ticks + 1)]
+    masks = [0b111, 0b110, 0b100, 0b111, 0b010, 0b100, 0b101, 0b110, 0b100, 0b000, 0b011, 0b100]
+    if name == "adamw":
+        kw = dict(optimizer=O.OPT_ADAMW, weight_decay=0.01)
+        mk = lambda ps: torch.optim.AdamW(ps, lr=O.f32(lr), betas=(b1, b2), eps=eps, weight_decay=O.f32(0.01), foreach=False)
+    else:
+        kw = dict(optimizer=O.OPT_NADAMW, weight_decay=0.01)
+        mk = lambda ps: torch.optim.NAdam(ps, lr=O.f32(lr), betas=(b1, b2), eps=eps, weight_decay=O.f32(0.01),
+                                          decoupled_weight_decay=True, momentum_decay=0.004, foreach=False)
+    orc = O.Oracle(n, R, delay=1, fraction=EMPTY_P, **kw)
+    orc.set_w(w0)
+    for t in range(1, ticks + 1):
+        before = [(orc.w(i).copy(), orc.m(i).copy(), orc.v(i).copy()) for i in range(R)]
+        g = [grads[t - 1][i] if (masks[t - 1] >> i) & 1 else None for i in range(R)]
+        orc.step_masked(t, g, lr, 0.5, masks[t - 1])
+        for i in range(R):
+            if not (masks[t - 1] >> i) & 1:
+                assert all(np.array_equal(a, b) for a, b in zip(before[i], (orc.w(i), orc.m(i), orc.v(i))))
+    for i in range(R):
+        own = [grads[t][i] for t in range(ticks) if (masks[t] >> i) & 1]
+        want = _torch_run(mk, w0, own)
+        scale = np.maximum(np.abs(want), np.sqrt(np.mean(want ** 2)))
+        assert np.max(np.abs(orc.w(i) - want) / scale) < 2e-6, i
+
+
+def test_all_replicas_active_is_the_ordinary_step_and_idle_ones_still_average():
+    n, R, lr = 5000, 3, O.f32(0.25)
+    for opt in (O.OPT_ADAMW, O.OPT_NADAMW):
+        a = O.Oracle(n, R, delay=1, fraction=0.2, seed=3, optimizer=opt, lookahead=True, gamma=0.9)
+        b = O.Oracle(n, R, delay=1, fraction=0.2, seed=3, optimizer=opt, lookahead=True, gamma=0.9)
+        w0 = si.stage_weights(n, seed=5)
+        a.set_w(w0); b.set_w(w0)
+        for t in range(1, 7):
+            g = si.replica_grads(n, R, t, seed=5)
+            a.step(t, g, 1e-3, 0.5)
+            b.step_masked(t, g, 1e-3, 0.5, 0b111)
+        for i in range(R):
+            for name in ("w", "m", "v", "d", "fwd"):
+                assert np.array_equal(getattr(a, name)(i), getattr(b, name)(i)), (opt, name, i)
+    # tau = 0, p = 1, plain SGD: everybody ends on the mean of the w^, and an idle replica's w^ is its old w
+    w0 = np.stack([si.stage_weights(n, seed=80 + i) for i in range(R)])
+    orc = O.Oracle(n, R, delay=0, fraction=1.0, optimizer=O.OPT_SGD, beta1=0.0, weight_decay=0.0, lookahead=True, gamma=0.5)
+    orc.set_w(w0)
+    g = np.stack(si.replica_grads(n, R, 1, seed=6))
+    orc.step_masked(1, [g[0], None, g[2]], lr, 0.5, 0b101)
+    what = w0.astype(np.float64) - lr * g.astype(np.float64) * np.array([1.0, 0.0, 1.0])[:, None]
+    what = what.astype(np.float32)
+    mean = what.astype(np.float64).mean(axis=0).astype(np.float32)
+    for i in range(R):
+        assert np.array_equal(orc.w(i), mean)
+        delta = what[i].astype(np.float64) - w0[i].astype(np.float64)          # the optimizer's displacement: 0 when idle
+        assert np.array_equal(orc.fwd(i), (mean.astype(np.float64) + 0.5 * delta).astype(np.float32))
+
+
 def test_first_adamw_step_closed_form():
     """From zero moments, one AdamW step is w(1 - lr wd) - lr g / (|g| + eps)."""
     n, lr, wd, eps = 1000, O.f32(1e-3), O.f32(0.01), O.f32(1e-8)
