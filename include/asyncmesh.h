@@ -154,6 +154,19 @@ am_status am_step(am_state *st, uint64_t t, const void *const *grads,
  * kernel: g_i <- grad_scale * replica_scale[i] * g_i.  For global-norm clipping (norm 1 in the
  * paper's set-up) without a host round trip: am_grad_sqnorm gives the stage's share of each
  * replica's squared norm, the caller turns the norms of all stages into factors on the device. */
+/* One tick of the heterogeneous set-up (Sec. "Heterogeneous setup" and its appendix paragraph:
+ * devices of unequal speed; the averaging interval is proportional to the device speed, so faster
+ * devices make more iterations between two averaging steps).  The R replicas advance in lock-step
+ * ticks t = 1, 2, ...; replica i makes a local optimizer step in this tick iff bit i of
+ * active_mask is set, with its own count of steps made so far in the bias corrections (and in
+ * NADAMW's momentum schedule).  An idle replica keeps w, m, v (its w^ is its w, its look-ahead
+ * displacement is zero) and grads[i] is not read (may be NULL); it still sends and receives when
+ * the tick is an averaging step (t a multiple of avg_interval).  With every bit set in every tick
+ * this is am_step_scaled.  am_step / am_step_scaled set every replica's count to t.
+ * AM_EINVAL if a bit at or above `replicas` is set. */
+am_status am_step_masked(am_state *st, uint64_t t, const void *const *grads, float lr, float lambda_t,
+                         float grad_scale, const float *dev_replica_scale, uint32_t active_mask);
+
 am_status am_step_scaled(am_state *st, uint64_t t, const void *const *grads, float lr, float lambda_t,
                          float grad_scale, const float *dev_replica_scale);
 
@@ -214,9 +227,10 @@ typedef struct {
     uint64_t config_digest;
     uint64_t last_t;            /* the last step made                                           */
     uint64_t next_lines_step;   /* the step whose send subset is already sized in the workspace */
-    double   mu_product;        /* NADAMW: running product of the momentum schedule             */
     uint32_t delay_now;         /* the delay in force (am_set_delay)                            */
     uint32_t reserved;
+    uint64_t opt_steps[AM_MAX_REPLICAS];   /* optimizer steps each replica has made             */
+    double   mu_product[AM_MAX_REPLICAS];  /* NADAMW: running product of the momentum schedule  */
 } am_snapshot;
 
 am_status am_export_state(const am_state *st, am_snapshot *out);

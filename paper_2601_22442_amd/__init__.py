@@ -5,4 +5,4 @@ from .binding import (  # noqa: F401
     SUBSET_BERNOULLI, SUBSET_STRATIFIED,
     AsyncMeshError, Config, Snapshot, Stage, init_state, lookahead, make_config, version, workspace_bytes,
 )
-from .schedules import ema_lambda, learning_rate  # noqa: F401,E402
+from .schedules import active_mask, ema_lambda, learning_rate  # noqa: F401,E402

@@ -22,7 +22,7 @@ MSG_F32, MSG_BF16, MSG_E4M3 = 0, 1, 2
 SUBSET_BERNOULLI, SUBSET_STRATIFIED = 0, 1
 
 EXPORTS = (
-    "am_workspace_bytes", "am_init_state", "am_step", "am_step_scaled", "am_grad_sqnorm", "am_sparse_average",
+    "am_workspace_bytes", "am_init_state", "am_step", "am_step_scaled", "am_step_masked", "am_grad_sqnorm", "am_sparse_average",
     "am_lookahead",
     "am_subset_indices", "am_set_delay", "am_diagnostics", "am_read_flags", "am_set_profiling", "am_get_profile", "am_ring_info",
     "am_export_state", "am_resume_state",
@@ -64,8 +64,9 @@ class Snapshot(C.Structure):
     """Mirror of am_snapshot: what the library itself remembers between steps."""
     _fields_ = [
         ("magic", C.c_uint64), ("config_digest", C.c_uint64), ("last_t", C.c_uint64),
-        ("next_lines_step", C.c_uint64), ("mu_product", C.c_double),
+        ("next_lines_step", C.c_uint64),
         ("delay_now", C.c_uint32), ("reserved", C.c_uint32),
+        ("opt_steps", C.c_uint64 * MAX_REPLICAS), ("mu_product", C.c_double * MAX_REPLICAS),
     ]
 
 
@@ -79,6 +80,7 @@ def _load():
     L.am_init_state.argtypes = [C.POINTER(Config), C.POINTER(Buffers), C.c_void_p, C.POINTER(C.c_void_p)]
     L.am_step.argtypes = [C.c_void_p, C.c_uint64, C.POINTER(C.c_void_p), C.c_float, C.c_float, C.c_float]
     L.am_step_scaled.argtypes = [C.c_void_p, C.c_uint64, C.POINTER(C.c_void_p), C.c_float, C.c_float, C.c_float, C.c_void_p]
+    L.am_step_masked.argtypes = [C.c_void_p, C.c_uint64, C.POINTER(C.c_void_p), C.c_float, C.c_float, C.c_float, C.c_void_p, C.c_uint32]
     L.am_grad_sqnorm.argtypes = [C.c_void_p, C.POINTER(C.c_void_p), C.c_void_p]
     L.am_sparse_average.argtypes = [C.c_void_p, C.c_uint64, C.c_float]
     L.am_lookahead.argtypes = [C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p, C.c_uint64, C.c_float, C.c_void_p]
@@ -222,6 +224,16 @@ class Stage:
         table = _ptr_table(grads)
         with torch.cuda.device(self.device):
             _check(lib.am_step_scaled(self._handle, t, table, lr, lambda_t, grad_scale, replica_scale.data_ptr()))
+
+    def step_masked(self, t: int, grads, lr: float, lambda_t: float, active_mask: int, grad_scale: float = 1.0,
+                    replica_scale: torch.Tensor | None = None):
+        """One tick in which only the replicas named by active_mask make a local step (am_step_masked);
+        grads[i] of an idle replica may be None."""
+        assert len(grads) == self.R
+        table = (C.c_void_p * self.R)(*[None if g is None else g.data_ptr() for g in grads])
+        with torch.cuda.device(self.device):
+            _check(lib.am_step_masked(self._handle, t, table, lr, lambda_t, grad_scale,
+                                      None if replica_scale is None else replica_scale.data_ptr(), active_mask))
 
     def grad_sqnorm(self, grads) -> torch.Tensor:
         """am_grad_sqnorm: device tensor of R doubles, sum of squares of each replica's gradient."""

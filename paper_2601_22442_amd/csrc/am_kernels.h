@@ -162,7 +162,12 @@ struct StepArgs {
     //   m' = a_m m + b_m g ;  v' = a_v v + b_v g^2
     //   w^ = w - (c_wd w + (c_g g + c_m m') / (c_v sqrt(v') + eps))           (Adam family)
     //   w^ = w - (c_wd w + c_m m')     resp.     w - (c_wd w + c_g g)          (SGD with / without momentum)
-    double a_m, b_m, a_v, b_v, c_wd, c_g, c_m, c_v, eps;
+    // c_g, c_m, c_v hold the bias corrections and are per replica: replicas of unequal speed have made
+    // unequal numbers of optimizer steps.  A replica whose bit in active_mask is clear makes no local
+    // step in this launch (w^ = w; m, v kept; its gradient pointer is not read).
+    double a_m, b_m, a_v, b_v, c_wd, eps;
+    double c_g[kMaxReplicas], c_m[kMaxReplicas], c_v[kMaxReplicas];
+    uint32_t active_mask;
     uint32_t lookahead;
     double gamma;
     const float *replica_scale;                    // NULL, or one more gradient factor per replica (DEVICE)
@@ -205,7 +210,14 @@ template <int OPT>
 __device__ __forceinline__ void local_step(const StepArgs &a, uint32_t i, const GroupIn &in,
                                            F4 &w_hat, F4 &m_new, F4 &v_new)
 {
-    const double rs = (OPT != kOptNone && a.replica_scale) ? (double)a.replica_scale[i] : 1.0;
+    // A replica that is idle in this tick goes through the same arithmetic with the coefficients of
+    // the identity (m' = m, v' = v, w^ = w exactly); its gradient was not loaded.
+    const bool idle = OPT != kOptNone && !((a.active_mask >> i) & 1u);
+    const double rs = (OPT != kOptNone && a.replica_scale && !idle) ? (double)a.replica_scale[i] : 1.0;
+    const double a_m = idle ? 1.0 : a.a_m, b_m = idle ? 0.0 : a.b_m;
+    const double a_v = idle ? 1.0 : a.a_v, b_v = idle ? 0.0 : a.b_v;
+    const double c_wd = idle ? 0.0 : a.c_wd;
+    const double c_g = a.c_g[i], c_m = a.c_m[i], c_v = a.c_v[i];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         if (OPT == kOptNone) {                                 // averaging only: the caller's w is w^
@@ -216,18 +228,18 @@ __device__ __forceinline__ void local_step(const StepArgs &a, uint32_t i, const 
         const double wo = (double)in.w.v[j];
         double step;                                           // what is subtracted besides the decay
         if (OPT == kOptSgdPlain) {
-            step = a.c_g * gj;
+            step = c_g * gj;
         } else if (OPT == kOptSgdMomentum) {
-            m_new.v[j] = (float)fma(a.a_m, (double)in.m.v[j], a.b_m * gj);
-            step = a.c_m * (double)m_new.v[j];
+            m_new.v[j] = (float)fma(a_m, (double)in.m.v[j], b_m * gj);
+            step = c_m * (double)m_new.v[j];
         } else {
-            m_new.v[j] = (float)fma(a.a_m, (double)in.m.v[j], a.b_m * gj);
-            v_new.v[j] = (float)fma(a.a_v, (double)in.v.v[j], a.b_v * gj * gj);
-            const double den = fma(a.c_v, sqrt_refined(v_new.v[j]), a.eps);
-            const double num = fma(a.c_g, gj, a.c_m * (double)m_new.v[j]);
+            m_new.v[j] = (float)fma(a_m, (double)in.m.v[j], b_m * gj);
+            v_new.v[j] = (float)fma(a_v, (double)in.v.v[j], b_v * gj * gj);
+            const double den = fma(c_v, sqrt_refined(v_new.v[j]), a.eps);
+            const double num = fma(c_g, gj, c_m * (double)m_new.v[j]);
             step = quotient_refined(num, den);
         }
-        w_hat.v[j] = (float)(wo - fma(a.c_wd, wo, step));
+        w_hat.v[j] = (float)(wo - fma(c_wd, wo, idle ? 0.0 : step));
     }
 }
 
@@ -254,8 +266,11 @@ template <int OPT, bool GRAD_BF16>
 __device__ __forceinline__ void load_group(const StepArgs &a, uint32_t i, uint64_t mu, int nvalid, GroupIn &in)
 {
     in.w = load_f32x4(a.w[i], mu, nvalid);
-    in.g = GRAD_BF16 ? load_bf16x4(static_cast<const uint16_t *>(a.g[i]), mu, nvalid)
-                     : load_f32x4(static_cast<const float *>(a.g[i]), mu, nvalid);
+    if ((a.active_mask >> i) & 1u)
+        in.g = GRAD_BF16 ? load_bf16x4(static_cast<const uint16_t *>(a.g[i]), mu, nvalid)
+                         : load_f32x4(static_cast<const float *>(a.g[i]), mu, nvalid);
+    else
+        in.g.v[0] = in.g.v[1] = in.g.v[2] = in.g.v[3] = 0.f;
     if (OPT != kOptSgdPlain) in.m = load_f32x4(a.m[i], mu, nvalid);
     if (OPT == kOptAdam) in.v = load_f32x4(a.v[i], mu, nvalid);
 }

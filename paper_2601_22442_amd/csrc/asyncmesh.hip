@@ -151,7 +151,9 @@ struct am_state {
     uint64_t last_t;
     uint64_t next_lines_step;    // the step whose send subset next_lines() was sized for (0 = none)
     uint32_t delay_now;          // the delay in force (<= cfg.delay, which sizes the ring)
-    double mu_product;           // NAdam: running product of the momentum schedule
+    // per replica, because replicas of unequal speed make unequal numbers of local steps:
+    uint64_t opt_steps[AM_MAX_REPLICAS];     // optimizer steps made so far (the t of the bias corrections)
+    double mu_product[AM_MAX_REPLICAS];      // NAdam: running product of the momentum schedule
     uint64_t threshold;
     // profiling of the fused kernel
     bool profiling;
@@ -292,7 +294,7 @@ am_status am_workspace_bytes(const am_config *cfg, uint64_t *out_bytes)
 
 namespace {
 
-constexpr uint64_t kSnapshotMagic = 0x414D534E41503031ull;     // "AMSNAP01"
+constexpr uint64_t kSnapshotMagic = 0x414D534E41503032ull;     // "AMSNAP02"
 
 // digest (FNV-1a) of the config fields that shape the ring and the subsets
 uint64_t config_digest(const am_config &c)
@@ -347,7 +349,7 @@ am_status create_state(const am_config *cfg, const am_buffers *buf, void *hip_st
     st->last_t = 0;
     st->next_lines_step = 0;
     st->delay_now = cfg->delay;
-    st->mu_product = 1.0;
+    for (uint32_t i = 0; i < AM_MAX_REPLICAS; ++i) { st->opt_steps[i] = 0; st->mu_product[i] = 1.0; }
     st->threshold = subset_threshold(cfg->fraction);
     st->profiling = false;
     st->ev_used = 0;
@@ -404,7 +406,7 @@ am_status am_export_state(const am_state *st, am_snapshot *out)
     out->config_digest = config_digest(st->cfg);
     out->last_t = st->last_t;
     out->next_lines_step = st->next_lines_step;
-    out->mu_product = st->mu_product;
+    for (uint32_t i = 0; i < AM_MAX_REPLICAS; ++i) { out->opt_steps[i] = st->opt_steps[i]; out->mu_product[i] = st->mu_product[i]; }
     out->delay_now = st->delay_now;
     out->reserved = 0;
     return AM_OK;
@@ -418,12 +420,13 @@ am_status am_resume_state(const am_config *cfg, const am_buffers *buf, void *hip
     if (snapshot->magic != kSnapshotMagic) return fail(AM_EINVAL, "snapshot has an unknown layout (magic %016llx)", (unsigned long long)snapshot->magic);
     if (snapshot->config_digest != config_digest(*cfg)) return fail(AM_EINVAL, "snapshot was exported under a different config (n, replicas, delay, avg_interval, optimizer, fraction, seed or subset rule differ)");
     if (snapshot->delay_now > cfg->delay) return fail(AM_EINVAL, "snapshot delay %u exceeds the configured delay %u", snapshot->delay_now, cfg->delay);
-    if (!(snapshot->mu_product >= 0.0 && snapshot->mu_product <= 1.0)) return fail(AM_EINVAL, "snapshot mu_product=%g not in [0, 1]", snapshot->mu_product);
+    for (uint32_t i = 0; i < AM_MAX_REPLICAS; ++i)
+        if (!(snapshot->mu_product[i] >= 0.0 && snapshot->mu_product[i] <= 1.0)) return fail(AM_EINVAL, "snapshot mu_product[%u]=%g not in [0, 1]", i, snapshot->mu_product[i]);
     am_state *st = nullptr;
     if (am_status s = create_state(cfg, buf, hip_stream, &st)) return s;
     st->last_t = snapshot->last_t;
     st->next_lines_step = snapshot->next_lines_step;
-    st->mu_product = snapshot->mu_product;
+    for (uint32_t i = 0; i < AM_MAX_REPLICAS; ++i) { st->opt_steps[i] = snapshot->opt_steps[i]; st->mu_product[i] = snapshot->mu_product[i]; }
     st->delay_now = snapshot->delay_now;
     *out = st;
     return AM_OK;
@@ -457,8 +460,14 @@ am_status am_grad_sqnorm(am_state *st, const void *const *grads, double *dev_out
     return AM_OK;
 }
 
-am_status am_step_scaled(am_state *st, uint64_t t, const void *const *grads, float lr, float lambda_t,
-                         float grad_scale, const float *dev_replica_scale)
+}  // extern "C"
+
+namespace {
+
+// One step (active == nullptr: every replica steps and its optimizer step count becomes t) or one
+// tick of the heterogeneous set-up (bit i of *active: replica i makes a local step and counts it).
+am_status step_impl(am_state *st, uint64_t t, const void *const *grads, float lr, float lambda_t,
+                    float grad_scale, const float *dev_replica_scale, const uint32_t *active)
 {
     if (!st) return fail(AM_EINVAL, "state is NULL");
     if (!aligned(dev_replica_scale, 4)) return fail(AM_EALIGN, "dev_replica_scale is not 4-byte aligned");
@@ -467,8 +476,12 @@ am_status am_step_scaled(am_state *st, uint64_t t, const void *const *grads, flo
     if (!(lambda_t >= 0.f && lambda_t <= 1.f)) return fail(AM_EINVAL, "lambda_t=%g not in [0, 1]", lambda_t);
     if (!std::isfinite(lr) || !std::isfinite(grad_scale)) return fail(AM_EINVAL, "lr / grad_scale not finite");
     const am_config &c = st->cfg;
+    const uint32_t all = c.replicas == 32 ? 0xFFFFFFFFu : ((1u << c.replicas) - 1u);
+    if (active && (*active & ~all)) return fail(AM_EINVAL, "active_mask=%08x names replicas beyond %u", *active, c.replicas);
+    const uint32_t mask = active ? *active : all;
     const uintptr_t galign = c.grad_dtype == AM_BF16 ? 8 : 16;
     for (uint32_t i = 0; i < c.replicas; ++i) {
+        if (!((mask >> i) & 1u)) continue;                       // an idle replica's gradient is not read
         if (!grads[i]) return fail(AM_EINVAL, "grads[%u] is NULL", i);
         if (!aligned(grads[i], galign)) return fail(AM_EALIGN, "grads[%u] is not %u-byte aligned", i, (unsigned)galign);
     }
@@ -481,28 +494,41 @@ am_status am_step_scaled(am_state *st, uint64_t t, const void *const *grads, flo
     }
     a.lookahead = c.lookahead != 0; a.gamma = (double)c.gamma;
     a.replica_scale = dev_replica_scale;
+    a.active_mask = mask;
     const double gs = (double)grad_scale;        // folded into the coefficients that multiply g
 
-    // per-step scalars, evaluated once in double
+    // per-step scalars, evaluated once in double; those that depend on a replica's own step count per replica
     const double b1 = c.beta1, b2 = c.beta2, lrd = lr, wd = c.weight_decay;
-    double mu_prod_next = st->mu_product;
+    uint64_t steps_next[AM_MAX_REPLICAS];
+    double mu_prod_next[AM_MAX_REPLICAS];
     a.c_wd = lrd * wd;
     a.eps = (double)c.eps;
     if (c.optimizer == AM_OPT_SGD) {
-        a.a_m = b1; a.b_m = gs; a.c_m = lrd; a.c_g = lrd * gs;
+        a.a_m = b1; a.b_m = gs;
     } else {
-        const double bc1 = 1.0 - std::pow(b1, (double)t), bc2 = 1.0 - std::pow(b2, (double)t);
         a.a_m = b1; a.b_m = (1.0 - b1) * gs;
         a.a_v = b2; a.b_v = (1.0 - b2) * gs * gs;
-        a.c_v = 1.0 / std::sqrt(bc2);
+    }
+    for (uint32_t i = 0; i < c.replicas; ++i) {
+        steps_next[i] = st->opt_steps[i];
+        mu_prod_next[i] = st->mu_product[i];
+        if (!((mask >> i) & 1u)) continue;
+        const uint64_t k = active ? st->opt_steps[i] + 1 : t;
+        steps_next[i] = k;
+        if (c.optimizer == AM_OPT_SGD) {
+            a.c_m[i] = lrd; a.c_g[i] = lrd * gs;
+            continue;
+        }
+        const double bc1 = 1.0 - std::pow(b1, (double)k), bc2 = 1.0 - std::pow(b2, (double)k);
+        a.c_v[i] = 1.0 / std::sqrt(bc2);
         if (c.optimizer == AM_OPT_ADAMW) {
-            a.c_g = 0.0; a.c_m = lrd / bc1;
+            a.c_g[i] = 0.0; a.c_m[i] = lrd / bc1;
         } else {
-            const double mu_t = b1 * (1.0 - 0.5 * std::pow(0.96, (double)t * c.momentum_decay));
-            const double mu_t1 = b1 * (1.0 - 0.5 * std::pow(0.96, (double)(t + 1) * c.momentum_decay));
-            mu_prod_next = st->mu_product * mu_t;
-            a.c_g = lrd * (1.0 - mu_t) / (1.0 - mu_prod_next) * gs;
-            a.c_m = lrd * mu_t1 / (1.0 - mu_prod_next * mu_t1);
+            const double mu_t = b1 * (1.0 - 0.5 * std::pow(0.96, (double)k * c.momentum_decay));
+            const double mu_t1 = b1 * (1.0 - 0.5 * std::pow(0.96, (double)(k + 1) * c.momentum_decay));
+            mu_prod_next[i] = st->mu_product[i] * mu_t;
+            a.c_g[i] = lrd * (1.0 - mu_t) / (1.0 - mu_prod_next[i]) * gs;
+            a.c_m[i] = lrd * mu_t1 / (1.0 - mu_prod_next[i] * mu_t1);
         }
     }
 
@@ -537,8 +563,24 @@ am_status am_step_scaled(am_state *st, uint64_t t, const void *const *grads, flo
     }
     st->last_t = t;
     if (do_next) st->next_lines_step = t + 1;
-    st->mu_product = mu_prod_next;
+    for (uint32_t i = 0; i < c.replicas; ++i) { st->opt_steps[i] = steps_next[i]; st->mu_product[i] = mu_prod_next[i]; }
     return AM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+am_status am_step_scaled(am_state *st, uint64_t t, const void *const *grads, float lr, float lambda_t,
+                         float grad_scale, const float *dev_replica_scale)
+{
+    return step_impl(st, t, grads, lr, lambda_t, grad_scale, dev_replica_scale, nullptr);
+}
+
+am_status am_step_masked(am_state *st, uint64_t t, const void *const *grads, float lr, float lambda_t,
+                         float grad_scale, const float *dev_replica_scale, uint32_t active_mask)
+{
+    return step_impl(st, t, grads, lr, lambda_t, grad_scale, dev_replica_scale, &active_mask);
 }
 
 am_status am_sparse_average(am_state *st, uint64_t t, float lambda_t)

@@ -542,6 +542,65 @@ def test_two_states_do_not_interfere(amlib):
     compare(a, oa, "state a"); compare(b, ob, "state b")
 
 
+@pytest.mark.parametrize("speeds,opt,bf16", [
+    ([2, 1, 2, 3], O.OPT_ADAMW, False), ([5, 3, 1, 11], O.OPT_NADAMW, False), ([1, 2, 1, 2, 1, 2, 1, 2, 2, 1], O.OPT_ADAMW, True),
+    ([3, 1], O.OPT_SGD, False),
+])
+def test_replicas_of_unequal_speed(amlib, speeds, opt, bf16):
+    """Heterogeneous set-up: ticks in which only some replicas make a local step, the averaging
+    interval equal to the round length."""
+    am = amlib
+    n, R, K, seed = 40_009, len(speeds), max(speeds), 41
+    kw = dict(delay=1, avg_interval=K, fraction=0.2, seed=seed, optimizer=opt, lookahead=(opt == O.OPT_ADAMW), gamma=0.9)
+    st, orc = make_pair(am, n, R, grad_bf16=bf16, fwd_bf16=bf16, **kw)
+    for t in range(1, 3 * K + 2):
+        mask = am.active_mask(t, speeds)
+        g, gd = grads_for(n, R, t, seed, bf16)
+        g = [x if (mask >> i) & 1 else None for i, x in enumerate(g)]
+        gd = [x if (mask >> i) & 1 else None for i, x in enumerate(gd)]
+        st.step_masked(t, gd, 1e-3, 0.5, mask)
+        orc.step_masked(t, g, 1e-3, 0.5, mask)
+        if t % K <= 1:
+            compare(st, orc, f"speeds={speeds} t={t}")
+    assert any(np.any(orc.d(i)) for i in range(R))
+    with pytest.raises(am.AsyncMeshError):
+        st.step_masked(3 * K + 2, gd, 1e-3, 0.5, 1 << R)               # names a replica that does not exist
+
+
+def test_idle_replica_ignores_its_gradient_pointer_and_scale(amlib):
+    am = amlib
+    n, R, seed = 20_011, 3, 47
+    st, orc = make_pair(am, n, R, delay=1, fraction=0.3, seed=seed, lookahead=True, gamma=0.9)
+    scale = np.array([0.5, np.nan, 2.0], dtype=np.float32)
+    scale_dev = torch.from_numpy(scale).cuda()
+    for t in range(1, 5):
+        g, gd = grads_for(n, R, t, seed, False)
+        mask = 0b101 if t != 3 else 0b111
+        sc = scale if t != 3 else np.array([0.5, 1.5, 2.0], dtype=np.float32)
+        scale_dev.copy_(torch.from_numpy(sc))
+        if t != 3:
+            g[1], gd[1] = None, None
+        st.step_masked(t, gd, 1e-3, 0.5, mask, grad_scale=0.75, replica_scale=scale_dev)
+        orc.step_masked(t, g, 1e-3, 0.5, mask, grad_scale=0.75, replica_scale=sc)
+        compare(st, orc, f"t={t}")
+
+
+def test_all_active_ticks_are_ordinary_steps(amlib):
+    am = amlib
+    n, R, seed = 30_011, 3, 43
+    kw = dict(delay=1, fraction=0.2, seed=seed, optimizer=O.OPT_NADAMW)
+    a, _ = make_pair(am, n, R, **kw)
+    b, _ = make_pair(am, n, R, **kw)
+    for t in range(1, 6):
+        _, gd = grads_for(n, R, t, seed, False)
+        a.step(t, gd, 1e-3, 0.5)
+        b.step_masked(t, gd, 1e-3, 0.5, 0b111)
+    torch.cuda.synchronize()
+    for name in ("w", "m", "v", "d"):
+        for i in range(R):
+            assert torch.equal(getattr(a, name)[i], getattr(b, name)[i]), (name, i)
+
+
 @pytest.mark.parametrize("opt,K", [(O.OPT_NADAMW, 1), (O.OPT_ADAMW, 2)])
 def test_checkpoint_and_resume(amlib, opt, K):
     """A run that is checkpointed after step 5 and resumed on other memory continues bit for bit as
@@ -551,9 +610,10 @@ def test_checkpoint_and_resume(amlib, opt, K):
     kw = dict(delay=tau, avg_interval=K, fraction=0.1, seed=seed, optimizer=opt, lookahead=(opt != O.OPT_NADAMW), gamma=0.9)
     a, orc = make_pair(am, n, R, **kw)
     saved = None
+    mask_at = lambda t: 0b1111 if (t % 2 or opt != O.OPT_NADAMW) else 0b1011    # NADAMW case: replica 2 idles in even ticks
     for t in range(1, total + 1):
         g, gd = grads_for(n, R, t, seed, False)
-        a.step(t, gd, 1e-3, 0.5); orc.step(t, g, 1e-3, 0.5)
+        a.step_masked(t, gd, 1e-3, 0.5, mask_at(t)); orc.step_masked(t, g, 1e-3, 0.5, mask_at(t))
         if t == 3:
             a.set_delay(1); orc.set_delay(1)
         if t == 5:
@@ -566,8 +626,9 @@ def test_checkpoint_and_resume(amlib, opt, K):
     b = am.Stage.resume(a.cfg, snap, w, m, v, d, fwd, ws)
     with pytest.raises(am.AsyncMeshError):
         b.step(5, grads_for(n, R, 5, seed, False)[1], 1e-3, 0.5)           # the step counter came back too
+    assert list(snap.opt_steps[:R]) == ([5, 5, 3, 5] if opt == O.OPT_NADAMW else [5] * R)
     for t in range(6, total + 1):
-        b.step(t, grads_for(n, R, t, seed, False)[1], 1e-3, 0.5)
+        b.step_masked(t, grads_for(n, R, t, seed, False)[1], 1e-3, 0.5, mask_at(t))
     torch.cuda.synchronize()
     for name in ("w", "m", "v", "d", "fwd"):
         if getattr(a, name) is not None:

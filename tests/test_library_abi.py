@@ -119,7 +119,7 @@ def test_snapshot_record_layout_and_checks(amlib):
     """am_resume_state looks at the record before it looks at the device."""
     am = amlib
     from paper_2601_22442_amd import binding as B
-    assert C.sizeof(B.Snapshot) == 48 and B.Snapshot.mu_product.offset == 32 and B.Snapshot.delay_now.offset == 40
+    assert C.sizeof(B.Snapshot) == 40 + 2 * 8 * 32 and B.Snapshot.delay_now.offset == 32 and B.Snapshot.opt_steps.offset == 40
     cfg = am.make_config(1000, 2, delay=1, fraction=0.1)
     h = C.c_void_p(None)
     bufs = B.Buffers()
@@ -127,8 +127,26 @@ def test_snapshot_record_layout_and_checks(amlib):
     snap = B.Snapshot(magic=123)
     assert B.lib.am_resume_state(C.byref(cfg), C.byref(bufs), None, C.byref(snap), C.byref(h)) == -1
     assert "layout" in B.lib.am_last_error().decode()
-    snap = B.Snapshot(magic=0x414D534E41503031, config_digest=1)
+    snap = B.Snapshot(magic=0x414D534E41503032, config_digest=1)
     assert B.lib.am_resume_state(C.byref(cfg), C.byref(bufs), None, C.byref(snap), C.byref(h)) == -1
     assert "different config" in B.lib.am_last_error().decode()
     assert B.lib.am_resume_state(C.byref(cfg), C.byref(bufs), None, None, C.byref(h)) == -1
     assert not h.value
+
+
+def test_active_mask_schedule_of_the_heterogeneous_setup():
+    """Replica i steps speeds[i] times per round of max(speeds) ticks, the fastest in every tick."""
+    from paper_2601_22442_amd.schedules import active_mask
+    for speeds in ([1, 1, 1, 1], [2, 1, 2, 3], [5, 3, 1, 11], [10, 8, 1, 21]):
+        K = max(speeds)
+        counts = [0] * len(speeds)
+        for t in range(1, 3 * K + 1):
+            m = active_mask(t, speeds)
+            assert m & (1 << speeds.index(K))
+            for i in range(len(speeds)):
+                counts[i] += (m >> i) & 1
+            if t % K == 0:
+                assert counts == [s * (t // K) for s in speeds]
+    assert [active_mask(t, [1, 3]) for t in (1, 2, 3, 4)] == [0b10, 0b10, 0b11, 0b10]
+    with pytest.raises(ValueError):
+        active_mask(1, [0, 2])
