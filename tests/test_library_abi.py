@@ -150,3 +150,19 @@ def test_active_mask_schedule_of_the_heterogeneous_setup():
     assert [active_mask(t, [1, 3]) for t in (1, 2, 3, 4)] == [0b10, 0b10, 0b11, 0b10]
     with pytest.raises(ValueError):
         active_mask(1, [0, 2])
+
+
+def test_no_fallback_without_the_library(tmp_path):
+    """In a tree where nothing is built the builder imports, and the first use of the binding fails loudly."""
+    import shutil
+    import subprocess
+    import sys
+    pkg = tmp_path / "paper_2601_22442_amd"
+    pkg.mkdir()
+    for f in ("__init__.py", "binding.py", "schedules.py", "build.py"):
+        shutil.copy(ROOT / "paper_2601_22442_amd" / f, pkg / f)
+    code = ("import paper_2601_22442_amd as am; from paper_2601_22442_amd.build import LIB; assert not LIB.exists()\n"
+            "assert am.active_mask(1, [1, 2]) == 2\n"
+            "try:\n    am.make_config(10, 2)\nexcept ImportError as e:\n    assert 'no fallback' in str(e); print('refused')\n")
+    out = subprocess.run([sys.executable, "-c", code], cwd=tmp_path, capture_output=True, text=True)
+    assert out.returncode == 0 and "refused" in out.stdout, out.stderr
