@@ -166,3 +166,46 @@ def test_no_fallback_without_the_library(tmp_path):
             "try:\n    am.make_config(10, 2)\nexcept ImportError as e:\n    assert 'no fallback' in str(e); print('refused')\n")
     out = subprocess.run([sys.executable, "-c", code], cwd=tmp_path, capture_output=True, text=True)
     assert out.returncode == 0 and "refused" in out.stdout, out.stderr
+
+
+def test_header_is_plain_c_and_the_binding_mirrors_its_layout(amlib, tmp_path):
+    """A C11 program that includes the header, links the library, prints the layout the C compiler
+    gives the structs and makes two host-only calls."""
+    import subprocess
+    from paper_2601_22442_amd import binding as B
+    src = tmp_path / "abi.c"
+    src.write_text(r"""
+#include <stddef.h>
+#include <stdio.h>
+#include "asyncmesh.h"
+int main(void) {
+    printf("%zu %zu %zu %zu %zu\n", sizeof(am_config), offsetof(am_config, fraction), offsetof(am_config, momentum_decay),
+           offsetof(am_config, subset_kind), sizeof(am_buffers));
+    printf("%zu %zu %zu\n", sizeof(am_snapshot), offsetof(am_snapshot, opt_steps), offsetof(am_snapshot, mu_product));
+    am_config c = {0};
+    c.n = 125829120u; c.replicas = 8; c.delay = 4; c.avg_interval = 1; c.optimizer = AM_OPT_ADAMW; c.fraction = 0.05;
+    c.beta1 = 0.9f; c.beta2 = 0.999f; c.eps = 1e-8f; c.correction = AM_CORR_EMA;
+    uint64_t bytes = 0;
+    am_status s = am_workspace_bytes(&c, &bytes);
+    printf("%d %llu\n", (int)s, (unsigned long long)bytes);
+    c.replicas = 99;
+    s = am_workspace_bytes(&c, &bytes);
+    printf("%d %s\n", (int)s, am_last_error());
+    return 0;
+}
+""")
+    exe = tmp_path / "abi"
+    lib_dir = ROOT / "paper_2601_22442_amd"
+    subprocess.run(["gcc", "-std=c11", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", str(ROOT / "include"), "-o", str(exe), str(src),
+                    "-L", str(lib_dir), "-lasyncmesh", f"-Wl,-rpath,{lib_dir}"], check=True)
+    out = subprocess.run([str(exe)], capture_output=True, text=True, check=True).stdout.splitlines()
+    assert out[0].split() == [str(C.sizeof(B.Config)), str(B.Config.fraction.offset), str(B.Config.momentum_decay.offset),
+                              str(B.Config.subset_kind.offset), str(C.sizeof(B.Buffers))]
+    assert out[1].split() == [str(C.sizeof(B.Snapshot)), str(B.Snapshot.opt_steps.offset), str(B.Snapshot.mu_product.offset)]
+    status, nbytes = out[2].split()
+    assert status == "0" and int(nbytes) == am_bytes(amlib)
+    assert out[3].startswith("-1 ") and "replicas" in out[3]
+
+
+def am_bytes(am):
+    return am.workspace_bytes(am.make_config(125_829_120, 8, delay=4, fraction=0.05))
