@@ -718,3 +718,21 @@ def test_step_order_is_enforced():
     orc = O.Oracle(4, 1)
     with pytest.raises(ValueError):
         orc.step(2, si.replica_grads(4, 1, 1), 1e-3)
+
+
+def test_oracle_is_clean_under_address_and_undefined_behaviour_sanitizers(tmp_path):
+    """Host-side check of the checker itself: every mode on small ragged sizes, no out-of-bounds
+    access, no undefined behaviour, no leak."""
+    import os
+    import subprocess
+    from pathlib import Path
+    root = Path(__file__).resolve().parent.parent
+    exe = tmp_path / "drive"
+    subprocess.run(["gcc", "-O1", "-g", "-std=c11", "-fopenmp", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+                    "-I", str(root / "oracle"), "-o", str(exe), str(root / "tests" / "oracle_sanitizer_driver.c"), "-lm"], check=True)
+    env = dict(os.environ, ASAN_OPTIONS="verify_asan_link_order=0:detect_leaks=1", OMP_NUM_THREADS="2")
+    out = subprocess.run([str(exe)], capture_output=True, text=True, env=env)
+    if out.returncode != 0 and "AddressSanitizer" in out.stderr and "runtime does not come first" in out.stderr:
+        pytest.skip("the sanitizer runtime cannot start in this environment")
+    assert out.returncode == 0, out.stderr[-2000:]
+    assert len(out.stdout.splitlines()) == 30
