@@ -176,7 +176,7 @@ def test_block_granule_variant(amlib):
     run_steps(am, 1000, 3, 6, delay=0, fraction=0.3, seed=2, subset_granule=32)
     run_steps(am, 4099, 8, 6, delay=1, fraction=1.0, seed=2, subset_granule=32)
 
-@pytest.mark.parametrize("p", [0.05, 0.3, 1.0 / 256, 1.0 / 1000, 1.0])
+@pytest.mark.parametrize("p", [0.05, 0.3, 0.6, 1.0 / 256, 1.0 / 1000, 1.0])
 def test_stratified_variant(amlib, p):
     """Variant sampling: exactly one coordinate of every aligned block of round(1/p) (indices bit-exact,
     state to the fp32 bar); block lengths below, at and above the tile length, and a cut last block."""

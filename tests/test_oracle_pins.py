@@ -110,7 +110,7 @@ def test_stratified_variant_has_exact_size_and_the_marginal_probability():
     """Variant (not the paper's independent draws): one coordinate out of every aligned block of
     B = round(1/p).  Exact size, offsets written out from the generator word of block b, every
     offset equally likely, and the averaging itself unchanged."""
-    assert [O.block_size(p) for p in (1.0, 0.5, 0.3, 0.05, 0.01, 1e-3)] == [1, 2, 3, 20, 100, 1000]
+    assert [O.block_size(p) for p in (1.0, 0.6, 0.5, 0.4, 0.3, 0.05, 0.01, 1e-3)] == [1, 2, 2, 3, 3, 20, 100, 1000]   # nearest, halves up
     seed, s, p = 21, 6, 0.05
     B = 20
     for n in (20 * 500, 20 * 500 + 7):
