@@ -236,8 +236,9 @@ def main():
 
 # HBM bytes per launch of the fused kernel measured with rocprofv3 hardware counters (FETCH_SIZE and
 # WRITE_SIZE, each scaled by what the same counter reads for a plain copy of known size: x2.0 and
-# x1.0 on gfx950); the runs are in profiles/k_step_stage125m.md.  None = not measured for that workload.
-MEASURED_TRAFFIC: dict = {"stage125m": 39.79e9}
+# x1.0 on gfx950); the runs are in profiles/k_step_stage125m.md and profiles/k_step_other_workloads.md.
+# None = not measured for that workload.
+MEASURED_TRAFFIC: dict = {"stage125m": 39.79e9, "bf16": 62.74e9, "model1b": 327.06e9}
 
 
 if __name__ == "__main__":
