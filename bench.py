@@ -229,6 +229,14 @@ def main():
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": MEASURED_TRAFFIC.get(args.workload),
                      "kernel_ms": kernel_s * 1e3, "algorithmic_bytes_per_launch": bytes_per_launch},
     }
+    traffic = MEASURED_TRAFFIC.get(args.workload)
+    if traffic is not None and p == WORKLOADS[args.workload]["p"] and tau == WORKLOADS[args.workload]["tau"] \
+            and args.avg_interval == 1 and not args.no_correction and args.subset_granule == 1 and args.subset_kind == "bernoulli":
+        # the counter-measured bytes of this very configuration over this run's kernel time
+        out["roofline"]["traffic_GBps"] = traffic / kernel_s / 1e9
+        out["roofline"]["traffic_frac"] = traffic / kernel_s / 1e9 / HBM_PEAK_GBPS
+    else:
+        out["roofline"]["traffic"] = None             # the stored figure is for the workload's own settings
     if not args.skip_cpu:
         out["cpu_baseline"] = cpu_baseline(w, args, st, gsets, t, w_pool_host)
     print(json.dumps(out))
