@@ -601,6 +601,46 @@ def test_all_active_ticks_are_ordinary_steps(amlib):
             assert torch.equal(getattr(a, name)[i], getattr(b, name)[i]), (name, i)
 
 
+@pytest.mark.parametrize("case", range(96))
+def test_random_configurations(amlib, case):
+    """Seeded random draws over the whole configuration space (sizes, replicas, delay, interval,
+    fraction, optimizer, correction, message precision, sampling rule, dtypes, idle replicas)."""
+    am = amlib
+    rng = np.random.default_rng(1000 + case)
+    n = int(rng.choice([1, 7, 255, 256, 257, 1023, int(rng.integers(1, 200_000)), int(rng.integers(1, 200_000))]))
+    R = int(rng.integers(1, 13)) if rng.integers(0, 4) else int(rng.integers(13, 33))
+    tau, K = int(rng.integers(0, 4)), int(rng.integers(1, 4))
+    p = float(rng.choice([0.003, 0.05, 0.3, 0.9, 1.0]))
+    opt = int(rng.choice([O.OPT_SGD, O.OPT_ADAMW, O.OPT_NADAMW]))
+    rule = int(rng.integers(0, 3))                       # 0 independent, 1 whole lines, 2 stratified
+    bf16 = bool(rng.integers(0, 2))
+    kw = dict(delay=tau, avg_interval=K, fraction=p, seed=int(rng.integers(0, 2 ** 62)), optimizer=opt,
+              beta1=float(rng.choice([0.0, 0.9])) if opt == O.OPT_SGD else 0.9,
+              lookahead=bool(rng.integers(0, 2)) and opt != O.OPT_NADAMW, gamma=0.9,
+              correction=int(rng.choice([O.CORR_NONE, O.CORR_EMA, O.CORR_EAGER])),
+              msg_dtype=int(rng.choice([O.MSG_F32, O.MSG_BF16, O.MSG_E4M3])),
+              subset_granule=32 if rule == 1 else 1,
+              subset_kind=am.SUBSET_STRATIFIED if rule == 2 else am.SUBSET_BERNOULLI)
+    print(f"case {case}: n={n} R={R} bf16={bf16} {kw}", flush=True)
+    st, orc = make_pair(am, n, R, grad_bf16=bf16, fwd_bf16=bf16, **kw)
+    if st.fwd is not None:                       # am_sparse_average leaves fwd alone; the oracle's starts at zero
+        for f in st.fwd:
+            f.zero_()
+    masked = bool(rng.integers(0, 2))
+    for t in range(1, (tau + 2) * K + 3):
+        g, gd = grads_for(n, R, t, case, bf16)
+        lam, lr = float(rng.choice([0.0, 0.01, 0.5, 1.0])), float(rng.choice([1e-4, 3e-3]))
+        if masked:
+            mask = int(rng.integers(0, 1 << R))
+            st.step_masked(t, gd, lr, lam, mask, grad_scale=0.5)
+            orc.step_masked(t, g, lr, lam, mask, grad_scale=0.5)
+        elif rng.integers(0, 4) == 0:
+            st.sparse_average(t, lam); orc.sparse_average(t, lam)
+        else:
+            st.step(t, gd, lr, lam); orc.step(t, g, lr, lam)
+        compare(st, orc, f"case {case} t={t}")
+
+
 @pytest.mark.parametrize("opt,K", [(O.OPT_NADAMW, 1), (O.OPT_ADAMW, 2)])
 def test_checkpoint_and_resume(amlib, opt, K):
     """A run that is checkpointed after step 5 and resumed on other memory continues bit for bit as
