@@ -601,6 +601,25 @@ def test_all_active_ticks_are_ordinary_steps(amlib):
             assert torch.equal(getattr(a, name)[i], getattr(b, name)[i]), (name, i)
 
 
+def test_a_thousand_steps_stay_within_the_bar(amlib):
+    """Rounding must not random-walk: the tiny configuration (1,048,576 x 4, delay 1, 5 %) with
+    look-ahead for 1000 steps, eight gradient sets cycled, schedules of the paper's set-up."""
+    am = amlib
+    n, R, seed, steps = 1_048_576, 4, 0, 1000
+    st, orc = make_pair(am, n, R, delay=1, fraction=0.05, seed=seed, lookahead=True, gamma=0.9)
+    pool = [grads_for(n, R, 100 + k, seed, False) for k in range(8)]
+    worst = {}
+    for t in range(1, steps + 1):
+        g, gd = pool[t % 8]
+        lr = am.learning_rate(t, steps, warmup=100)
+        lam = am.ema_lambda(t, steps, hold=300)
+        st.step(t, gd, lr, lam); orc.step(t, g, lr, lam)
+        if t % 250 == 0:
+            worst = compare(st, orc, f"t={t}")
+            print(f"  t={t}", {k: f"{v:.1e}" for k, v in worst.items()}, flush=True)
+    assert max(worst.values()) < TOL_F32
+
+
 @pytest.mark.parametrize("case", range(96))
 def test_random_configurations(amlib, case):
     """Seeded random draws over the whole configuration space (sizes, replicas, delay, interval,
