@@ -133,7 +133,7 @@ typedef struct {
 /* Bytes of workspace a configuration needs.  The delay ring inside it holds tau+1 slots; in a
  * slot every tile of 256 coordinates owns, per replica, ceil(X/32) whole 128-byte lines, X its
  * number of selected coordinates; a slot has room for the expected number of lines plus twelve
- * standard deviations. */
+ * standard deviations (stratified sampling: exactly what the fullest tile can need, times the tiles). */
 am_status am_workspace_bytes(const am_config *cfg, uint64_t *out_bytes);
 
 /* Validate, bind the caller's buffers and the stream, and enqueue the zeroing of m, v, d (d^0 = 0,
@@ -154,6 +154,9 @@ am_status am_step(am_state *st, uint64_t t, const void *const *grads,
  * kernel: g_i <- grad_scale * replica_scale[i] * g_i.  For global-norm clipping (norm 1 in the
  * paper's set-up) without a host round trip: am_grad_sqnorm gives the stage's share of each
  * replica's squared norm, the caller turns the norms of all stages into factors on the device. */
+am_status am_step_scaled(am_state *st, uint64_t t, const void *const *grads, float lr, float lambda_t,
+                         float grad_scale, const float *dev_replica_scale);
+
 /* One tick of the heterogeneous set-up (Sec. "Heterogeneous setup" and its appendix paragraph:
  * devices of unequal speed; the averaging interval is proportional to the device speed, so faster
  * devices make more iterations between two averaging steps).  The R replicas advance in lock-step
@@ -167,8 +170,6 @@ am_status am_step(am_state *st, uint64_t t, const void *const *grads,
 am_status am_step_masked(am_state *st, uint64_t t, const void *const *grads, float lr, float lambda_t,
                          float grad_scale, const float *dev_replica_scale, uint32_t active_mask);
 
-am_status am_step_scaled(am_state *st, uint64_t t, const void *const *grads, float lr, float lambda_t,
-                         float grad_scale, const float *dev_replica_scale);
 
 /* dev_out[i] (DEVICE, R doubles) = sum over the stage of g_i[mu]^2.  grads as for am_step.
  * Deterministic (fixed reduction order). */
