@@ -200,6 +200,20 @@ am_status am_diagnostics(am_state *st, double *dev_out3);
 am_status am_subset_indices(am_state *st, uint64_t t, uint64_t *dev_out, uint64_t capacity,
                             uint64_t *dev_count);
 
+/* am_subset_indices for callers that cannot allocate: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, same result bit for bit, but the
+ * per-tile offsets the three kernels share live in a static device array of the library
+ * (2 MiB + 4.25 KiB, held by every GPU the library runs on until the process ends; its device
+ * address is looked up once per device at am_init_state / am_resume_state) instead of the
+ * caller's workspace, and the call allocates nothing, on the device or on the host.
+ * Limit: n <= 2^27 = 134,217,728 coordinates; a larger stage is refused with AM_EINVAL (use
+ * am_subset_indices).  The device that was current at am_init_state must be current (AM_EINVAL
+ * otherwise).  Every call on one GPU uses that GPU's one array: calls that overlap on a GPU (two
+ * states on different streams, two threads) race on it -- serialise them.  Nothing in the array has
+ * to start at zero: every word a call reads it has written first. */
+am_status am_subset_indices_static(am_state *st, uint64_t t, uint64_t *dev_out, uint64_t capacity,
+                                   uint64_t *dev_count);
+
 /* Synchronises the stream and returns sticky flags: bit 0 = some S^t needed more lines than a
  * ring slot holds (the tiles past the capacity were left out of that round's average). */
 am_status am_read_flags(am_state *st, uint32_t *out_flags);

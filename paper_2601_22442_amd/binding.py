@@ -24,7 +24,7 @@ SUBSET_BERNOULLI, SUBSET_STRATIFIED = 0, 1
 EXPORTS = (
     "am_workspace_bytes", "am_init_state", "am_step", "am_step_scaled", "am_step_masked", "am_grad_sqnorm", "am_sparse_average",
     "am_lookahead",
-    "am_subset_indices", "am_set_delay", "am_diagnostics", "am_read_flags", "am_set_profiling", "am_get_profile", "am_ring_info",
+    "am_subset_indices", "am_subset_indices_static", "am_set_delay", "am_diagnostics", "am_read_flags", "am_set_profiling", "am_get_profile", "am_ring_info",
     "am_export_state", "am_resume_state",
     "am_destroy", "am_last_error", "am_version",
 )
@@ -85,6 +85,7 @@ def _load():
     L.am_sparse_average.argtypes = [C.c_void_p, C.c_uint64, C.c_float]
     L.am_lookahead.argtypes = [C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p, C.c_uint64, C.c_float, C.c_void_p]
     L.am_subset_indices.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint64, C.c_void_p]
+    L.am_subset_indices_static.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint64, C.c_void_p]
     L.am_set_delay.argtypes = [C.c_void_p, C.c_uint32]
     L.am_diagnostics.argtypes = [C.c_void_p, C.c_void_p]
     L.am_read_flags.argtypes = [C.c_void_p, C.POINTER(C.c_uint32)]
@@ -256,6 +257,15 @@ class Stage:
             _check(lib.am_subset_indices(self._handle, t, out.data_ptr(), cap, count.data_ptr()))
         k = int(count.item())
         return out[:min(k, cap)], k
+
+    def subset_indices_static(self, t: int, out: torch.Tensor, count: torch.Tensor):
+        """am_subset_indices_static: the variant that allocates nothing.  out (int64, its length is
+        the capacity) and count (int64, one element) are the caller's device tensors; nothing is
+        read back."""
+        assert out.is_cuda and out.dtype == torch.int64 and out.is_contiguous()
+        assert count.is_cuda and count.dtype == torch.int64 and count.numel() == 1
+        with torch.cuda.device(self.device):
+            _check(lib.am_subset_indices_static(self._handle, t, out.data_ptr(), out.numel(), count.data_ptr()))
 
     def set_delay(self, tau: int):
         _check(lib.am_set_delay(self._handle, tau))

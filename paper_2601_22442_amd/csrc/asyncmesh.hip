@@ -17,6 +17,19 @@
 
 #include "am_kernels.h"
 
+#include <mutex>
+
+// Scratch of am_subset_indices_static: per-tile offsets and per-superblock bases of one subset,
+// for stages of up to kStaticMaxN coordinates.  Every GPU the library runs on holds its own copy of
+// this array for the life of the process.  The name is a host-side stand-in: host code reaches the
+// memory only through the address hipGetSymbolAddress returns for the current device.
+namespace {
+constexpr uint64_t kStaticMaxN = 1ull << 27;
+constexpr uint32_t kStaticMaxTiles = (uint32_t)(kStaticMaxN / am::kTileCoords);
+constexpr uint32_t kStaticMaxSb = kStaticMaxTiles / am::kTilesPerSuperblock;
+}
+static __device__ __align__(256) uint32_t scratch[kStaticMaxTiles + kStaticMaxSb + 64];
+
 namespace {
 
 thread_local std::string g_last_error;
@@ -82,6 +95,25 @@ uint64_t slot_capacity_lines(uint64_t ntiles, double p, bool by_line, uint64_t b
     const double var = sq - mean * mean > 0.0 ? sq - mean * mean : 0.0;
     const double cap = std::ceil((double)ntiles * mean + 12.0 * std::sqrt((double)ntiles * var)) + 64.0;
     return cap >= (double)all ? all : (uint64_t)cap;
+}
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+uint32_t *g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of the static scratch array on the CURRENT device, looked up once per device.
+am_status resolve_static_scratch(int device, uint32_t **out)
+{
+    if (device < 0 || device >= kMaxDevices) return fail(AM_EINVAL, "device %d is beyond the %d the static scratch table covers", device, kMaxDevices);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+        void *p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) return fail(AM_EHIP, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(e));
+        g_scratch_ptr[device] = static_cast<uint32_t *>(p);
+    }
+    *out = g_scratch_ptr[device];
+    return AM_OK;
 }
 
 struct Layout {
@@ -155,6 +187,7 @@ struct am_state {
     uint64_t opt_steps[AM_MAX_REPLICAS];     // optimizer steps made so far (the t of the bias corrections)
     double mu_product[AM_MAX_REPLICAS];      // NAdam: running product of the momentum schedule
     uint64_t threshold;
+    uint32_t *static_scratch;    // this device's copy of the static scratch array (am_subset_indices_static)
     // profiling of the fused kernel
     bool profiling;
     std::vector<hipEvent_t> ev_pool;
@@ -201,6 +234,33 @@ am_status launch_subset_offsets(am_state *st, uint64_t step, uint32_t slot, uint
     am::k_subset_scan<<<1, 256, 0, st->stream>>>(st->meta_sb(slot), L.nsb, (uint32_t)L.cap_lines,
                                                  for_ring ? st->flags() : nullptr, dev_count);
     AM_HIP(hipGetLastError());
+    return AM_OK;
+}
+
+am_status check_index_list_args(const am_state *st, const uint64_t *dev_out, uint64_t capacity, const uint64_t *dev_count)
+{
+    if (!st) return fail(AM_EINVAL, "state is NULL");
+    if (!dev_count) return fail(AM_EINVAL, "dev_count is NULL");
+    if (!dev_out && capacity) return fail(AM_EINVAL, "dev_out is NULL with capacity > 0");
+    if (!aligned(dev_out, 8) || !aligned(dev_count, 8)) return fail(AM_EALIGN, "pointer not 8-byte aligned");
+    return AM_OK;
+}
+
+// S^t as an ascending index list: sizes of the tiles (in coordinates) -> offsets -> indices.  local_off
+// (ntiles words) and sb_base (nsb + 1 words) are the scratch the three kernels share; every word of
+// them that is read is written first, so the scratch needs no clearing.
+am_status launch_index_list(am_state *st, uint64_t t, uint32_t *local_off, uint32_t *sb_base,
+                            uint64_t *dev_out, uint64_t capacity, uint64_t *dev_count)
+{
+    const Layout &L = st->lay;
+    am::k_subset_count<<<L.nsb, 256, 0, st->stream>>>(make_key(st, t), st->cfg.n, L.ntiles, 1u, local_off, sb_base);
+    AM_HIP(hipGetLastError());
+    am::k_subset_scan<<<1, 256, 0, st->stream>>>(sb_base, L.nsb, 0u, nullptr, dev_count);
+    AM_HIP(hipGetLastError());
+    if (capacity) {
+        am::k_subset_write<<<st->grid_sparse, 256, 0, st->stream>>>(make_key(st, t), st->cfg.n, L.ntiles, local_off, sb_base, dev_out, capacity);
+        AM_HIP(hipGetLastError());
+    }
     return AM_OK;
 }
 
@@ -365,6 +425,7 @@ am_status create_state(const am_config *cfg, const am_buffers *buf, void *hip_st
     int cus = 256;
     if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, st->device);
     if (e != hipSuccess) { delete st; return fail(AM_EHIP, "device query: %s", hipGetErrorString(e)); }
+    if (am_status s = resolve_static_scratch(st->device, &st->static_scratch)) { delete st; return s; }
     // the stand-alone kernels stride over the tiles with a fixed number of workgroups per compute unit
     const uint32_t tile_groups = (lay.ntiles + 3) / 4;
     const uint32_t want = (uint32_t)cus * 8u;
@@ -624,18 +685,22 @@ am_status am_lookahead(void *out, uint32_t out_dtype, const float *w, const floa
 
 am_status am_subset_indices(am_state *st, uint64_t t, uint64_t *dev_out, uint64_t capacity, uint64_t *dev_count)
 {
-    if (!st) return fail(AM_EINVAL, "state is NULL");
-    if (!dev_count) return fail(AM_EINVAL, "dev_count is NULL");
-    if (!dev_out && capacity) return fail(AM_EINVAL, "dev_out is NULL with capacity > 0");
-    if (!aligned(dev_out, 8) || !aligned(dev_count, 8)) return fail(AM_EALIGN, "pointer not 8-byte aligned");
-    const uint32_t scratch = st->lay.slots;          // the metadata block after the ring slots' own
-    if (am_status s = launch_subset_offsets(st, t, scratch, dev_count, false)) return s;
-    if (capacity) {
-        am::k_subset_write<<<st->grid_sparse, 256, 0, st->stream>>>(make_key(st, t), st->cfg.n, st->lay.ntiles,
-                                                                  st->meta_local(scratch), st->meta_sb(scratch), dev_out, capacity);
-        AM_HIP(hipGetLastError());
-    }
-    return AM_OK;
+    if (am_status s = check_index_list_args(st, dev_out, capacity, dev_count)) return s;
+    const uint32_t meta_slot = st->lay.slots;        // the metadata block after the ring slots' own
+    return launch_index_list(st, t, st->meta_local(meta_slot), st->meta_sb(meta_slot), dev_out, capacity, dev_count);
+}
+
+am_status am_subset_indices_static(am_state *st, uint64_t t, uint64_t *dev_out, uint64_t capacity, uint64_t *dev_count)
+{
+    if (am_status s = check_index_list_args(st, dev_out, capacity, dev_count)) return s;
+    if (st->cfg.n > kStaticMaxN)
+        return fail(AM_EINVAL, "n=%llu exceeds the %llu coordinates the static scratch covers; use am_subset_indices",
+                    (unsigned long long)st->cfg.n, (unsigned long long)kStaticMaxN);
+    int device = -1;
+    AM_HIP(hipGetDevice(&device));
+    if (device != st->device) return fail(AM_EINVAL, "device %d is current, the state lives on device %d", device, st->device);
+    uint32_t *base = st->static_scratch;             // looked up at am_init_state / am_resume_state
+    return launch_index_list(st, t, base, base + kStaticMaxTiles, dev_out, capacity, dev_count);
 }
 
 am_status am_set_delay(am_state *st, uint32_t tau)
