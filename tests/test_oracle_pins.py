@@ -318,6 +318,78 @@ def test_all_replicas_active_is_the_ordinary_step_and_idle_ones_still_average():
         assert np.array_equal(orc.fwd(i), (mean.astype(np.float64) + 0.5 * delta).astype(np.float32))
 
 
+def test_sgd_decoupled_weight_decay_hand_trace(golden_dir):
+    """SGD (plain and heavy-ball) with weight_decay != 0 against a hand-worked dyadic trace: the decay
+    multiplies the weights and never enters the momentum."""
+    rows = [l.split() for l in (golden_dir / "sgd_decoupled_decay_trace.txt").read_text().splitlines()
+            if l.strip() and not l.startswith("#")]
+    for beta in (0.5, 0.0):
+        orc = O.Oracle(1, 1, fraction=EMPTY_P, optimizer=O.OPT_SGD, beta1=beta, weight_decay=0.25)
+        orc.set_w(np.array([1.0], np.float32))
+        mine = [r for r in rows if float(r[0]) == beta]
+        assert len(mine) == 2
+        for r in mine:
+            t, g, m, w = int(r[1]), float(r[2]), float(r[3]), float(r[4])
+            orc.step(t, [np.array([g], np.float32)], 0.5)
+            assert orc.w(0)[0] == w and orc.m(0)[0] == m, (beta, t, orc.w(0)[0], orc.m(0)[0])
+
+
+def test_sgd_decoupled_weight_decay_closed_form_and_library():
+    """One plain step is w (1 - lr wd) - lr g element-wise; many heavy-ball steps equal the library's
+    SGD (no decay of its own) run on weights that are shrunk by (1 - lr wd) before every step."""
+    n, lr, wd, b1, steps = 2000, 3e-3, 0.05, 0.9, 10
+    lr32, wd32, b132 = O.f32(lr), O.f32(wd), O.f32(b1)
+    w0 = si.stage_weights(n, seed=6)
+    grads = [si.replica_grads(n, 1, t, seed=6)[0] for t in range(1, steps + 1)]
+    one = O.Oracle(n, 1, fraction=EMPTY_P, optimizer=O.OPT_SGD, beta1=0.0, weight_decay=wd)
+    one.set_w(w0); one.step(1, [grads[0]], lr)
+    want = w0.astype(np.float64) * (1.0 - lr32 * wd32) - lr32 * grads[0].astype(np.float64)
+    assert np.array_equal(one.w(0), want.astype(np.float32))
+    assert not np.array_equal(one.w(0), (w0.astype(np.float64) - lr32 * grads[0].astype(np.float64)).astype(np.float32))
+    orc = O.Oracle(n, 1, fraction=EMPTY_P, optimizer=O.OPT_SGD, beta1=b1, weight_decay=wd)
+    orc.set_w(w0)
+    p = torch.nn.Parameter(torch.from_numpy(w0.astype(np.float64)))
+    opt = torch.optim.SGD([p], lr=lr32, momentum=b132, foreach=False)
+    for t in range(1, steps + 1):
+        orc.step(t, [grads[t - 1]], lr)
+        with torch.no_grad():
+            p.mul_(1.0 - lr32 * wd32)
+        p.grad = torch.from_numpy(grads[t - 1].astype(np.float64))
+        opt.step()
+    want = p.detach().numpy()
+    scale = np.maximum(np.abs(want), np.sqrt(np.mean(want ** 2)))
+    assert np.max(np.abs(orc.w(0) - want) / scale) < 1e-6
+    nodecay = O.Oracle(n, 1, fraction=EMPTY_P, optimizer=O.OPT_SGD, beta1=b1, weight_decay=0.0)
+    nodecay.set_w(w0)
+    for t in range(1, steps + 1):
+        nodecay.step(t, [grads[t - 1]], lr)
+    assert np.max(np.abs(nodecay.w(0) - want) / scale) > 1e-4          # the decay term is not a no-op here
+
+
+def test_stateless_lookahead_bf16_branch_rounds_once_to_nearest_even():
+    """out = w + gamma (w - w_prev) in bf16: on inputs whose exact result fits fp32 (12-bit integers
+    times 2^-10, gamma = 0.5) the library's fp32 -> bf16 cast is the one correct rounding, ties
+    included; on general inputs the result is the bf16 nearest to the fp64 value."""
+    rng = np.random.default_rng(12)
+    k1 = rng.integers(-4095, 4096, 5000); k2 = rng.integers(-4095, 4096, 5000)
+    w = (k1 * 2.0 ** -10).astype(np.float32); wp = (k2 * 2.0 ** -10).astype(np.float32)
+    exact = (3 * k1 - k2) * 2.0 ** -11                                  # 1.5 w - 0.5 w_prev, a 15-bit integer / 2^11
+    assert np.array_equal(exact.astype(np.float32).astype(np.float64), exact)
+    want = torch.from_numpy(exact.astype(np.float32)).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    got = O.lookahead(w, wp, 0.5, bf16=True)
+    assert np.array_equal(got, want)
+    ties = np.abs(exact) * 2.0 ** 11 >= 512                              # more than 8 significant bits: rounding happened
+    assert ties.sum() > 1000
+    # general inputs: nearest bf16 to the fp64 value (|error| <= half a bf16 ulp) and the fp32 branch agrees
+    w = si.stage_weights(4000, seed=3); wp = si.stage_weights(4000, seed=4)
+    g = O.f32(0.9)
+    x = w.astype(np.float64) + g * (w.astype(np.float64) - wp.astype(np.float64))
+    got = si.bf16_bits_to_f32(O.lookahead(w, wp, g, bf16=True)).astype(np.float64)
+    ulp = 2.0 ** (np.floor(np.log2(np.abs(x))) - 7)
+    assert np.all(np.abs(got - x) <= 0.5 * ulp)
+    assert np.array_equal(O.lookahead(w, wp, g), x.astype(np.float32))
+
+
 def test_first_adamw_step_closed_form():
     """From zero moments, one AdamW step is w(1 - lr wd) - lr g / (|g| + eps)."""
     n, lr, wd, eps = 1000, O.f32(1e-3), O.f32(0.01), O.f32(1e-8)
@@ -441,8 +513,10 @@ def _read_trace(golden_dir):
 
 
 def _trace_oracle(**kw):
+    # look-ahead with gamma = 1: fwd = w + (w^ - w_before), so the local step's result w^ (which the
+    # oracle does not hand out) is fwd - w + w_before, exactly, in these dyadic numbers
     orc = O.Oracle(1, 2, delay=1, avg_interval=1, fraction=1.0, optimizer=O.OPT_SGD, beta1=0.0,
-                   weight_decay=0.0, **kw)
+                   weight_decay=0.0, lookahead=True, gamma=1.0, **kw)
     orc.set_w(np.array([1.0], dtype=np.float32))
     return orc
 
@@ -455,7 +529,11 @@ def test_hand_worked_ema_trace(golden_dir):
     for r in rows:
         t = int(r[0]); g0, g1, wh0, wh1, w0, w1, d0, d1 = map(float, r[1:])
         grads = [np.array([g0], np.float32), np.array([g1], np.float32)]
+        before = (float(orc.w(0)[0]), float(orc.w(1)[0]))
         orc.step(t, grads, 0.5, lam=0.5)
+        # the local step's result (what is sent, and what enters the EMA): first line of the
+        # asynchronous sparse averaging equation
+        assert tuple(float(orc.fwd(i)[0]) - float(orc.w(i)[0]) + before[i] for i in (0, 1)) == (wh0, wh1)
         assert (orc.w(0)[0], orc.w(1)[0]) == (w0, w1)
         assert (orc.d(0)[0], orc.d(1)[0]) == (d0, d1)
         none.step(t, grads, 0.5, lam=0.5)
