@@ -4,12 +4,15 @@
 A step = one am_step call = local optimizer step + look-ahead + asynchronous sparse averaging
 with EMA correction for all R replicas of the stage (subset offsets, then the fused kernel).
 Inputs (weights, optimizer state, gradients) are resident in HBM before the timed region.
+The K timed steps run as REPEATS consecutive segments, each bracketed by a device synchronisation;
+the median segment gives `value` and `ms_per_step`, the spread is reported beside it.
 Prints ONE JSON line.
 """
 from __future__ import annotations
 
 import argparse
 import json
+import statistics
 import sys
 import time
 from pathlib import Path
@@ -19,6 +22,7 @@ if str(ROOT) not in sys.path:
     sys.path.insert(0, str(ROOT))
 
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
+REPEATS = 5
 
 # name -> (n, R, tau, p, lookahead, bf16)
 WORKLOADS = {
@@ -31,6 +35,16 @@ WORKLOADS = {
 DESCRIPTION = {
     "stage125m": "one stage of 125,829,120 fp32 params (2.5 layers at d=2048), R=8 replicas, staleness 4, "
                  "subset 5%, AdamW, look-ahead and EMA correction on",
+}
+
+# HBM bytes per launch of the fused kernel measured with rocprofv3 hardware counters (FETCH_SIZE and
+# WRITE_SIZE, each scaled by what the same counter reads for a plain copy of known size: x2.0 and
+# x1.0 on gfx950); the runs are in profiles/.  Keyed by the digest of the library sources the
+# figures were measured on and by (workload, layout of the EMA vectors): a library built from other
+# sources gets no traffic figure from here.
+MEASURED_TRAFFIC = {
+    "source_hash": None,
+    "bytes": {},
 }
 
 
@@ -140,6 +154,9 @@ def main():
     ap.add_argument("--fraction", type=float, default=None, help="override the workload's subset fraction p")
     ap.add_argument("--delay", type=int, default=None, help="override the workload's delay tau")
     ap.add_argument("--no-correction", action="store_true", help="plain delayed averaging (no EMA vector)")
+    ap.add_argument("--d-layout", default="interleaved", choices=("interleaved", "per-replica"),
+                    help="memory layout of the EMA vectors: replicas side by side per coordinate (one-GPU simulation, "
+                         "the headline) or one array per replica")
     ap.add_argument("--subset-granule", type=int, default=1, choices=(1, 32),
                     help="1: coordinates drawn independently (the paper); 32: variant, whole 128-byte lines drawn")
     ap.add_argument("--subset-kind", default="bernoulli", choices=("bernoulli", "stratified"),
@@ -154,6 +171,9 @@ def main():
 
     import paper_2601_22442_amd as am
     import synth_inputs as si
+    from paper_2601_22442_amd.build import check_library_is_current
+
+    digest = check_library_is_current(am.version())      # refuses a library not built from the sources beside it
 
     w = dict(WORKLOADS[args.workload])
     if args.fraction is not None:
@@ -168,6 +188,7 @@ def main():
                          correction=am.CORR_NONE if args.no_correction else am.CORR_EMA,
                          subset_granule=args.subset_granule,
                          subset_kind=am.SUBSET_STRATIFIED if args.subset_kind == "stratified" else am.SUBSET_BERNOULLI,
+                         d_layout=am.D_INTERLEAVED if args.d_layout == "interleaved" else am.D_PER_REPLICA,
                          lookahead=w["lookahead"], gamma=0.9,
                          fwd_dtype=am.BF16 if w["bf16"] else am.F32,
                          grad_dtype=am.BF16 if w["bf16"] else am.F32)
@@ -194,59 +215,63 @@ def main():
         st.step(t, gsets[t % nsets], 3e-4, 0.5)
     torch.cuda.synchronize()
 
+    # exactly args.steps timed steps, as up to REPEATS consecutive segments
+    repeats = max(1, min(REPEATS, args.steps))
+    seg_steps = [args.steps // repeats + (1 if k < args.steps % repeats else 0) for k in range(repeats)]
     st.set_profiling(True)
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        t += 1
-        st.step(t, gsets[t % nsets], 3e-4, 0.5)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    kernel_ms, launches = st.get_profile()
+    seg_ms, launch_ms = [], []
+    for k in seg_steps:
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(k):
+            t += 1
+            st.step(t, gsets[t % nsets], 3e-4, 0.5)
+        torch.cuda.synchronize()
+        seg_ms.append((time.perf_counter() - t0) * 1e3 / k)
+        launch_ms += st.get_profile_times()          # HIP events around each launch of the fused kernel, on its stream
     st.set_profiling(False)
-    assert launches == args.steps
+    assert len(launch_ms) == args.steps
     assert st.read_flags() == 0, "a subset overflowed its ring slot"
 
     bpp = algorithmic_bytes_per_param(w)
     bytes_per_launch = bpp * R * n
-    kernel_s = kernel_ms / 1e3 / launches
-    achieved = bytes_per_launch / kernel_s / 1e9
-    ms_per_step = elapsed / args.steps * 1e3
+    ms_per_step = statistics.median(seg_ms)
+    kernel_ms_mean = sum(launch_ms) / len(launch_ms)
+    achieved = bytes_per_launch / (kernel_ms_mean * 1e-3) / 1e9
     out = {
         "metric": "fused AsyncMesh step: params/s and achieved HBM GB/s (% peak), 125M stage",
-        "value": R * n * args.steps / elapsed,
+        "value": R * n / (ms_per_step * 1e-3),
         "unit": "params/s",
         "n_gpus": 1, "steps": args.steps, "warmup": warm, "ms_per_step": ms_per_step,
+        "ms_per_step_segments": {"repeats": repeats, "steps_per_segment": seg_steps, "median": ms_per_step,
+                                 "min": min(seg_ms), "max": max(seg_ms), "mean": sum(a * b for a, b in zip(seg_ms, seg_steps)) / args.steps},
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
+        "dtype": "bf16 gradients and forward weights, f32 state" if w["bf16"] else "f32", "data": "synthetic",
+        "library": am.version(), "source_hash": digest,
         "config": {"workload": DESCRIPTION.get(args.workload, args.workload), "name": args.workload,
                    "n": n, "replicas": R, "delay": tau, "fraction": p, "lookahead": w["lookahead"],
                    "avg_interval": args.avg_interval,
-                   "correction": "none" if args.no_correction else "ema",
+                   "correction": "none" if args.no_correction else "ema", "d_layout": args.d_layout,
                    "subset_granule": args.subset_granule, "subset_kind": args.subset_kind, "bf16": w["bf16"], "algorithmic_bytes_per_param": bpp},
-        "step_GBps": bytes_per_launch / (elapsed / args.steps) / 1e9,
-        "step_frac_of_hbm_peak": bytes_per_launch / (elapsed / args.steps) / 1e9 / HBM_PEAK_GBPS,
+        "step_GBps": bytes_per_launch / (ms_per_step * 1e-3) / 1e9,
+        "step_frac_of_hbm_peak": bytes_per_launch / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
         "roofline": {"kernel": "k_step", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": MEASURED_TRAFFIC.get(args.workload),
-                     "kernel_ms": kernel_s * 1e3, "algorithmic_bytes_per_launch": bytes_per_launch},
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                     "kernel_ms": kernel_ms_mean, "kernel_ms_median": statistics.median(launch_ms),
+                     "kernel_ms_min": min(launch_ms), "kernel_ms_max": max(launch_ms), "launches": len(launch_ms),
+                     "algorithmic_bytes_per_launch": bytes_per_launch},
     }
-    traffic = MEASURED_TRAFFIC.get(args.workload)
-    if traffic is not None and p == WORKLOADS[args.workload]["p"] and tau == WORKLOADS[args.workload]["tau"] \
-            and args.avg_interval == 1 and not args.no_correction and args.subset_granule == 1 and args.subset_kind == "bernoulli":
-        # the counter-measured bytes of this very configuration over this run's kernel time
-        out["roofline"]["traffic_GBps"] = traffic / kernel_s / 1e9
-        out["roofline"]["traffic_frac"] = traffic / kernel_s / 1e9 / HBM_PEAK_GBPS
-    else:
-        out["roofline"]["traffic"] = None             # the stored figure is for the workload's own settings
+    default_settings = (p == WORKLOADS[args.workload]["p"] and tau == WORKLOADS[args.workload]["tau"] and args.avg_interval == 1
+                        and not args.no_correction and args.subset_granule == 1 and args.subset_kind == "bernoulli")
+    traffic = MEASURED_TRAFFIC["bytes"].get(f"{args.workload}/{args.d_layout}")
+    if traffic is not None and default_settings and MEASURED_TRAFFIC["source_hash"] == digest:
+        # counter-measured bytes of this very configuration and this very library, over this run's kernel time
+        out["roofline"]["traffic"] = traffic
+        out["roofline"]["traffic_from_profile_GBps"] = traffic / (kernel_ms_mean * 1e-3) / 1e9
+        out["roofline"]["traffic_from_profile_frac"] = traffic / (kernel_ms_mean * 1e-3) / 1e9 / HBM_PEAK_GBPS
     if not args.skip_cpu:
         out["cpu_baseline"] = cpu_baseline(w, args, st, gsets, t, w_pool_host)
     print(json.dumps(out))
-
-
-# HBM bytes per launch of the fused kernel measured with rocprofv3 hardware counters (FETCH_SIZE and
-# WRITE_SIZE, each scaled by what the same counter reads for a plain copy of known size: x2.0 and
-# x1.0 on gfx950); the runs are in profiles/k_step_stage125m.md and profiles/k_step_other_workloads.md.
-# None = not measured for that workload.
-MEASURED_TRAFFIC: dict = {"stage125m": 39.79e9, "bf16": 62.74e9, "model1b": 327.06e9}
 
 
 if __name__ == "__main__":

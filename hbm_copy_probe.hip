@@ -1,6 +1,8 @@
 // Plain copy kernel of known size: the yardstick for the HBM counters and for what this chip's
 // memory system sustains on a pure stream.  Usage: hbm_copy_probe [MiB per buffer] [repeats]
 // Prints the bytes one launch reads and writes and the bandwidth from HIP events.
+// Not part of the library; build it by hand when profiling:
+//   hipcc --offload-arch=gfx950 -O3 -Xclang -target-feature -Xclang -packed-fp32-ops -o hbm_copy_probe hbm_copy_probe.hip
 #include <hip/hip_runtime.h>
 
 #include <cstdio>

@@ -14,8 +14,8 @@
  *   (4) extrapolates the optimizer's displacement to get the weights of the next forward pass
  *                                             [Sec. "Asynchronous pipeline parallelism": NAG-style
  *                                              look-ahead of the last update direction].
- * The R replicas and the delay buffer ("we simulate the asynchronous setup via buffering",
- * appendix, wall-clock paragraph) live side by side in the memory of ONE GPU.
+ * The R replicas and the delay buffer (appendix, wall-clock paragraph: the asynchronous set-up is
+ * simulated with a buffer of delayed copies) live side by side in the memory of ONE GPU.
  *
  * General conventions
  *   - Every pointer marked DEVICE is memory of the GPU that was current at am_init_state; it is
@@ -25,8 +25,11 @@
  *   - All work is enqueued on the stream given to am_init_state (am_lookahead: its own argument).
  *     No call synchronises with the device, allocates device memory, or copies to the host,
  *     except am_read_flags and am_get_profile, which say so.
- *   - Every function returns AM_OK (0) or a negative am_status; on an error nothing is enqueued
- *     and the state is unchanged.  am_last_error() gives a message for the calling thread.
+ *   - Every function returns AM_OK (0) or a negative am_status.  On an error the state (host
+ *     record and the caller's arrays) is unchanged and the call may be repeated; argument errors
+ *     are found before anything is enqueued (a step whose kernel launch itself fails may already
+ *     have enqueued its subset-offsets pass, which a repeated call simply redoes).
+ *     am_last_error() gives a message for the calling thread.
  *   - No exception crosses this boundary.
  */
 #ifndef ASYNCMESH_H
@@ -48,7 +51,9 @@ typedef enum {
     AM_EALIGN  = -2,    /* a device pointer is not aligned as required                     */
     AM_ENOMEM  = -3,    /* workspace too small / host allocation failed                    */
     AM_EORDER  = -4,    /* step index is not the previous one plus one                     */
-    AM_EHIP    = -5     /* a HIP runtime call failed (message has the HIP error string)    */
+    AM_EHIP    = -5,    /* a HIP runtime call failed (message has the HIP error string)    */
+    AM_EOVERFLOW = -6   /* am_read_flags has reported a subset that did not fit its ring slot:
+                           the state no longer follows the method, further steps are refused  */
 } am_status;
 
 /* local optimizer (experimental-setup appendix: NAdamW with momentum 0.99 for asynchronous
@@ -89,6 +94,21 @@ typedef enum {
     AM_SUBSET_STRATIFIED = 1
 } am_subset;
 
+/* How the EMA vectors d_i lie in memory.  S^t is the same for every replica (Sec. "Sparse parameter
+ * averaging"), so the entries of d that one step touches are the same coordinates in every replica.
+ *   PER_REPLICA: one flat array of n floats per replica (what a replica on its own GPU would hold).
+ *   INTERLEAVED: the replicas are cut into blocks of rb = min(8, R rounded up to a power of two)
+ *     consecutive replicas; a block is ONE array [coordinate][replica in block] of
+ *     ceil(n / 256) * 256 * rb floats (whole tiles; entries of absent replicas and of coordinates
+ *     >= n are never changed).  A 128-byte line then holds 32 / rb coordinates of all the block's
+ *     replicas, so far fewer lines are touched per step (R = 8, p = 5 %: 18.5 % of the lines
+ *     instead of 80.6 %).  A property of holding all replicas on one GPU.  am_d_layout_info gives rb,
+ *     the number of blocks and the floats per block. */
+typedef enum {
+    AM_D_PER_REPLICA = 0,
+    AM_D_INTERLEAVED = 1
+} am_dlayout;
+
 typedef struct {
     uint64_t n;              /* d_j: parameters of the stage, per replica; 1 <= n < 2^32 - 2^20          */
     uint32_t replicas;       /* m = R, 1 .. AM_MAX_REPLICAS                                              */
@@ -110,7 +130,11 @@ typedef struct {
                                 the generator; same inclusion probability p per coordinate.         */
     uint32_t msg_dtype;      /* am_msg: precision of the exchanged subset values                        */
     uint32_t subset_kind;    /* am_subset: how S^t is drawn                                             */
-    uint32_t reserved;       /* set to 0                                                                */
+    uint32_t d_layout;       /* am_dlayout: memory layout of the EMA vectors                            */
+    uint64_t ring_cap_lines; /* 0: a ring slot is sized from the distribution of |S^t| (see
+                                am_workspace_bytes).  Else: the number of 128-byte lines per block a slot
+                                gets, for callers that bound the workspace themselves; tiles that do
+                                not fit are left out of that round's average and flag bit 0 is raised */
 } am_config;
 
 /* The subset: S^t = { mu in [0, n) : X(seed, t, mu) < floor(p * 2^32) }, X = word (mu & 3) of
@@ -123,18 +147,26 @@ typedef struct {
     float *const *w;        /* master weights, fp32, in: w^{t-1}, out: w^t                       */
     float *const *m;        /* first moment / momentum, fp32 (may be NULL for SGD with beta1=0)  */
     float *const *v;        /* second moment, fp32 (may be NULL for SGD)                         */
-    float *const *d;        /* EMA of staleness d_i, fp32 (may be NULL when correction = NONE)   */
+    float *const *d;        /* EMA of staleness d_i, fp32 (may be NULL when correction = NONE);
+                               d_layout = INTERLEAVED: one pointer per BLOCK instead (am_d_layout_info) */
     void  *const *fwd;      /* weights for the next forward pass, fwd_dtype; NULL = not produced
                                (allowed only with lookahead = 0 and fwd_dtype = AM_F32)          */
     void    *workspace;     /* DEVICE, 256-byte aligned: delay ring + subset offsets + flags     */
     uint64_t workspace_bytes;
 } am_buffers;
 
-/* Bytes of workspace a configuration needs.  The delay ring inside it holds tau+1 slots; in a
- * slot every tile of 256 coordinates owns, per replica, ceil(X/32) whole 128-byte lines, X its
- * number of selected coordinates; a slot has room for the expected number of lines plus twelve
- * standard deviations (stratified sampling: exactly what the fullest tile can need, times the tiles). */
+/* Bytes of workspace a configuration needs.  The delay ring inside it holds tau+1 slots; a slot
+ * keeps the replicas of a block (rb <= 8 consecutive replicas) side by side, [coordinate][replica]:
+ * every tile of 256 coordinates owns, per block, ceil(X rb / 32) whole 128-byte lines, X its number
+ * of selected coordinates; a slot has room for the expected number of lines plus twelve standard
+ * deviations (stratified sampling: exactly what the fullest tile can need, times the tiles), or for
+ * ring_cap_lines lines when the config names a size. */
 am_status am_workspace_bytes(const am_config *cfg, uint64_t *out_bytes);
+
+/* Shape of the EMA vectors under the config's d_layout: replicas per block (PER_REPLICA: 1), number
+ * of arrays buffers.d must point to, and floats per array.  Any of the outputs may be NULL. */
+am_status am_d_layout_info(const am_config *cfg, uint32_t *out_replicas_per_block, uint32_t *out_arrays,
+                           uint64_t *out_floats_per_array);
 
 /* Validate, bind the caller's buffers and the stream, and enqueue the zeroing of m, v, d (d^0 = 0,
  * experimental-setup appendix) and of the workspace.  w is left as given.  hip_stream is a
@@ -215,14 +247,20 @@ am_status am_subset_indices_static(am_state *st, uint64_t t, uint64_t *dev_out, 
                                    uint64_t *dev_count);
 
 /* Synchronises the stream and returns sticky flags: bit 0 = some S^t needed more lines than a
- * ring slot holds (the tiles past the capacity were left out of that round's average). */
+ * ring slot holds (the tiles past the capacity were left out of that round's average, at send and
+ * at receive alike; with the default slot size the chance is about 1e-33 per step).  Once this
+ * call has reported bit 0, am_step* and am_sparse_average on the state return AM_EOVERFLOW. */
 am_status am_read_flags(am_state *st, uint32_t *out_flags);
 
 /* Optional timing of the fused step kernel alone: while on, am_step brackets that kernel with
- * events on its stream.  am_get_profile synchronises, returns the summed kernel time in
- * milliseconds and the number of launches since profiling was switched on, and resets both. */
+ * events on its stream (at most 4096 launches between two am_get_profile calls; later ones run
+ * untimed).  am_get_profile synchronises, returns the summed kernel time in milliseconds and the
+ * number of launches timed since profiling was switched on (or since the last call), and resets
+ * both.  am_get_profile_times additionally copies the individual launch times (milliseconds, in
+ * launch order) to out_ms[0 .. min(launches, capacity)) before resetting. */
 am_status am_set_profiling(am_state *st, int on);
 am_status am_get_profile(am_state *st, double *out_kernel_ms, uint64_t *out_launches);
+am_status am_get_profile_times(am_state *st, float *out_ms, uint64_t capacity, uint64_t *out_launches);
 
 /* Slot capacity (fp32 positions per replica = lines * 32) and number of ring slots of this state;
  * host values, no device work. */
@@ -235,8 +273,9 @@ am_status am_ring_info(const am_state *st, uint64_t *out_capacity, uint32_t *out
  * addresses, same alignment rules), and call am_resume_state instead of am_init_state; it clears
  * nothing.  S^t is a pure function of (seed, t), so there is no generator state to save.  The
  * record is refused (AM_EINVAL) when the config differs from the one it was exported under in a
- * field that shapes the ring or the subsets (n, replicas, delay, avg_interval, optimizer,
- * fraction, seed, subset_granule, subset_kind).  Host-only calls apart from what am_init_state does. */
+ * field that shapes the ring, the subsets or the arrays (n, replicas, delay, avg_interval, optimizer,
+ * fraction, seed, subset_granule, subset_kind, d_layout, ring_cap_lines).  Host-only calls apart
+ * from what am_init_state does. */
 typedef struct {
     uint64_t magic;             /* layout version of this record                                */
     uint64_t config_digest;
@@ -255,7 +294,8 @@ am_status am_resume_state(const am_config *cfg, const am_buffers *buf, void *hip
 am_status am_destroy(am_state *st);
 
 const char *am_last_error(void);      /* message of the last failing call on this thread */
-const char *am_version(void);
+const char *am_version(void);          /* "asyncmesh-gfx950 <version> src:<hash>": the hash is a digest of the
+                                          library's source files taken when it was built */
 
 #ifdef __cplusplus
 }

@@ -8,7 +8,8 @@ from .schedules import active_mask, ema_lambda, learning_rate  # noqa: F401
 
 _BINDING_NAMES = (
     "BF16", "CORR_EAGER", "CORR_EMA", "CORR_NONE", "F32", "MAX_REPLICAS", "MSG_BF16", "MSG_E4M3", "MSG_F32",
-    "OPT_ADAMW", "OPT_NADAMW", "OPT_SGD", "SUBSET_BERNOULLI", "SUBSET_STRATIFIED",
+    "OPT_ADAMW", "OPT_NADAMW", "OPT_SGD", "SUBSET_BERNOULLI", "SUBSET_STRATIFIED", "D_PER_REPLICA", "D_INTERLEAVED",
+    "d_layout_info",
     "AsyncMeshError", "Config", "Snapshot", "Stage", "init_state", "lookahead", "make_config", "version",
     "workspace_bytes",
 )

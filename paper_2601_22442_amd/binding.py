@@ -20,11 +20,12 @@ CORR_NONE, CORR_EMA, CORR_EAGER = 0, 1, 2
 F32, BF16 = 0, 1
 MSG_F32, MSG_BF16, MSG_E4M3 = 0, 1, 2
 SUBSET_BERNOULLI, SUBSET_STRATIFIED = 0, 1
+D_PER_REPLICA, D_INTERLEAVED = 0, 1
 
 EXPORTS = (
-    "am_workspace_bytes", "am_init_state", "am_step", "am_step_scaled", "am_step_masked", "am_grad_sqnorm", "am_sparse_average",
+    "am_workspace_bytes", "am_d_layout_info", "am_init_state", "am_step", "am_step_scaled", "am_step_masked", "am_grad_sqnorm", "am_sparse_average",
     "am_lookahead",
-    "am_subset_indices", "am_subset_indices_static", "am_set_delay", "am_diagnostics", "am_read_flags", "am_set_profiling", "am_get_profile", "am_ring_info",
+    "am_subset_indices", "am_subset_indices_static", "am_set_delay", "am_diagnostics", "am_read_flags", "am_set_profiling", "am_get_profile", "am_get_profile_times", "am_ring_info",
     "am_export_state", "am_resume_state",
     "am_destroy", "am_last_error", "am_version",
 )
@@ -47,7 +48,8 @@ class Config(C.Structure):
         ("lookahead", C.c_uint32), ("correction", C.c_uint32), ("fwd_dtype", C.c_uint32), ("grad_dtype", C.c_uint32),
         ("momentum_decay", C.c_double),
         ("subset_granule", C.c_uint32), ("msg_dtype", C.c_uint32),
-        ("subset_kind", C.c_uint32), ("reserved", C.c_uint32),
+        ("subset_kind", C.c_uint32), ("d_layout", C.c_uint32),
+        ("ring_cap_lines", C.c_uint64),
     ]
 
 
@@ -77,6 +79,7 @@ def _load():
             "__graft_entry__.build()).  There is no fallback path.")
     L = C.CDLL(str(_LIB_PATH))
     L.am_workspace_bytes.argtypes = [C.POINTER(Config), C.POINTER(C.c_uint64)]
+    L.am_d_layout_info.argtypes = [C.POINTER(Config), C.POINTER(C.c_uint32), C.POINTER(C.c_uint32), C.POINTER(C.c_uint64)]
     L.am_init_state.argtypes = [C.POINTER(Config), C.POINTER(Buffers), C.c_void_p, C.POINTER(C.c_void_p)]
     L.am_step.argtypes = [C.c_void_p, C.c_uint64, C.POINTER(C.c_void_p), C.c_float, C.c_float, C.c_float]
     L.am_step_scaled.argtypes = [C.c_void_p, C.c_uint64, C.POINTER(C.c_void_p), C.c_float, C.c_float, C.c_float, C.c_void_p]
@@ -91,6 +94,7 @@ def _load():
     L.am_read_flags.argtypes = [C.c_void_p, C.POINTER(C.c_uint32)]
     L.am_set_profiling.argtypes = [C.c_void_p, C.c_int]
     L.am_get_profile.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_uint64)]
+    L.am_get_profile_times.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.c_uint64, C.POINTER(C.c_uint64)]
     L.am_ring_info.argtypes = [C.c_void_p, C.POINTER(C.c_uint64), C.POINTER(C.c_uint32)]
     L.am_export_state.argtypes = [C.c_void_p, C.POINTER(Snapshot)]
     L.am_resume_state.argtypes = [C.POINTER(Config), C.POINTER(Buffers), C.c_void_p, C.POINTER(Snapshot), C.POINTER(C.c_void_p)]
@@ -119,18 +123,35 @@ def version() -> str:
 def make_config(n, replicas, delay=0, avg_interval=1, fraction=0.05, seed=0, optimizer=OPT_ADAMW,
                 beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01, lookahead=False, gamma=0.0,
                 correction=CORR_EMA, fwd_dtype=F32, grad_dtype=F32, momentum_decay=0.004,
-                subset_granule=1, msg_dtype=MSG_F32, subset_kind=SUBSET_BERNOULLI) -> Config:
+                subset_granule=1, msg_dtype=MSG_F32, subset_kind=SUBSET_BERNOULLI, d_layout=D_PER_REPLICA,
+                ring_cap_lines=0) -> Config:
     return Config(n=n, replicas=replicas, delay=delay, avg_interval=avg_interval, optimizer=optimizer,
                   fraction=fraction, seed=seed, beta1=beta1, beta2=beta2, eps=eps, weight_decay=weight_decay,
                   gamma=gamma, lookahead=int(bool(lookahead)), correction=correction,
                   fwd_dtype=fwd_dtype, grad_dtype=grad_dtype, momentum_decay=momentum_decay,
-                  subset_granule=subset_granule, msg_dtype=msg_dtype, subset_kind=subset_kind, reserved=0)
+                  subset_granule=subset_granule, msg_dtype=msg_dtype, subset_kind=subset_kind, d_layout=d_layout,
+                  ring_cap_lines=ring_cap_lines)
 
 
 def workspace_bytes(cfg: Config) -> int:
     out = C.c_uint64(0)
     _check(lib.am_workspace_bytes(C.byref(cfg), C.byref(out)))
     return int(out.value)
+
+
+def d_layout_info(cfg: Config):
+    """(replicas per block, number of arrays, floats per array) of the EMA vectors (am_d_layout_info)."""
+    rb, arrays, floats = C.c_uint32(0), C.c_uint32(0), C.c_uint64(0)
+    _check(lib.am_d_layout_info(C.byref(cfg), C.byref(rb), C.byref(arrays), C.byref(floats)))
+    return int(rb.value), int(arrays.value), int(floats.value)
+
+
+def _check_tensors(name, tensors, count, numel, dtype, device):
+    if len(tensors) != count:
+        raise ValueError(f"{name}: {len(tensors)} tensors, {count} expected")
+    for i, x in enumerate(tensors):
+        if not (x.is_cuda and x.device == device and x.is_contiguous() and x.numel() == numel and x.dtype == dtype):
+            raise ValueError(f"{name}[{i}] must be a contiguous {dtype} tensor of {numel} elements on {device}")
 
 
 def _ptr_table(tensors):
@@ -160,7 +181,7 @@ class Stage:
         self.w = [torch.empty(n, **f32) for _ in range(R)]
         self.m = [torch.empty(n, **f32) for _ in range(R)] if need_m else None
         self.v = [torch.empty(n, **f32) for _ in range(R)] if need_v else None
-        self.d = [torch.empty(n, **f32) for _ in range(R)] if need_d else None
+        self._alloc_d(need_d, f32)
         fdt = torch.bfloat16 if cfg.fwd_dtype == BF16 else torch.float32
         self.fwd = [torch.empty(n, dtype=fdt, device=self.device) for _ in range(R)] if with_fwd else None
         if w0 is not None:
@@ -169,14 +190,45 @@ class Stage:
         self._handle = C.c_void_p(None)
         self._init()
 
+    def _alloc_d(self, need_d: bool, f32):
+        """d_storage: the arrays handed to the library (one per replica, or one per block of
+        replicas in the interleaved layout); d: one view per replica, for reading."""
+        if not need_d:
+            self.d_storage = self.d = None
+            return
+        rb, arrays, floats = d_layout_info(self.cfg)
+        self.d_storage = [torch.empty(floats, **f32) for _ in range(arrays)]
+        self._d_views(rb)
+
+    def _d_views(self, rb: int):
+        if self.cfg.d_layout == D_INTERLEAVED:
+            self.d = [self.d_storage[i // rb].view(-1, rb)[:self.n, i % rb] for i in range(self.R)]
+        else:
+            self.d = self.d_storage
+
     @classmethod
     def resume(cls, cfg: Config, snapshot: Snapshot, w, m, v, d, fwd, workspace, device="cuda:0"):
         """A stage bound to arrays whose bytes were restored from a checkpoint (am_resume_state);
-        nothing is cleared.  m, v, d, fwd are lists of tensors or None, as the config needs."""
+        nothing is cleared.  m, v, d, fwd are lists of tensors or None, as the config needs (d: what
+        d_storage held: one array per replica, or per block in the interleaved layout)."""
         self = cls.__new__(cls)
         self.cfg, self.device = cfg, torch.device(device)
         self.n, self.R = int(cfg.n), int(cfg.replicas)
-        self.w, self.m, self.v, self.d, self.fwd, self.workspace = w, m, v, d, fwd, workspace
+        self.w, self.m, self.v, self.fwd, self.workspace = w, m, v, fwd, workspace
+        self.d_storage = d
+        if d is None:
+            self.d = None
+        else:
+            rb, arrays, floats = d_layout_info(cfg)
+            _check_tensors("d", d, arrays, floats, torch.float32, self.device)
+            self._d_views(rb)
+        fdt = torch.bfloat16 if cfg.fwd_dtype == BF16 else torch.float32
+        for name, ts, dt in (("w", w, torch.float32), ("m", m, torch.float32), ("v", v, torch.float32), ("fwd", fwd, fdt)):
+            if ts is not None:
+                _check_tensors(name, ts, self.R, self.n, dt, self.device)
+        if not (workspace.is_cuda and workspace.is_contiguous() and workspace.dtype == torch.uint8
+                and workspace.numel() >= workspace_bytes(cfg)):
+            raise ValueError("workspace must be a contiguous uint8 device tensor of at least workspace_bytes(cfg) bytes")
         self._handle = C.c_void_p(None)
         self._init(snapshot)
         return self
@@ -192,7 +244,7 @@ class Stage:
         bufs = Buffers()
         self._tables = {}
         for name in ("w", "m", "v", "d", "fwd"):
-            ts = getattr(self, name)
+            ts = self.d_storage if name == "d" else getattr(self, name)
             if ts is not None:
                 self._tables[name] = _ptr_table(ts)
                 setattr(bufs, name, C.cast(self._tables[name], C.POINTER(C.c_void_p)))
@@ -211,16 +263,32 @@ class Stage:
         for i in range(self.R):
             self.w[i].copy_(w0 if w0.dim() == 1 else w0[i])
 
+    def _check_grads(self, grads, allow_none: bool = False):
+        """The C side sees raw pointers only: everything that could make a kernel read past an
+        allocation is refused here, before any launch."""
+        if len(grads) != self.R:
+            raise ValueError(f"{len(grads)} gradient tensors for {self.R} replicas")
+        want = torch.bfloat16 if self.cfg.grad_dtype == BF16 else torch.float32
+        for i, g in enumerate(grads):
+            if g is None:
+                if allow_none:
+                    continue
+                raise ValueError(f"grads[{i}] is None")
+            if not (g.is_cuda and g.device == self.device and g.is_contiguous() and g.numel() == self.n and g.dtype == want):
+                raise ValueError(f"grads[{i}] must be a contiguous {want} tensor of {self.n} elements on {self.device}, "
+                                 f"got {tuple(g.shape)} {g.dtype} on {g.device}, contiguous={g.is_contiguous()}")
+
     # ---- entry points -------------------------------------------------------------------
     def step(self, t: int, grads, lr: float, lambda_t: float = 0.5, grad_scale: float = 1.0):
-        assert len(grads) == self.R
+        self._check_grads(grads)
         table = _ptr_table(grads)
         with torch.cuda.device(self.device):
             _check(lib.am_step(self._handle, t, table, lr, lambda_t, grad_scale))
 
     def step_scaled(self, t: int, grads, lr: float, lambda_t: float, grad_scale: float, replica_scale: torch.Tensor):
         """am_step_scaled: replica_scale is a device tensor of R fp32 factors."""
-        assert len(grads) == self.R and replica_scale.is_cuda and replica_scale.dtype == torch.float32
+        self._check_grads(grads)
+        assert replica_scale.is_cuda and replica_scale.dtype == torch.float32
         assert replica_scale.numel() == self.R and replica_scale.is_contiguous()
         table = _ptr_table(grads)
         with torch.cuda.device(self.device):
@@ -230,7 +298,7 @@ class Stage:
                     replica_scale: torch.Tensor | None = None):
         """One tick in which only the replicas named by active_mask make a local step (am_step_masked);
         grads[i] of an idle replica may be None."""
-        assert len(grads) == self.R
+        self._check_grads([g if (active_mask >> i) & 1 else None for i, g in enumerate(grads)], allow_none=True)
         table = (C.c_void_p * self.R)(*[None if g is None else g.data_ptr() for g in grads])
         with torch.cuda.device(self.device):
             _check(lib.am_step_masked(self._handle, t, table, lr, lambda_t, grad_scale,
@@ -238,7 +306,7 @@ class Stage:
 
     def grad_sqnorm(self, grads) -> torch.Tensor:
         """am_grad_sqnorm: device tensor of R doubles, sum of squares of each replica's gradient."""
-        assert len(grads) == self.R
+        self._check_grads(grads)
         out = torch.empty(self.R, dtype=torch.float64, device=self.device)
         table = _ptr_table(grads)
         with torch.cuda.device(self.device):
@@ -289,6 +357,13 @@ class Stage:
         ms, k = C.c_double(0), C.c_uint64(0)
         _check(lib.am_get_profile(self._handle, C.byref(ms), C.byref(k)))
         return float(ms.value), int(k.value)
+
+    def get_profile_times(self):
+        """Per-launch times (ms) of the fused kernel since profiling was switched on (am_get_profile_times)."""
+        buf = (C.c_float * 4096)()
+        k = C.c_uint64(0)
+        _check(lib.am_get_profile_times(self._handle, buf, 4096, C.byref(k)))
+        return [float(buf[i]) for i in range(min(int(k.value), 4096))]
 
     def ring_info(self):
         cap, slots = C.c_uint64(0), C.c_uint32(0)

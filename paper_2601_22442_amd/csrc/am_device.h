@@ -1,22 +1,16 @@
 // Device-side building blocks of the AsyncMesh stage update for gfx950 (wave64).
 //
-// Geometry used by every kernel here:
-//   group      = 4 consecutive coordinates (one 128-bit access, one Philox4x32 block)
-//   tile       = 64 groups = 256 consecutive coordinates = what one wavefront handles at a time
-//   superblock = 512 tiles; subset counts are scanned inside a superblock by one workgroup and
-//                across superblocks by a second tiny kernel
+// Geometry (group, tile, superblock, line, block): am_geometry.h.
 // A tile's first entry in a packed list (of selected coordinates, or of the whole lines a tile
-// owns in a ring slot) is  sb_base[tile >> 9] + local_off[tile].
+// owns in a ring slot) is  sb_base[tile >> 9] + local_off[tile]  (ring slots: the low 24 bits of
+// the tile's word; the high 8 bits hold the number of lines the tile owns).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-namespace am {
+#include "am_geometry.h"
 
-constexpr uint32_t kTileCoords = 256;
-constexpr uint32_t kTilesPerSuperblock = 512;
-constexpr uint32_t kLineFloats = 32;        // floats per 128-byte line, the unit in which memory is written
-constexpr uint32_t kMaxReplicas = 32;
+namespace am {
 
 // ---------------------------------------------------------------------------------------------
 // Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11): ten rounds of two 32x32->64 multiplies.
@@ -125,11 +119,32 @@ __device__ __forceinline__ uint32_t wave_prefix_mask4(uint32_t mask4, uint32_t &
     return pre;
 }
 
+// A 32-bit word at an address that is the same for every lane of the wave and that no kernel in
+// flight writes (subset offsets written by an earlier kernel): read through the constant address
+// space, so that the compiler may use a scalar load that does not queue behind the vector loads.
+__device__ __forceinline__ uint32_t uniform_load(const uint32_t *p, uint32_t idx)
+{
+    typedef const uint32_t __attribute__((address_space(4))) *const_u32_ptr;
+    return ((const_u32_ptr)(uintptr_t)p)[idx];
+}
+
+// Direct global -> LDS load of 16 bytes per active lane: lane l of the wave writes
+// lds_wave_base[4 l .. 4 l + 3] (lds_wave_base must be the same for all lanes); no registers are
+// held while the load is in flight.  The data is in LDS once the wave's vector-memory counter has
+// drained (lds_dma_wait) -- other waves must additionally pass a workgroup barrier.
+__device__ __forceinline__ void lds_dma_16(const float *src, float *lds_wave_base)
+{
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                     (__attribute__((address_space(3))) void *)lds_wave_base, 16, 0, 0);
+}
+__device__ __forceinline__ void lds_dma_wait() { __builtin_amdgcn_s_waitcnt(0x0F70); }     // vmcnt(0)
+
 // ---------------------------------------------------------------------------------------------
 // 128-bit accesses with a scalar tail (only the last group of an array can be partial)
 // ---------------------------------------------------------------------------------------------
 struct F4 { float v[4]; };
 typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v2f __attribute__((ext_vector_type(2)));
 typedef uint32_t v2u __attribute__((ext_vector_type(2)));
 
 // The arrays of this update are streamed: every element is read once and written once per step,
@@ -203,17 +218,32 @@ __device__ __forceinline__ F4 load_bf16x4(const uint16_t *__restrict__ p, uint64
     return r;
 }
 
-__device__ __forceinline__ void store_bf16x4(uint16_t *__restrict__ p, uint64_t mu, int nvalid, const F4 &x)
+// fp64 -> bfloat16 with ONE rounding to nearest even: the value is first rounded to odd in fp32
+// (truncated magnitude, last bit forced to 1 when inexact), which keeps enough information
+// (16 spare bits) for the final rounding to land where a direct rounding of the fp64 value would.
+__device__ __forceinline__ uint16_t f64_to_bf16_bits(double x)
+{
+    float f = (float)x;
+    const double back = (double)f;
+    if (back != x) {
+        uint32_t u = __float_as_uint(f);
+        if (fabs(back) > fabs(x)) u -= 1u;             // the nearest fp32 was the one further from zero
+        f = __uint_as_float(u | 1u);
+    }
+    return f32_to_bf16_bits(f);
+}
+
+__device__ __forceinline__ void store_bf16x4_from_f64(uint16_t *__restrict__ p, uint64_t mu, int nvalid, const double (&x)[4])
 {
     if (nvalid == 4) {
         v2u t;
-        t.x = (uint32_t)f32_to_bf16_bits(x.v[0]) | ((uint32_t)f32_to_bf16_bits(x.v[1]) << 16);
-        t.y = (uint32_t)f32_to_bf16_bits(x.v[2]) | ((uint32_t)f32_to_bf16_bits(x.v[3]) << 16);
+        t.x = (uint32_t)f64_to_bf16_bits(x[0]) | ((uint32_t)f64_to_bf16_bits(x[1]) << 16);
+        t.y = (uint32_t)f64_to_bf16_bits(x[2]) | ((uint32_t)f64_to_bf16_bits(x[3]) << 16);
         __builtin_nontemporal_store(t, reinterpret_cast<v2u *>(p + mu));
     } else {
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-            if (j < nvalid) p[mu + j] = f32_to_bf16_bits(x.v[j]);
+            if (j < nvalid) p[mu + j] = f64_to_bf16_bits(x[j]);
     }
 }
 

@@ -9,8 +9,10 @@ namespace am {
 // Subset offsets:   k_subset_count (or k_subset_offsets)  ->  k_subset_scan
 // =============================================================================================
 // cnt[512] (LDS) holds the sizes of the tiles of superblock blockIdx.x: write their exclusive
-// prefix to local_off and their total to sb_sum.  Called by all 256 threads after a barrier.
-__device__ __forceinline__ void scan_superblock(const uint32_t *cnt, uint32_t *wave_tot, uint32_t ntiles,
+// prefix to local_off and their total to sb_sum.  pack: a tile's word also carries its own size in
+// the high 8 bits (ring slots, where a tile owns at most 64 lines and a superblock at most 2^15).
+// Called by all 256 threads after a barrier.
+__device__ __forceinline__ void scan_superblock(const uint32_t *cnt, uint32_t *wave_tot, uint32_t ntiles, bool pack,
                                                 uint32_t *__restrict__ local_off, uint32_t *__restrict__ sb_sum)
 {
     const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
@@ -29,18 +31,18 @@ __device__ __forceinline__ void scan_superblock(const uint32_t *cnt, uint32_t *w
     for (uint32_t w = 0; w < wave; ++w) base += wave_tot[w];
     const uint32_t excl = base + incl - (a + b);
     const uint32_t t_a = tile0 + 2 * threadIdx.x;
-    if (t_a < ntiles) local_off[t_a] = excl;
-    if (t_a + 1 < ntiles) local_off[t_a + 1] = excl + a;
+    if (t_a < ntiles) local_off[t_a] = pack ? (excl | (a << 24)) : excl;
+    if (t_a + 1 < ntiles) local_off[t_a + 1] = pack ? ((excl + a) | (b << 24)) : excl + a;
     if (threadIdx.x == 255) sb_sum[blockIdx.x] = base + incl;
 }
 
 // One workgroup (4 waves) per superblock of 512 tiles.  Pure integer hashing, no array reads.
-// A tile's size is its number of selected coordinates (unit = 1: packed index lists) or that
-// number rounded up to whole 128-byte lines of 32 floats (unit = 32: ring slots, where every tile
-// owns whole lines).  Writes, per tile, the summed size of the tiles of the same superblock before
-// it (local_off) and, per superblock, its total (sb_sum).
+// A tile's size is ceil(count * mul / unit), count its number of selected coordinates:
+// mul = unit = 1 for packed index lists; mul = replicas per block, unit = 32 for ring slots, where a
+// tile owns whole 128-byte lines of [coordinate][replica] values.  Writes, per tile, the summed size
+// of the tiles of the same superblock before it (local_off) and, per superblock, its total (sb_sum).
 __global__ void __launch_bounds__(256)
-k_subset_count(SubsetKey key, uint64_t n, uint32_t ntiles, uint32_t unit,
+k_subset_count(SubsetKey key, uint64_t n, uint32_t ntiles, uint32_t mul, uint32_t unit, uint32_t pack,
                uint32_t *__restrict__ local_off, uint32_t *__restrict__ sb_sum)
 {
     __shared__ uint32_t cnt[kTilesPerSuperblock];
@@ -58,10 +60,10 @@ k_subset_count(SubsetKey key, uint64_t n, uint32_t ntiles, uint32_t unit,
             const int nvalid = mu >= n ? 0 : (n - mu >= 4u ? 4 : (int)(n - mu));
             (void)wave_prefix_mask4(member_mask(key, group, nvalid), total);
         }
-        if (lane == 0) cnt[k] = (total + unit - 1u) / unit;
+        if (lane == 0) cnt[k] = (total * mul + unit - 1u) / unit;
     }
     __syncthreads();
-    scan_superblock(cnt, wave_tot, ntiles, local_off, sb_sum);
+    scan_superblock(cnt, wave_tot, ntiles, pack != 0u, local_off, sb_sum);
 }
 
 // Same, from tile sizes that are already in memory (the fused step kernel leaves the line counts
@@ -76,7 +78,7 @@ k_subset_offsets(const uint32_t *__restrict__ tile_size, uint32_t ntiles,
     for (uint32_t k = threadIdx.x; k < kTilesPerSuperblock; k += 256u)
         cnt[k] = tile0 + k < ntiles ? tile_size[tile0 + k] : 0u;
     __syncthreads();
-    scan_superblock(cnt, wave_tot, ntiles, local_off, sb_sum);
+    scan_superblock(cnt, wave_tot, ntiles, true, local_off, sb_sum);
 }
 
 // Single workgroup: exclusive scan of the superblock totals, in place (sb[i] <- sum of sb[<i]),
@@ -134,43 +136,51 @@ k_subset_write(SubsetKey key, uint64_t n, uint32_t ntiles, const uint32_t *__res
 enum : int { kOptSgdPlain = 0, kOptSgdMomentum = 1, kOptAdam = 2, kOptNone = 3 };   // kOptNone: w^ = w (averaging only)
 enum : int { kFwdNone = 0, kFwdF32 = 1, kFwdBf16 = 2 };
 
+// What one replica's wave needs to know about its replica: 64 bytes, one scalar load.
+struct ReplicaArgs {
+    float *w, *m, *v;
+    void *fwd;
+    const void *g;
+    // bias corrections of the optimizer, per replica: replicas of unequal speed have made unequal
+    // numbers of optimizer steps
+    double c_g, c_m, c_v;
+};
+
 struct StepArgs {
-    float *w[kMaxReplicas];
-    float *m[kMaxReplicas];
-    float *v[kMaxReplicas];
-    float *d[kMaxReplicas];
-    void *fwd[kMaxReplicas];
-    const void *g[kMaxReplicas];
     uint64_t n;
     uint32_t ntiles;
     uint32_t replicas;
+    // blocks: replicas b rb .. b rb + rb - 1 form block b; one wave of a workgroup per replica of a block
+    uint32_t rb, rb_shift;                         // replicas per block (1, 2, 4 or 8) and its log2
+    uint32_t nblocks;                              // ceil(replicas / rb)
+    uint32_t blocks_per_wg;                        // 1 (grid = tiles x blocks), or nblocks when tau = 0 (grid = tiles)
+    uint32_t active_mask;                          // bit i clear: replica i makes no local step in this launch
+                                                   // (w^ = w; m, v kept; its gradient pointer is not read)
+    uint32_t lookahead;
     // averaging
     uint32_t do_send, do_recv, ema, same_slot;     // ema: a correction vector d is kept; same_slot: tau = 0,
                                                    // the average is of this step's w^
     uint32_t do_next;                              // also count the lines each tile will send next step
     uint32_t msg_dtype;                            // precision of the exchanged values: 0 fp32, 1 bf16, 2 E4M3
-    SubsetKey key_send, key_recv, key_next;
-    uint32_t *next_lines;                          // [ntiles], written when do_next
-    float *ring_send;                              // slot written now: [replica][line][32]
+    uint32_t cap_lines;                            // lines (of 32 floats) per block in a ring slot
+    const uint32_t *send_meta, *send_sb_base;      // tile's word: lines << 24 | offset in its superblock; first line = sb_base[tile >> 9] + offset
+    const uint32_t *recv_meta, *recv_sb_base;
+    float *ring_send;                              // slot written now: [block][line][32], a line = [coordinate][rb]
     const float *ring_recv;                        // slot sent tau rounds ago
-    const uint32_t *send_local_off, *send_sb_base; // first line of each tile = sb_base[tile >> 9] + local_off[tile]
-    const uint32_t *recv_local_off, *recv_sb_base;
-    uint32_t cap_lines;                            // lines (of 32 floats) per replica in a ring slot
+    uint32_t *next_lines;                          // [ntiles], written when do_next
+    const float *replica_scale;                    // NULL, or one more gradient factor per replica (DEVICE)
+    SubsetKey key;                                 // seed, threshold and sampling rule; the step words are filled per job
+    uint32_t step_lo[3], step_hi[3];               // the steps whose subsets are hashed: [0] received now, [1] sent now, [2] sent next step
     double coef_d, coef_s;                         // d <- coef_d d + coef_s (w^ - sent): EMA (1-lambda, lambda), eager (0, 1/R)
     // optimizer, every coefficient a per-step scalar evaluated once on the host in double:
     //   g  = grad_scale * g_raw                        (folded into b_m, b_v, c_g on the host)
     //   m' = a_m m + b_m g ;  v' = a_v v + b_v g^2
     //   w^ = w - (c_wd w + (c_g g + c_m m') / (c_v sqrt(v') + eps))           (Adam family)
     //   w^ = w - (c_wd w + c_m m')     resp.     w - (c_wd w + c_g g)          (SGD with / without momentum)
-    // c_g, c_m, c_v hold the bias corrections and are per replica: replicas of unequal speed have made
-    // unequal numbers of optimizer steps.  A replica whose bit in active_mask is clear makes no local
-    // step in this launch (w^ = w; m, v kept; its gradient pointer is not read).
     double a_m, b_m, a_v, b_v, c_wd, eps;
-    double c_g[kMaxReplicas], c_m[kMaxReplicas], c_v[kMaxReplicas];
-    uint32_t active_mask;
-    uint32_t lookahead;
     double gamma;
-    const float *replica_scale;                    // NULL, or one more gradient factor per replica (DEVICE)
+    float *d[kMaxReplicas];          // one array per replica, or (interleaved) one per block: [tiles * 256][rb]
+    ReplicaArgs rep[kMaxReplicas];
 };
 
 // Precision.  State is fp32 in memory (the method's precision).  The accumulating expressions
@@ -202,12 +212,12 @@ __device__ __forceinline__ double quotient_refined(double num, double den)
 // What one replica's update of one group reads from memory.
 struct GroupIn {
     F4 w, g, m, v;          // weights, gradients (widened), moments
-    F4 d;                   // EMA entries of the group (loaded only when its line receives)
+    F4 d;                   // EMA entries of the group (per-replica layout: loaded when its line receives)
 };
 
 // Local optimizer step on one group, from loaded operands.
 template <int OPT>
-__device__ __forceinline__ void local_step(const StepArgs &a, uint32_t i, const GroupIn &in,
+__device__ __forceinline__ void local_step(const StepArgs &a, const ReplicaArgs &r, uint32_t i, const GroupIn &in,
                                            F4 &w_hat, F4 &m_new, F4 &v_new)
 {
     // A replica that is idle in this tick goes through the same arithmetic with the coefficients of
@@ -217,7 +227,7 @@ __device__ __forceinline__ void local_step(const StepArgs &a, uint32_t i, const 
     const double a_m = idle ? 1.0 : a.a_m, b_m = idle ? 0.0 : a.b_m;
     const double a_v = idle ? 1.0 : a.a_v, b_v = idle ? 0.0 : a.b_v;
     const double c_wd = idle ? 0.0 : a.c_wd;
-    const double c_g = a.c_g[i], c_m = a.c_m[i], c_v = a.c_v[i];
+    const double c_g = r.c_g, c_m = r.c_m, c_v = r.c_v;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         if (OPT == kOptNone) {                                 // averaging only: the caller's w is w^
@@ -251,265 +261,422 @@ __device__ __forceinline__ void wave_lds_sync()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// Where the coordinates of one group sit in the subsets of this step.
+// Where the coordinates of one group (= one lane) sit in the subsets of this step.
 struct GroupSubsets {
     uint32_t mask_send, mask_recv;      // bit j: coordinate 4*group + j is sent / received now
     uint32_t rank_send, rank_recv;      // rank of the first such coordinate among those of the tile
-    uint32_t count_recv;                // received coordinates of the tile
-    uint64_t run_send, run_recv;        // float offset, inside one replica's part of the slot, of the tile's lines
-    uint32_t lines_send;                // whole lines the tile sends per replica
-    bool line_recv;                     // the 128-byte line (of w, of d) holding the group receives something
+    bool line_recv;                     // the 128-byte line of a per-replica array (8 lanes) holding the group receives something
+    uint32_t d_slot;                    // interleaved d: float offset, in the LDS staging area, of the group's first entry
+};
+
+// LDS of one workgroup (floats): what the replicas sent tau rounds ago, the touched lines of d, the
+// lines about to be sent, and the list of touched lines.
+struct TileLds {
+    float *recv;        // [nblocks][256 coordinates in rank order][rb]
+    float *d;           // [touched line][32]         (interleaved d only)
+    float *send;        // [256 coordinates in rank order][rb]
+    uint32_t *list;     // [64] tile-local index of the q-th touched line of d
+    uint8_t *masks;     // [0..63] the lanes' masks of the sent subset, [64..127] of the received one
+    float *abar;        // [256] mean over the replicas of what they sent, per received coordinate in rank order
 };
 
 // Issues the loads of replica i's dense operands for one group.
 template <int OPT, bool GRAD_BF16>
-__device__ __forceinline__ void load_group(const StepArgs &a, uint32_t i, uint64_t mu, int nvalid, GroupIn &in)
+__device__ __forceinline__ void load_group(const StepArgs &a, const ReplicaArgs &r, uint32_t i, uint64_t tbase, uint32_t loff, int nvalid, GroupIn &in)
 {
-    in.w = load_f32x4(a.w[i], mu, nvalid);
+    in.w = load_f32x4(r.w + tbase, loff, nvalid);
     if ((a.active_mask >> i) & 1u)
-        in.g = GRAD_BF16 ? load_bf16x4(static_cast<const uint16_t *>(a.g[i]), mu, nvalid)
-                         : load_f32x4(static_cast<const float *>(a.g[i]), mu, nvalid);
+        in.g = GRAD_BF16 ? load_bf16x4(static_cast<const uint16_t *>(r.g) + tbase, loff, nvalid)
+                         : load_f32x4(static_cast<const float *>(r.g) + tbase, loff, nvalid);
     else
         in.g.v[0] = in.g.v[1] = in.g.v[2] = in.g.v[3] = 0.f;
-    if (OPT != kOptSgdPlain) in.m = load_f32x4(a.m[i], mu, nvalid);
-    if (OPT == kOptAdam) in.v = load_f32x4(a.v[i], mu, nvalid);
+    if (OPT != kOptSgdPlain) in.m = load_f32x4(r.m + tbase, loff, nvalid);
+    if (OPT == kOptAdam) in.v = load_f32x4(r.v + tbase, loff, nvalid);
 }
 
-// What the averaging alone touches: the EMA entries of a line that receives, and (when there is no
-// optimizer pass that reads w anyway) the weights of a group that sends or whose line receives.
-template <int OPT>
-__device__ __forceinline__ void load_group_sparse(const StepArgs &a, uint32_t i, uint64_t mu, int nvalid,
+// What the averaging alone touches in the per-replica arrays: the EMA entries of a line that
+// receives (per-replica layout of d), and (when there is no optimizer pass that reads w anyway) the
+// weights of a group that sends or whose line receives.
+template <int OPT, bool DIL>
+__device__ __forceinline__ void load_group_sparse(const StepArgs &a, uint32_t i, uint64_t tbase, uint32_t loff, int nvalid,
                                                   const GroupSubsets &s, GroupIn &in)
 {
-    if (a.ema && s.line_recv) in.d = load_f32x4(a.d[i], mu, nvalid);
-    if (OPT == kOptNone && (s.mask_send != 0u || s.line_recv)) in.w = load_f32x4(a.w[i], mu, nvalid);
+    if (!DIL && a.ema && s.line_recv) in.d = load_f32x4(a.d[i] + tbase, loff, nvalid);
+    if (OPT == kOptNone && (s.mask_send != 0u || s.line_recv)) in.w = load_f32x4(a.rep[i].w + tbase, loff, nvalid);
 }
 
-// Replica i of one group, from loaded operands to stored results.  sent_lds: what replica i sent
-// tau rounds ago for the received coordinates of the tile, in rank order.
-template <int OPT, int FWD>
-__device__ __forceinline__ void step_replica(const StepArgs &a, uint32_t i, uint64_t mu, int nvalid, uint32_t lane,
-                                             const GroupSubsets &s, const float (&abar)[4], GroupIn &in,
-                                             const float *sent_lds, float *send_lds)
+// Replica i (slot `slot` of its block) of one group, from loaded operands to stored results.
+// recv_block: what the replicas of i's block sent tau rounds ago, [rank][rb].
+template <int OPT, int FWD, bool DIL, bool TAU0>
+__device__ __forceinline__ void step_replica(const StepArgs &a, const ReplicaArgs &r, uint32_t i, uint32_t slot, uint64_t tbase, uint32_t loff, int nvalid,
+                                             const GroupSubsets &s, const bool tile_receives, const float (&abar)[4], GroupIn &in,
+                                             const float *recv_block, const TileLds &L)
 {
+    const uint32_t rb = a.rb;
     F4 w_hat, m_new, v_new;
-    local_step<OPT>(a, i, in, w_hat, m_new, v_new);
+    local_step<OPT>(a, r, i, in, w_hat, m_new, v_new);
+    // the moments are final: out they go, before the averaging needs registers
+    if (OPT == kOptSgdMomentum || OPT == kOptAdam) store_f32x4(r.m + tbase, loff, nvalid, m_new);
+    if (OPT == kOptAdam) store_f32x4(r.v + tbase, loff, nvalid, v_new);
 
-    if (s.lines_send) {
-        // send: the tile's w^ values are gathered in LDS (the tail of the last line stays zero) and
-        // leave as whole 128-byte lines
+    if (s.mask_send) {                                     // send: into the staging lines, [rank][rb]
         uint32_t c = s.rank_send;
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-            if ((s.mask_send >> j) & 1u) send_lds[c++] = w_hat.v[j];
-        wave_lds_sync();
-        float *__restrict__ dst = a.ring_send + (uint64_t)i * a.cap_lines * kLineFloats + s.run_send;
-        for (uint32_t r = lane; r < s.lines_send * kLineFloats; r += 64u) __builtin_nontemporal_store(send_lds[r], dst + r);
-        wave_lds_sync();
+            if ((s.mask_send >> j) & 1u) L.send[(c++) * rb + slot] = w_hat.v[j];
     }
 
     F4 w_new;
 #pragma unroll
     for (int j = 0; j < 4; ++j) w_new.v[j] = w_hat.v[j];
-    if (s.mask_recv) {                                     // receive: old average (+ EMA of staleness)
-        uint32_t c = s.rank_recv;
+    if (tile_receives) {                                   // receive: old average (+ EMA of staleness)
+        // Same for the whole workgroup, and free of branches inside: every lane reads (a lane without
+        // a received coordinate reads entry 0 and drops the result), so that the LDS reads of the four
+        // coordinates are in flight together instead of one dependent round trip per coordinate.
+        uint32_t cj[4], c = s.rank_recv;
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            if ((s.mask_recv >> j) & 1u) {
-                if (a.ema) {
-                    const float sent = a.same_slot ? w_hat.v[j] : sent_lds[c];
-                    in.d.v[j] = (float)fma(a.coef_d, (double)in.d.v[j],
-                                           a.coef_s * ((double)w_hat.v[j] - (double)sent));
-                    w_new.v[j] = (float)((double)abar[j] + (double)in.d.v[j]);
-                } else {
-                    w_new.v[j] = abar[j];
-                }
-                ++c;
+        for (int j = 0; j < 4; ++j) { const uint32_t bit = (s.mask_recv >> j) & 1u; cj[j] = bit ? c : 0u; c += bit; }
+        if (a.ema) {
+            float sent[4], d_old[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t bit = (s.mask_recv >> j) & 1u;
+                sent[j] = TAU0 ? w_hat.v[j] : recv_block[cj[j] * rb + slot];
+                d_old[j] = DIL ? L.d[bit ? s.d_slot + (uint32_t)j * rb + slot : 0u] : in.d.v[j];
             }
-    }
-    if (a.ema && s.line_recv) store_f32x4(a.d[i], mu, nvalid, in.d);
-
-    if (OPT == kOptNone) {                                 // averaging only: rewrite just the lines that receive
-        if (s.line_recv) store_f32x4(a.w[i], mu, nvalid, w_new);
-        return;
-    }
-    store_f32x4(a.w[i], mu, nvalid, w_new);
-    if (OPT == kOptSgdMomentum || OPT == kOptAdam) store_f32x4(a.m[i], mu, nvalid, m_new);
-    if (OPT == kOptAdam) store_f32x4(a.v[i], mu, nvalid, v_new);
-    if (FWD != kFwdNone) {
-        F4 f = w_new;
-        if (a.lookahead) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float d_new = (float)fma(a.coef_d, (double)d_old[j], a.coef_s * ((double)w_hat.v[j] - (double)sent[j]));
+                if ((s.mask_recv >> j) & 1u) {
+                    if (DIL) L.d[s.d_slot + (uint32_t)j * rb + slot] = d_new;
+                    else in.d.v[j] = d_new;
+                    w_new.v[j] = (float)((double)abar[j] + (double)d_new);
+                }
+            }
+        } else {
 #pragma unroll
             for (int j = 0; j < 4; ++j)
-                f.v[j] = (float)fma(a.gamma, (double)w_hat.v[j] - (double)in.w.v[j], (double)w_new.v[j]);
+                if ((s.mask_recv >> j) & 1u) w_new.v[j] = abar[j];
         }
-        if (FWD == kFwdF32) store_f32x4(static_cast<float *>(a.fwd[i]), mu, nvalid, f);
-        else store_bf16x4(static_cast<uint16_t *>(a.fwd[i]), mu, nvalid, f);
+    }
+    if (!DIL && a.ema && s.line_recv) store_f32x4(a.d[i] + tbase, loff, nvalid, in.d);
+
+    if (OPT == kOptNone) {                                 // averaging only: rewrite just the lines that receive
+        if (s.line_recv) store_f32x4(r.w + tbase, loff, nvalid, w_new);
+        return;
+    }
+    store_f32x4(r.w + tbase, loff, nvalid, w_new);
+    if (FWD != kFwdNone) {
+        // fwd = w + gamma (w^ - w_before): product and sum rounded separately in fp64, then ONE
+        // rounding to the stored type
+        double f[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            f[j] = a.lookahead ? __dadd_rn((double)w_new.v[j], __dmul_rn(a.gamma, (double)w_hat.v[j] - (double)in.w.v[j]))
+                               : (double)w_new.v[j];
+        if (FWD == kFwdF32) {
+            F4 o;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) o.v[j] = (float)f[j];
+            store_f32x4(static_cast<float *>(r.fwd) + tbase, loff, nvalid, o);
+        } else {
+            store_bf16x4_from_f64(static_cast<uint16_t *>(r.fwd) + tbase, loff, nvalid, f);
+        }
     }
 }
 
-// One workgroup per tile of 256 coordinates; its waves are the replicas (wave w takes replicas
-// w, w + W, ...; W = min(R, 8) waves), one lane per group of 4 coordinates.  Each wave streams
-// its replica's 1 KB of every array once and retires; measured on MI355X this shape, with
-// non-temporal accesses, is the fastest way through the 4-read / 4-write stream mix of this update.
-// Every wave hashes the tile's two subsets itself (integer work that hides under the memory time);
-// the only thing the waves of a tile share is what the replicas sent tau rounds ago, which they
-// put side by side in LDS to form the old average.
+// Mean over the replicas, in replica order and in fp64, of what they sent for the coordinate of
+// rank c of the tile (recv: [block][rank][RB]): the RB values of a block come with one or two wide
+// LDS reads.
+template <int RB>
+__device__ __forceinline__ float replica_mean(const StepArgs &a, const float *recv, uint32_t c)
+{
+    double sum = 0.;
+    for (uint32_t b = 0; b < a.nblocks; ++b) {
+        const uint32_t nrep = a.replicas - b * RB;         // replicas present in this block (>= RB: all)
+        const float *p = recv + b * (kTileCoords * RB) + c * RB;
+        float x[RB];
+        if (RB == 8) {
+            const v4f lo = *reinterpret_cast<const v4f *>(p), hi = *reinterpret_cast<const v4f *>(p + 4);
+            x[0] = lo.x; x[1 % RB] = lo.y; x[2 % RB] = lo.z; x[3 % RB] = lo.w;
+            x[4 % RB] = hi.x; x[5 % RB] = hi.y; x[6 % RB] = hi.z; x[7 % RB] = hi.w;
+        } else if (RB == 4) {
+            const v4f lo = *reinterpret_cast<const v4f *>(p);
+            x[0] = lo.x; x[1 % RB] = lo.y; x[2 % RB] = lo.z; x[3 % RB] = lo.w;
+        } else if (RB == 2) {
+            const v2f lo = *reinterpret_cast<const v2f *>(p);
+            x[0] = lo.x; x[1 % RB] = lo.y;
+        } else {
+            x[0] = p[0];
+        }
+        if (a.msg_dtype != 0u) {
+#pragma unroll
+            for (int k = 0; k < RB; ++k) x[k] = quantize_message(x[k], a.msg_dtype);
+        }
+#pragma unroll
+        for (int k = 0; k < RB; ++k)
+            if ((uint32_t)k < nrep) sum += (double)x[k];
+    }
+    return (float)(sum * (1.0 / (double)a.replicas));
+}
+
+// One workgroup per (tile of 256 coordinates, block of rb <= 8 replicas); its rb waves are the
+// replicas of the block, one lane per group of 4 coordinates.  Each wave streams its replica's 1 KB
+// of every per-replica array once, with non-temporal accesses (measured on MI355X: the fastest way
+// through the 4-read / 4-write stream mix of this update).
 //
-// This memory system writes 128-byte lines: a narrower write costs a read-modify-write of the line
-// and, measured, several times the time of a whole-line write.  Both sparse structures are
-// therefore laid out so that only whole lines are ever written:
-//  * Ring slot: per replica, every tile owns ceil(count / 32) whole lines ([replica][line][32]);
-//    a tile's selected values sit at the start of its lines in ascending coordinate order, the rest
-//    of the last line is zero.  A wave gathers its values in LDS and stores whole lines.
-//  * EMA vector d: dense in memory, touched only on received coordinates.  The 8 lanes that share
-//    a 128-byte line of d load and store their groups together whenever any of them holds a
-//    received coordinate, so the line is rewritten as a whole.
+// This memory system moves 128-byte lines, and a partial write costs several whole ones.  S^t is
+// the same for every replica, so the sparse structures keep the replicas of a block side by side,
+// [coordinate][replica]: a line holds 32 / rb coordinates of all rb replicas and is written as a whole.
+//  * Ring slot: per block, every tile owns ceil(count rb / 32) whole lines ([block][line][32]); the
+//    selected values sit in ascending coordinate order, the rest of the last line is zero.  The
+//    tile's word in the slot's offset table (a scalar load) says where its lines start and how
+//    many there are, so the lines sent tau rounds ago are requested without any hashing, straight
+//    into LDS; the waves gather this step's values in LDS and the lines leave with 16 bytes per thread.
+//  * EMA vector d, interleaved layout: [coordinate][replica] per block.  Lines that hold a received
+//    coordinate are copied to LDS (16 bytes per lane), updated there and written back whole.
+//    Per-replica layout: dense per replica; the 8 lanes that share a 128-byte line of d load and
+//    store their groups together whenever any of them holds a received coordinate.
+// Hashing a subset costs ten rounds of two 32 x 32 -> 64 multiplies per lane; the subsets are the
+// same for every wave of the workgroup, so (fused step) one wave hashes the received subset, one
+// the sent one, one the next step's, and the others read the 4-bit masks from LDS after the barrier
+// they have to pass anyway.  (Where the masks steer loads of per-replica arrays -- the per-replica
+// layout of d, the averaging-only call -- every wave still hashes what it needs itself, so that
+// those loads go out before the barrier.)
 //
 // FULL = every coordinate of the tile exists (all but possibly the last tile of the stage): all
 // dense accesses are unconditional 128-bit ones.
-template <int OPT, bool GRAD_BF16, int FWD, bool FULL>
-__device__ __forceinline__ void step_tile(const StepArgs &a, uint32_t tile, uint32_t wave, uint32_t nwaves,
-                                          uint32_t lane, float *sent_lds, float *send_lds)
+// TAU0 = the average is of this very step's values (tau = 0): the workgroup walks all the blocks
+// of its tile, because it needs every replica's new weights (a rarely used mode, kept out of the
+// code of the common one).
+template <int OPT, bool GRAD_BF16, int FWD, bool DIL, bool TAU0, bool FULL>
+__device__ __forceinline__ void step_tile(const StepArgs &a, const uint32_t tile, const uint32_t b0, const uint32_t wave,
+                                          const uint32_t lane, const TileLds &L)
 {
-    const uint32_t R = a.replicas;
+    constexpr bool kShareRecv = DIL && OPT != kOptNone;    // one wave hashes the received subset for all
+    constexpr bool kShareSend = OPT != kOptNone;           // one wave hashes the sent subset for all
+    const uint32_t R = a.replicas, rb = a.rb, sh = a.rb_shift;
+    const uint32_t flat = wave * 64u + lane;                               // 64 rb threads; thread f owns 16-byte chunk f
     const uint64_t group = (uint64_t)tile * 64u + lane;
     const uint64_t mu = group * 4u;
     const int nvalid = FULL ? 4 : (mu >= a.n ? 0 : (a.n - mu >= 4u ? 4 : (int)(a.n - mu)));
-    const uint64_t slot_floats = (uint64_t)a.cap_lines * kLineFloats;      // per replica
+    // addresses in the per-replica arrays: a pointer that is the same for the whole wave plus a 32-bit lane offset
+    const uint64_t tbase = (uint64_t)tile * kTileCoords;
+    const uint32_t loff = lane * 4u;
+    const uint64_t block_floats = (uint64_t)a.cap_lines * kLineFloats;     // one block's part of a ring slot
+    const uint32_t tile_floats = kTileCoords * rb;                         // one tile's part of an interleaved array
+    constexpr bool recv_is_send = TAU0;                                    // the host launches TAU0 iff do_recv && same_slot
 
-    // Averaging alone moves little per replica, so a wave keeps the loads of four of its replicas in
-    // flight together; with the optimizer pass one replica's operands fill the registers.
-    constexpr uint32_t DEPTH = OPT == kOptNone ? 4u : 1u;
+    // ---- dense operands of my replica of the first block: nothing else is requested before them
+    uint32_t i = b0 * rb + wave;
+    ReplicaArgs rep = a.rep[i < R ? i : 0u];               // my replica's pointers and coefficients, one scalar load
+    GroupIn in;
+    if (OPT != kOptNone && i < R) load_group<OPT, GRAD_BF16>(a, rep, i, tbase, loff, nvalid, in);
+    __builtin_amdgcn_sched_barrier(0);
 
-    // first replica's dense operands go out before anything else waits on memory
-    GroupIn in[DEPTH];
-    if (OPT != kOptNone) load_group<OPT, GRAD_BF16>(a, wave, mu, nvalid, in[0]);
+    // ---- the tile's words in the offset tables of the two slots (scalar loads)
+    uint32_t word_s = 0, base_s = 0, word_r = 0, base_r = 0;
+    if (a.do_send) { word_s = uniform_load(a.send_meta, tile); base_s = uniform_load(a.send_sb_base, tile / kTilesPerSuperblock); }
+    if (a.do_recv && !TAU0) { word_r = uniform_load(a.recv_meta, tile); base_r = uniform_load(a.recv_sb_base, tile / kTilesPerSuperblock); }
 
-    // ---- subsets: which of my 4 coordinates are sent now / received now, and where the tile's
-    //      lines start.  A tile whose lines would pass the slot capacity is left out, at send and at
-    //      receive alike.
+    // ---- where the tile's lines sit in the two slots.  A tile whose lines would pass the slot
+    //      capacity is left out, at send and at receive alike.
+    uint32_t first_s = base_s + (word_s & 0xFFFFFFu), lines_s = word_s >> 24;
+    uint32_t first_r = base_r + (word_r & 0xFFFFFFu), lines_r = word_r >> 24;
+    bool keep_s = a.do_send != 0u, keep_r = a.do_recv != 0u;
+    if ((uint64_t)first_s + lines_s > a.cap_lines) { keep_s = false; lines_s = 0; }
+    if (recv_is_send) { first_r = first_s; lines_r = lines_s; keep_r = keep_s; }
+    else if ((uint64_t)first_r + lines_r > a.cap_lines) { keep_r = false; lines_r = 0; }
+
+    // ---- what every replica sent tau rounds ago: straight into LDS
+    if (a.do_recv && !TAU0 && flat < lines_r * 8u) {
+        const float *src = a.ring_recv + (uint64_t)first_r * kLineFloats + flat * 4u;
+        for (uint32_t b = 0; b < a.nblocks; ++b)
+            lds_dma_16(src + b * block_floats, L.recv + b * tile_floats + wave * 256u);
+    }
+
+    // ---- subsets: bit j of a lane's mask = coordinate 4 group + j is received / sent now.
+    //      Jobs: 0 = the received subset, 1 = the sent one, 2 = the size of what the next step sends.
+    //      A shared job is done by wave (job mod rb), the others by every wave for itself.
     GroupSubsets s;
-    s.mask_send = s.mask_recv = s.rank_send = s.rank_recv = s.lines_send = s.count_recv = 0;
-    s.run_send = s.run_recv = 0;
-    if (a.do_send) {
-        uint32_t count;
-        s.mask_send = member_mask(a.key_send, group, nvalid);
-        s.rank_send = wave_prefix_mask4(s.mask_send, count);
-        const uint32_t first = a.send_sb_base[tile / kTilesPerSuperblock] + a.send_local_off[tile];
-        s.lines_send = (count + kLineFloats - 1u) / kLineFloats;
-        if ((uint64_t)first + s.lines_send > a.cap_lines) { s.mask_send = 0; s.lines_send = 0; count = 0; }
-        s.run_send = (uint64_t)first * kLineFloats;
-        if (a.same_slot) s.count_recv = count;
-    }
-    if (a.do_recv) {
-        if (a.same_slot) {
-            s.mask_recv = s.mask_send; s.rank_recv = s.rank_send; s.run_recv = s.run_send;
-        } else {
-            s.mask_recv = member_mask(a.key_recv, group, nvalid);
-            s.rank_recv = wave_prefix_mask4(s.mask_recv, s.count_recv);
-            const uint32_t first = a.recv_sb_base[tile / kTilesPerSuperblock] + a.recv_local_off[tile];
-            const uint32_t lines = (s.count_recv + kLineFloats - 1u) / kLineFloats;
-            if ((uint64_t)first + lines > a.cap_lines) { s.mask_recv = 0; s.count_recv = 0; }
-            s.run_recv = (uint64_t)first * kLineFloats;
-        }
-    }
-    {
-        const uint64_t any = __ballot(s.mask_recv != 0u);
-        s.line_recv = ((any >> (lane & ~7u)) & 0xFFull) != 0ull;
-    }
+    s.mask_send = s.mask_recv = s.rank_send = s.rank_recv = s.d_slot = 0;
+    s.line_recv = false;
+    const uint32_t lpl = 8u >> sh;                                         // lanes (groups) per 128-byte line of d
+    const uint32_t leader = lane & ~(lpl - 1u);
 #pragma unroll
-    for (uint32_t k = 0; k < DEPTH; ++k)
-        if (wave + k * nwaves < R) load_group_sparse<OPT>(a, wave + k * nwaves, mu, nvalid, s, in[k]);
-
-    if (a.do_next && wave == 0) {                           // one wave per tile sizes the next step's send
-        uint32_t count;
-        (void)wave_prefix_mask4(member_mask(a.key_next, group, nvalid), count);
-        if (lane == 0) a.next_lines[tile] = (count + kLineFloats - 1u) / kLineFloats;
-    }
-
-    if (s.lines_send) {                                     // zero the gather area once: line tails stay zero
-        for (uint32_t r = lane; r < s.lines_send * kLineFloats; r += 64u) send_lds[r] = 0.f;
-    }
-
-    // ---- old average of the coordinates received now: every wave puts what its replicas sent
-    //      (tau = 0: their w^ of this step) side by side in LDS, then each lane sums over the replicas
-    float abar[4] = {0.f, 0.f, 0.f, 0.f};
-    if (a.do_recv) {                                        // same for the whole workgroup
-        for (uint32_t i = wave; i < R; i += nwaves) {
-            float *row = sent_lds + i * kTileCoords;
-            if (a.same_slot) {
-                if (s.count_recv) {
-                    GroupIn pre;
-                    F4 w_hat, m_new, v_new;
-                    if (i == wave) {
-                        pre = in[0];
-                    } else {
-                        if (OPT != kOptNone) load_group<OPT, GRAD_BF16>(a, i, mu, nvalid, pre);
-                        load_group_sparse<OPT>(a, i, mu, nvalid, s, pre);
+    for (uint32_t job = 0; job < 3u; ++job) {
+        const bool shared = job == 0u ? kShareRecv : job == 1u ? kShareSend : true;
+        if (shared && wave != (job & (rb - 1u))) continue;
+        if (job == 0u && !keep_r) continue;
+        if (job == 1u && (!keep_s || recv_is_send)) continue;
+        if (job == 2u && !(a.do_next && b0 == 0u)) continue;
+        SubsetKey key = a.key;
+        const uint32_t which = (job == 0u && recv_is_send) ? 1u : job;
+        key.step_lo = a.step_lo[which]; key.step_hi = a.step_hi[which];
+        const uint32_t mask = member_mask(key, group, nvalid);
+        if (job == 0u) {
+            s.mask_recv = mask;
+            if (kShareRecv) L.masks[64u + lane] = (uint8_t)mask;
+            // interleaved d: the lines of the tile that hold a received coordinate, straight into LDS (one wave)
+            if (DIL && a.ema && wave == 0u) {
+                const uint64_t any_recv = __ballot(mask != 0u);
+                const bool touched = ((any_recv >> leader) & ((1ull << lpl) - 1ull)) != 0ull;
+                const uint64_t leaders = __ballot(touched && lane == leader);
+                const uint32_t nlines = (uint32_t)__popcll(leaders);
+                if (nlines) {
+                    if (touched && lane == leader) L.list[__popcll(leaders & ((1ull << leader) - 1ull))] = lane >> (3u - sh);
+                    wave_lds_sync();
+                    const float *src = a.d[b0] + (uint64_t)tile * tile_floats + (lane & 7u) * 4u;
+                    for (uint32_t q0 = 0; q0 < nlines; q0 += 8u) {
+                        const uint32_t q = q0 + (lane >> 3);
+                        if (q < nlines) lds_dma_16(src + L.list[q] * kLineFloats, L.d + q0 * kLineFloats);
                     }
-                    local_step<OPT>(a, i, pre, w_hat, m_new, v_new);
-                    uint32_t c = s.rank_recv;
-#pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        if ((s.mask_recv >> j) & 1u) row[c++] = w_hat.v[j];
                 }
-            } else {
-                const float *__restrict__ src = a.ring_recv + (uint64_t)i * slot_floats + s.run_recv;
-                for (uint32_t c = lane; c < s.count_recv; c += 64u) row[c] = src[c];
             }
-        }
-        __syncthreads();
-        if (s.mask_recv) {
-            const double inv_r = 1.0 / (double)R;
-            uint32_t c = s.rank_recv;
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                if ((s.mask_recv >> j) & 1u) {
-                    double sum = 0.;
-                    for (uint32_t i = 0; i < R; ++i) sum += (double)quantize_message(sent_lds[i * kTileCoords + c], a.msg_dtype);
-                    abar[j] = (float)(sum * inv_r);
-                    ++c;
-                }
+        } else if (job == 1u) {
+            s.mask_send = mask;
+            if (kShareSend) L.masks[lane] = (uint8_t)mask;
+        } else {
+            uint32_t count;
+            (void)wave_prefix_mask4(mask, count);
+            if (lane == 0) a.next_lines[tile] = (count * rb + kLineFloats - 1u) / kLineFloats;
         }
     }
+    if (!kShareRecv) {                                     // loads of per-replica arrays that the masks steer
+        const uint64_t any_recv = __ballot(s.mask_recv != 0u);
+        s.line_recv = ((any_recv >> (lane & ~7u)) & 0xFFull) != 0ull;
+        if (!kShareSend && recv_is_send) s.mask_send = s.mask_recv;
+        if (i < R) load_group_sparse<OPT, DIL>(a, i, tbase, loff, nvalid, s, in);
+    }
 
-    // ---- my replicas
-    for (uint32_t base = wave; base < R; base += DEPTH * nwaves) {
-        if (base != wave) {
-#pragma unroll
-            for (uint32_t k = 0; k < DEPTH; ++k) {
-                const uint32_t i = base + k * nwaves;
-                if (i < R) {
-                    if (OPT != kOptNone) load_group<OPT, GRAD_BF16>(a, i, mu, nvalid, in[k]);
-                    load_group_sparse<OPT>(a, i, mu, nvalid, s, in[k]);
+    // ---- staging lines of the send start at zero: line tails and the slots of absent replicas stay zero
+    if (flat < lines_s * 8u) *reinterpret_cast<v4f *>(L.send + flat * 4u) = v4f{0.f, 0.f, 0.f, 0.f};
+
+    // the masks of the hashing waves, ranks inside the tile, and where the group's d entries sit in LDS
+    uint32_t count_recv = 0, d_lines = 0;
+    auto finish_subsets = [&]() {
+        if (kShareRecv) s.mask_recv = keep_r ? (uint32_t)L.masks[64u + lane] : 0u;
+        if (kShareSend) s.mask_send = recv_is_send ? s.mask_recv : (keep_s ? (uint32_t)L.masks[lane] : 0u);
+        uint32_t count_send;
+        s.rank_send = wave_prefix_mask4(s.mask_send, count_send);
+        if (recv_is_send) { s.rank_recv = s.rank_send; count_recv = count_send; }
+        else s.rank_recv = wave_prefix_mask4(s.mask_recv, count_recv);
+        const uint64_t any_recv = __ballot(s.mask_recv != 0u);
+        s.line_recv = ((any_recv >> (lane & ~7u)) & 0xFFull) != 0ull;
+        if (DIL && a.ema) {
+            const bool touched = ((any_recv >> leader) & ((1ull << lpl) - 1ull)) != 0ull;
+            const uint64_t leaders = __ballot(touched && lane == leader);
+            d_lines = (uint32_t)__popcll(leaders);
+            s.d_slot = (uint32_t)__popcll(leaders & ((1ull << leader) - 1ull)) * kLineFloats + (lane & (lpl - 1u)) * 4u * rb;
+        }
+    };
+
+    // ---- tau = 0: the average is of this step's w^ : every wave puts those of its replicas in place
+    if (recv_is_send) {
+        if (kShareRecv) __syncthreads();                   // the masks are in LDS
+        finish_subsets();
+        if (count_recv) {
+            for (uint32_t b = 0; b < a.nblocks; ++b) {
+                const uint32_t ib = b * rb + wave;
+                if (ib >= R) continue;
+                GroupIn pre;
+                F4 w_hat, m_new, v_new;
+                if (b == b0) {
+                    pre = in;
+                } else {
+                    if (OPT != kOptNone) load_group<OPT, GRAD_BF16>(a, a.rep[ib], ib, tbase, loff, nvalid, pre);
+                    load_group_sparse<OPT, DIL>(a, ib, tbase, loff, nvalid, s, pre);
                 }
+                local_step<OPT>(a, a.rep[ib], ib, pre, w_hat, m_new, v_new);
+                uint32_t c = s.rank_recv;
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if ((s.mask_recv >> j) & 1u) L.recv[b * tile_floats + (c++) * rb + wave] = w_hat.v[j];
             }
         }
+    }
+    lds_dma_wait();
+    __syncthreads();
+    if (!recv_is_send) finish_subsets();
+
+    // ---- old average of the coordinates received now: thread c forms the mean of the coordinate of
+    //      rank c once for the whole workgroup (in fp64, in replica order); after one more barrier every
+    //      lane picks up the means of its own coordinates (a lane with fewer than four reads entry 0 and
+    //      drops it, so that the four reads are in flight together)
+    float abar[4] = {0.f, 0.f, 0.f, 0.f};
+    if (count_recv) {                                      // same for the whole workgroup
+        for (uint32_t c = flat; c < count_recv; c += 64u * rb)
+            L.abar[c] = rb == 8u ? replica_mean<8>(a, L.recv, c) : rb == 4u ? replica_mean<4>(a, L.recv, c)
+                      : rb == 2u ? replica_mean<2>(a, L.recv, c) : replica_mean<1>(a, L.recv, c);
+        __syncthreads();
+        uint32_t c = s.rank_recv;
 #pragma unroll
-        for (uint32_t k = 0; k < DEPTH; ++k) {
-            const uint32_t i = base + k * nwaves;
-            if (i < R) step_replica<OPT, FWD>(a, i, mu, nvalid, lane, s, abar, in[k], sent_lds + i * kTileCoords, send_lds);
+        for (int j = 0; j < 4; ++j) { const uint32_t bit = (s.mask_recv >> j) & 1u; abar[j] = L.abar[bit ? c : 0u]; c += bit; }
+    }
+
+    // my chunk of the touched lines of d: float offset inside the tile's part of the array
+    const uint32_t d_chunk_off = (DIL && flat < d_lines * 8u) ? L.list[flat >> 3] * kLineFloats + (flat & 7u) * 4u : 0u;
+
+    // ---- my replica of each block of this workgroup (one block, except when tau = 0 and R > 8)
+    for (uint32_t bb = 0; bb < (TAU0 ? a.blocks_per_wg : 1u); ++bb) {
+        const uint32_t b = b0 + bb;
+        i = b * rb + wave;
+        if (TAU0 && bb != 0u) {
+            __syncthreads();                               // the staging areas are free again
+            if (flat < lines_s * 8u) *reinterpret_cast<v4f *>(L.send + flat * 4u) = v4f{0.f, 0.f, 0.f, 0.f};
+            if (DIL && flat < d_lines * 8u)
+                lds_dma_16(a.d[b] + (uint64_t)tile * tile_floats + d_chunk_off, L.d + wave * 256u);
+            if (i < R) {
+                rep = a.rep[i];
+                if (OPT != kOptNone) load_group<OPT, GRAD_BF16>(a, rep, i, tbase, loff, nvalid, in);
+                load_group_sparse<OPT, DIL>(a, i, tbase, loff, nvalid, s, in);
+            }
+            lds_dma_wait();
+            __syncthreads();
+        }
+        if (i < R) step_replica<OPT, FWD, DIL, TAU0>(a, rep, i, wave, tbase, loff, nvalid, s, count_recv != 0u, abar, in, L.recv + b * tile_floats, L);
+        __syncthreads();
+        // whole lines leave with 16 bytes per thread
+        if (flat < lines_s * 8u) {
+            float *dst = a.ring_send + b * block_floats + (uint64_t)first_s * kLineFloats + flat * 4u;
+            __builtin_nontemporal_store(*reinterpret_cast<const v4f *>(L.send + flat * 4u), reinterpret_cast<v4f *>(dst));
+        }
+        if (DIL && flat < d_lines * 8u) {
+            float *dst = a.d[b] + (uint64_t)tile * tile_floats + d_chunk_off;
+            __builtin_nontemporal_store(*reinterpret_cast<const v4f *>(L.d + flat * 4u), reinterpret_cast<v4f *>(dst));
         }
     }
 }
 
-// grid = one workgroup per tile; blockDim = 64 * min(R, 8); dynamic LDS = (R + waves) * 256 floats
-template <int OPT, bool GRAD_BF16, int FWD>
-__global__ void __launch_bounds__(512)
+// Floats of dynamic LDS a workgroup needs.
+__host__ __device__ inline uint32_t step_lds_floats(uint32_t rb, uint32_t nblocks, bool d_interleaved)
+{
+    return nblocks * kTileCoords * rb + (d_interleaved ? kTileCoords * rb : 0u) + kTileCoords * rb + 64u + 32u + kTileCoords;
+}
+
+// grid = tiles x blocks (tau = 0: tiles); blockDim = 64 rb; dynamic LDS = step_lds_floats() floats
+// (at most 80 registers, so that three workgroups of eight waves fit a compute unit)
+template <int OPT, bool GRAD_BF16, int FWD, bool DIL, bool TAU0>
+__global__ void __launch_bounds__(512, 6)
 k_step(const StepArgs a)
 {
-    extern __shared__ float lds[];
+    extern __shared__ __attribute__((aligned(16))) float lds[];
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const uint32_t nwaves = blockDim.x >> 6;
-    const uint32_t tile = blockIdx.x;
-    float *sent_lds = lds;                                              // [R][256]
-    float *send_lds = lds + (a.replicas + wave) * kTileCoords;         // [wave][256]
+    uint32_t tile = blockIdx.x, b0 = 0;
+    if (!TAU0 && a.nblocks > 1u) { tile = blockIdx.x / a.nblocks; b0 = blockIdx.x - tile * a.nblocks; }
+    const uint32_t tile_floats = kTileCoords * a.rb;
+    TileLds L;
+    L.recv = lds;
+    L.d = L.recv + a.nblocks * tile_floats;
+    L.send = L.d + (DIL ? tile_floats : 0u);
+    L.list = reinterpret_cast<uint32_t *>(L.send + tile_floats);
+    L.masks = reinterpret_cast<uint8_t *>(L.list + 64);
+    L.abar = reinterpret_cast<float *>(L.list + 96);
     if ((uint64_t)(tile + 1u) * kTileCoords <= a.n)
-        step_tile<OPT, GRAD_BF16, FWD, true>(a, tile, wave, nwaves, lane, sent_lds, send_lds);
+        step_tile<OPT, GRAD_BF16, FWD, DIL, TAU0, true>(a, tile, b0, wave, lane, L);
     else
-        step_tile<OPT, GRAD_BF16, FWD, false>(a, tile, wave, nwaves, lane, sent_lds, send_lds);
+        step_tile<OPT, GRAD_BF16, FWD, DIL, TAU0, false>(a, tile, b0, wave, lane, L);
 }
 
 // =============================================================================================
@@ -526,11 +693,17 @@ k_lookahead(void *__restrict__ out, const float *__restrict__ w, const float *__
         const uint64_t mu = group * 4u;
         const int nvalid = n - mu >= 4u ? 4 : (int)(n - mu);
         const F4 a = load_f32x4(w, mu, nvalid), b = load_f32x4(w_prev, mu, nvalid);
-        F4 f;
+        double f[4];                                   // product and sum rounded separately in fp64, then one rounding
 #pragma unroll
-        for (int j = 0; j < 4; ++j) f.v[j] = (float)fma(gamma, (double)a.v[j] - (double)b.v[j], (double)a.v[j]);
-        if (OUT_BF16) store_bf16x4(static_cast<uint16_t *>(out), mu, nvalid, f);
-        else store_f32x4(static_cast<float *>(out), mu, nvalid, f);
+        for (int j = 0; j < 4; ++j) f[j] = __dadd_rn((double)a.v[j], __dmul_rn(gamma, (double)a.v[j] - (double)b.v[j]));
+        if (OUT_BF16) {
+            store_bf16x4_from_f64(static_cast<uint16_t *>(out), mu, nvalid, f);
+        } else {
+            F4 o;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) o.v[j] = (float)f[j];
+            store_f32x4(static_cast<float *>(out), mu, nvalid, o);
+        }
     }
 }
 
@@ -539,10 +712,11 @@ k_lookahead(void *__restrict__ out, const float *__restrict__ w, const float *__
 // =============================================================================================
 struct DiagArgs {
     const float *w[kMaxReplicas];
-    const float *d[kMaxReplicas];      // all NULL when there is no correction vector
+    const float *d[kMaxReplicas];      // replica i's entry of coordinate mu is d[i][mu * d_stride]; all NULL when there is no correction vector
     uint64_t n;
     uint32_t replicas;
     uint32_t has_d;
+    uint32_t d_stride;                 // 1 (one array per replica) or the replicas per block (interleaved)
 };
 
 // Workgroup b reduces the coordinates b, b + gridDim, ... (one coordinate per thread per pass) and
@@ -561,9 +735,9 @@ k_diag_partial(const DiagArgs a, double *__restrict__ partial)
         for (uint32_t i = 0; i < a.replicas; ++i) { const double e = (double)a.w[i][mu] - mean; cons += e * e; }
         if (a.has_d) {
             double dm = 0., v = 0.;
-            for (uint32_t i = 0; i < a.replicas; ++i) dm += (double)a.d[i][mu];
+            for (uint32_t i = 0; i < a.replicas; ++i) dm += (double)a.d[i][mu * a.d_stride];
             dm *= inv_r;
-            for (uint32_t i = 0; i < a.replicas; ++i) { const double e = (double)a.d[i][mu] - dm; v += e * e; }
+            for (uint32_t i = 0; i < a.replicas; ++i) { const double e = (double)a.d[i][mu * a.d_stride] - dm; v += e * e; }
             v *= inv_r;
             var_sum += v;
             var_max = v > var_max ? v : var_max;

@@ -5,19 +5,20 @@
 
 #include <hip/hip_runtime.h>
 
-#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
-#include <string>
-#include <vector>
 
+#include "am_host_logic.h"
 #include "am_kernels.h"
 
-#include <mutex>
+#ifndef AM_SOURCE_HASH
+#define AM_SOURCE_HASH "unknown"
+#endif
 
 // Scratch of am_subset_indices_static: per-tile offsets and per-superblock bases of one subset,
 // for stages of up to kStaticMaxN coordinates.  Every GPU the library runs on holds its own copy of
@@ -32,16 +33,19 @@ static __device__ __align__(256) uint32_t scratch[kStaticMaxTiles + kStaticMaxSb
 
 namespace {
 
-thread_local std::string g_last_error;
+using am_host::Layout;
+using am_host::Round;
+
+// message of the last failing call on this thread; a fixed buffer, so that reporting an error
+// allocates nothing and cannot throw
+thread_local char g_last_error[512] = "";
 
 am_status fail(am_status code, const char *fmt, ...)
 {
-    char buf[512];
     va_list ap;
     va_start(ap, fmt);
-    vsnprintf(buf, sizeof buf, fmt, ap);
+    vsnprintf(g_last_error, sizeof g_last_error, fmt, ap);
     va_end(ap);
-    g_last_error = buf;
     return code;
 }
 
@@ -51,51 +55,7 @@ am_status fail(am_status code, const char *fmt, ...)
         if (e_ != hipSuccess) return fail(AM_EHIP, "%s: %s", #call, hipGetErrorString(e_));   \
     } while (0)
 
-inline uint64_t round_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
 inline bool aligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
-
-uint64_t subset_threshold(double p)
-{
-    if (!(p > 0.0)) return 0;
-    if (p >= 1.0) return 1ull << 32;
-    return (uint64_t)std::floor(p * 4294967296.0);
-}
-
-// B = round(1/p) of the stratified sampling variant
-uint64_t stratified_block(double p)
-{
-    const long long B = std::llround(1.0 / p);
-    return B < 1 ? 1 : (uint64_t)B;
-}
-
-// Lines (of 32 floats) one replica's part of a ring slot must hold.  Every tile of 256
-// coordinates owns ceil(X / 32) whole lines, X ~ Binomial(256, p) its number of selected
-// coordinates; the slot has room for the expected total plus twelve standard deviations.
-uint64_t slot_capacity_lines(uint64_t ntiles, double p, bool by_line, uint64_t block)
-{
-    const uint64_t all = ntiles * (am::kTileCoords / am::kLineFloats);
-    if (p >= 1.0) return all;
-    if (block) {                         // stratified: a tile meets at most floor(255 / B) + 2 blocks, one member each: no chance involved
-        const uint64_t members = std::min<uint64_t>(am::kTileCoords, (am::kTileCoords - 1) / block + 2);
-        return std::min(all, ntiles * ((members + am::kLineFloats - 1) / am::kLineFloats));
-    }
-    if (by_line) {                       // every line of a tile is drawn as a whole: Binomial(8, p) lines
-        const double per = am::kTileCoords / am::kLineFloats;
-        const double cap = std::ceil((double)ntiles * per * p + 12.0 * std::sqrt((double)ntiles * per * p * (1.0 - p))) + 64.0;
-        return cap >= (double)all ? all : (uint64_t)cap;
-    }
-    double mean = 0.0, sq = 0.0;
-    const double lp = std::log(p), lq = std::log1p(-p), T = am::kTileCoords;
-    for (int k = 0; k <= (int)am::kTileCoords; ++k) {
-        const double pmf = std::exp(std::lgamma(T + 1.0) - std::lgamma(k + 1.0) - std::lgamma(T - k + 1.0) + k * lp + (T - k) * lq);
-        const double lines = (double)((k + am::kLineFloats - 1) / am::kLineFloats);
-        mean += pmf * lines;
-        sq += pmf * lines * lines;
-    }
-    const double var = sq - mean * mean > 0.0 ? sq - mean * mean : 0.0;
-    const double cap = std::ceil((double)ntiles * mean + 12.0 * std::sqrt((double)ntiles * var)) + 64.0;
-    return cap >= (double)all ? all : (uint64_t)cap;
-}
 
 constexpr int kMaxDevices = 64;
 std::mutex g_scratch_mutex;
@@ -105,44 +65,19 @@ uint32_t *g_scratch_ptr[kMaxDevices] = {};
 am_status resolve_static_scratch(int device, uint32_t **out)
 {
     if (device < 0 || device >= kMaxDevices) return fail(AM_EINVAL, "device %d is beyond the %d the static scratch table covers", device, kMaxDevices);
-    std::lock_guard<std::mutex> lock(g_scratch_mutex);
-    if (!g_scratch_ptr[device]) {
-        void *p = nullptr;
-        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
-        if (e != hipSuccess || !p) return fail(AM_EHIP, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(e));
-        g_scratch_ptr[device] = static_cast<uint32_t *>(p);
+    try {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        if (!g_scratch_ptr[device]) {
+            void *p = nullptr;
+            const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+            if (e != hipSuccess || !p) return fail(AM_EHIP, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(e));
+            g_scratch_ptr[device] = static_cast<uint32_t *>(p);
+        }
+        *out = g_scratch_ptr[device];
+    } catch (...) {
+        return fail(AM_EHIP, "could not lock the static scratch table");
     }
-    *out = g_scratch_ptr[device];
     return AM_OK;
-}
-
-struct Layout {
-    uint32_t ntiles, nsb, slots;
-    uint64_t cap_lines;
-    uint64_t off_flags, off_reduce, off_next, off_meta, meta_stride, meta_sb_off, off_ring, ring_stride, total;
-};
-
-// workspace = [flags 256 B][reduction partials 32 x 1024 doubles][next_lines u32[ntiles]][meta x (slots + 1)][ring values x slots]
-//   meta    = local_off u32[ntiles] | sb_base u32[nsb + 1]         (the extra one serves am_subset_indices)
-//   ring    = R * cap_lines * 32 fp32: [replica][line][32]; a tile owns whole lines
-Layout make_layout(const am_config &c)
-{
-    Layout L{};
-    L.ntiles = (uint32_t)((c.n + am::kTileCoords - 1) / am::kTileCoords);
-    L.nsb = (L.ntiles + am::kTilesPerSuperblock - 1) / am::kTilesPerSuperblock;
-    L.slots = c.delay + 1;
-    L.cap_lines = slot_capacity_lines(L.ntiles, c.fraction, c.subset_granule == 32,
-                                      c.subset_kind == AM_SUBSET_STRATIFIED ? stratified_block(c.fraction) : 0);
-    L.off_flags = 0;
-    L.off_reduce = 256;
-    L.off_next = L.off_reduce + (uint64_t)AM_MAX_REPLICAS * 1024 * 8;
-    L.off_meta = L.off_next + round_up((uint64_t)L.ntiles * 4, 256);
-    L.meta_sb_off = round_up((uint64_t)L.ntiles * 4, 256);
-    L.meta_stride = L.meta_sb_off + round_up(((uint64_t)L.nsb + 1) * 4, 256);
-    L.off_ring = L.off_meta + L.meta_stride * (L.slots + 1);
-    L.ring_stride = round_up(L.cap_lines * am::kLineFloats * c.replicas * 4, 256);
-    L.total = L.off_ring + L.ring_stride * L.slots;
-    return L;
 }
 
 am_status check_config(const am_config *c)
@@ -160,7 +95,8 @@ am_status check_config(const am_config *c)
     if (c->subset_granule != 0 && c->subset_granule != 1 && c->subset_granule != 32) return fail(AM_EINVAL, "subset_granule=%u is not 1 or 32", c->subset_granule);
     if (c->subset_kind > AM_SUBSET_STRATIFIED) return fail(AM_EINVAL, "unknown subset_kind %u", c->subset_kind);
     if (c->subset_kind == AM_SUBSET_STRATIFIED && c->subset_granule == 32) return fail(AM_EINVAL, "the stratified subset has no line-granular form (subset_granule must be 1)");
-    if (c->subset_kind == AM_SUBSET_STRATIFIED && stratified_block(c->fraction) > (1ull << 31)) return fail(AM_EINVAL, "fraction=%g gives a block longer than 2^31", c->fraction);
+    if (c->subset_kind == AM_SUBSET_STRATIFIED && am_host::stratified_block(c->fraction) > (1ull << 31)) return fail(AM_EINVAL, "fraction=%g gives a block longer than 2^31", c->fraction);
+    if (c->d_layout > AM_D_INTERLEAVED) return fail(AM_EINVAL, "unknown d_layout %u", c->d_layout);
     if (!(c->beta1 >= 0.f && c->beta1 < 1.f)) return fail(AM_EINVAL, "beta1=%g not in [0, 1)", c->beta1);
     if (c->optimizer != AM_OPT_SGD && !(c->beta2 >= 0.f && c->beta2 < 1.f)) return fail(AM_EINVAL, "beta2=%g not in [0, 1)", c->beta2);
     if (c->optimizer != AM_OPT_SGD && !(c->eps >= 0.f)) return fail(AM_EINVAL, "eps=%g negative", c->eps);
@@ -170,28 +106,34 @@ am_status check_config(const am_config *c)
 
 }  // namespace
 
+constexpr uint32_t kMaxProfiledLaunches = 4096;
+
 struct am_state {
     am_config cfg;
     Layout lay;
     hipStream_t stream;
     int device;
     uint32_t grid_sparse;
-    float *w[AM_MAX_REPLICAS], *m[AM_MAX_REPLICAS], *v[AM_MAX_REPLICAS], *d[AM_MAX_REPLICAS];
+    float *w[AM_MAX_REPLICAS], *m[AM_MAX_REPLICAS], *v[AM_MAX_REPLICAS];
+    float *d[AM_MAX_REPLICAS];   // per replica, or (interleaved layout) per block
+    uint32_t d_arrays, d_rb;     // how many entries of d are in use; replicas per array (1 = per replica)
+    uint64_t d_floats;           // floats per array of d
     void *fwd[AM_MAX_REPLICAS];
     bool has_fwd;
     char *ws;
     uint64_t last_t;
     uint64_t next_lines_step;    // the step whose send subset next_lines() was sized for (0 = none)
     uint32_t delay_now;          // the delay in force (<= cfg.delay, which sizes the ring)
+    bool overflow_seen;          // am_read_flags has reported a subset that did not fit its ring slot
     // per replica, because replicas of unequal speed make unequal numbers of local steps:
     uint64_t opt_steps[AM_MAX_REPLICAS];     // optimizer steps made so far (the t of the bias corrections)
     double mu_product[AM_MAX_REPLICAS];      // NAdam: running product of the momentum schedule
     uint64_t threshold;
     uint32_t *static_scratch;    // this device's copy of the static scratch array (am_subset_indices_static)
-    // profiling of the fused kernel
+    // profiling of the fused kernel: a fixed pool of event pairs, created on first use
     bool profiling;
-    std::vector<hipEvent_t> ev_pool;
-    size_t ev_used;
+    hipEvent_t ev_pool[2 * kMaxProfiledLaunches];
+    uint32_t ev_created, ev_used;
 
     uint32_t *flags() const { return reinterpret_cast<uint32_t *>(ws + lay.off_flags); }
     double *reduce_partials() const { return reinterpret_cast<double *>(ws + lay.off_reduce); }
@@ -213,26 +155,25 @@ am::SubsetKey make_key(const am_state *st, uint64_t step)
     k.threshold = st->threshold;
     k.mode = st->cfg.subset_kind == AM_SUBSET_STRATIFIED ? am::kDrawStratified
            : st->cfg.subset_granule == 32 ? am::kDrawLine : am::kDrawCoordinate;
-    k.block = st->cfg.subset_kind == AM_SUBSET_STRATIFIED ? (uint32_t)stratified_block(st->cfg.fraction) : 0u;
+    k.block = st->cfg.subset_kind == AM_SUBSET_STRATIFIED ? (uint32_t)am_host::stratified_block(st->cfg.fraction) : 0u;
     return k;
 }
 
-// count + scan of S^step into the metadata block `slot`; for_ring: sizes in whole lines per tile and
-// checked against the slot capacity, else sizes in coordinates
-am_status launch_subset_offsets(am_state *st, uint64_t step, uint32_t slot, uint64_t *dev_count, bool for_ring)
+// Offsets of S^step in ring slot `slot`: per tile, the lines it owns and where they start in its
+// superblock; per superblock, where it starts in the slot.
+am_status launch_ring_offsets(am_state *st, uint64_t step, uint32_t slot)
 {
     const Layout &L = st->lay;
-    if (for_ring && st->next_lines_step == step && step != 0) {
+    if (st->next_lines_step == step && step != 0) {
         // the previous fused step already sized this subset's tiles
         am::k_subset_offsets<<<L.nsb, 256, 0, st->stream>>>(st->next_lines(), L.ntiles, st->meta_local(slot), st->meta_sb(slot));
     } else {
-        am::k_subset_count<<<L.nsb, 256, 0, st->stream>>>(make_key(st, step), st->cfg.n, L.ntiles,
-                                                          for_ring ? am::kLineFloats : 1u,
+        am::k_subset_count<<<L.nsb, 256, 0, st->stream>>>(make_key(st, step), st->cfg.n, L.ntiles, L.blocks.rb, am::kLineFloats, 1u,
                                                           st->meta_local(slot), st->meta_sb(slot));
     }
     AM_HIP(hipGetLastError());
-    am::k_subset_scan<<<1, 256, 0, st->stream>>>(st->meta_sb(slot), L.nsb, (uint32_t)L.cap_lines,
-                                                 for_ring ? st->flags() : nullptr, dev_count);
+    const uint32_t cap = L.cap_lines > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)L.cap_lines;
+    am::k_subset_scan<<<1, 256, 0, st->stream>>>(st->meta_sb(slot), L.nsb, cap, st->flags(), nullptr);
     AM_HIP(hipGetLastError());
     return AM_OK;
 }
@@ -253,7 +194,7 @@ am_status launch_index_list(am_state *st, uint64_t t, uint32_t *local_off, uint3
                             uint64_t *dev_out, uint64_t capacity, uint64_t *dev_count)
 {
     const Layout &L = st->lay;
-    am::k_subset_count<<<L.nsb, 256, 0, st->stream>>>(make_key(st, t), st->cfg.n, L.ntiles, 1u, local_off, sb_base);
+    am::k_subset_count<<<L.nsb, 256, 0, st->stream>>>(make_key(st, t), st->cfg.n, L.ntiles, 1u, 1u, 0u, local_off, sb_base);
     AM_HIP(hipGetLastError());
     am::k_subset_scan<<<1, 256, 0, st->stream>>>(sb_base, L.nsb, 0u, nullptr, dev_count);
     AM_HIP(hipGetLastError());
@@ -264,42 +205,40 @@ am_status launch_index_list(am_state *st, uint64_t t, uint32_t *local_off, uint3
     return AM_OK;
 }
 
-struct Round {
-    bool send, recv, same_slot;
-    uint32_t slot_send, slot_recv;
-    uint64_t step_recv;
-};
-
 Round plan_round(const am_state *st, uint64_t t)
 {
-    Round r{};
-    const uint64_t K = st->cfg.avg_interval, depth = (uint64_t)st->cfg.delay + 1, tau = st->delay_now;
-    if (t % K != 0) return r;
-    const uint64_t round = t / K;
-    r.send = true;
-    r.slot_send = (uint32_t)(round % depth);
-    if (t >= tau * K + 1) {                       // s = t - tau K >= 1: something was sent that long ago
-        r.recv = true;
-        r.step_recv = t - tau * K;
-        r.slot_recv = (uint32_t)((round - tau) % depth);
-        r.same_slot = tau == 0;
-    }
-    return r;
+    return am_host::plan_round(st->cfg.avg_interval, (uint64_t)st->cfg.delay + 1, st->delay_now, t);
+}
+
+// One workgroup per (tile, block of replicas), one wave per replica of the block; when the average
+// is of this very step's values (tau = 0) a workgroup walks all the blocks of its tile, because it
+// needs every replica's new weights.
+template <int OPT, bool GBF, int FWD, bool DIL>
+am_status launch_step_tau(am_state *st, const am::StepArgs &a)
+{
+    const am_host::Blocks &B = st->lay.blocks;
+    const bool tau0 = a.do_recv && a.same_slot;
+    const dim3 grid(st->lay.ntiles * (tau0 ? 1u : B.nblocks)), block(64u * B.rb);
+    const size_t lds = (size_t)am::step_lds_floats(B.rb, B.nblocks, DIL) * sizeof(float);
+    if (tau0) am::k_step<OPT, GBF, FWD, DIL, true><<<grid, block, lds, st->stream>>>(a);
+    else am::k_step<OPT, GBF, FWD, DIL, false><<<grid, block, lds, st->stream>>>(a);
+    AM_HIP(hipGetLastError());
+    return AM_OK;
+}
+
+template <int OPT, bool GBF, int FWD>
+am_status launch_step_layout(am_state *st, const am::StepArgs &a)
+{
+    if (st->cfg.d_layout == AM_D_INTERLEAVED && a.ema) return launch_step_tau<OPT, GBF, FWD, true>(st, a);
+    return launch_step_tau<OPT, GBF, FWD, false>(st, a);
 }
 
 template <int OPT, bool GBF>
 am_status launch_step_fwd(am_state *st, const am::StepArgs &a)
 {
-    // one workgroup per tile, one wave per replica (at most 8 waves, so that several workgroups fit
-    // a compute unit; with more replicas the waves take turns)
-    const uint32_t waves = st->cfg.replicas < 8u ? st->cfg.replicas : 8u;
-    const dim3 grid(st->lay.ntiles), block(64u * waves);
-    const size_t lds = (size_t)(st->cfg.replicas + waves) * am::kTileCoords * sizeof(float);
-    if (!st->has_fwd) am::k_step<OPT, GBF, am::kFwdNone><<<grid, block, lds, st->stream>>>(a);
-    else if (st->cfg.fwd_dtype == AM_F32) am::k_step<OPT, GBF, am::kFwdF32><<<grid, block, lds, st->stream>>>(a);
-    else am::k_step<OPT, GBF, am::kFwdBf16><<<grid, block, lds, st->stream>>>(a);
-    AM_HIP(hipGetLastError());
-    return AM_OK;
+    if (!st->has_fwd) return launch_step_layout<OPT, GBF, am::kFwdNone>(st, a);
+    if (st->cfg.fwd_dtype == AM_F32) return launch_step_layout<OPT, GBF, am::kFwdF32>(st, a);
+    return launch_step_layout<OPT, GBF, am::kFwdBf16>(st, a);
 }
 
 template <int OPT>
@@ -312,24 +251,29 @@ am_status launch_step_grad(am_state *st, const am::StepArgs &a)
 am_status fill_averaging(am_state *st, uint64_t t, float lambda_t, const Round &r, am::StepArgs &a)
 {
     const am_config &c = st->cfg;
+    const am_host::Blocks &B = st->lay.blocks;
     a.n = c.n; a.ntiles = st->lay.ntiles; a.replicas = c.replicas;
-    a.cap_lines = (uint32_t)st->lay.cap_lines;
+    a.rb = B.rb; a.rb_shift = B.rb_shift; a.nblocks = B.nblocks;
+    a.blocks_per_wg = (r.recv && r.same_slot) ? B.nblocks : 1u;
+    a.cap_lines = st->lay.cap_lines > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)st->lay.cap_lines;
     a.ema = c.correction != AM_CORR_NONE;
     a.msg_dtype = c.msg_dtype;
     if (c.correction == AM_CORR_EAGER) { a.coef_d = 0.0; a.coef_s = 1.0 / (double)c.replicas; }
     else { a.coef_d = 1.0 - (double)lambda_t; a.coef_s = (double)lambda_t; }
     a.do_send = r.send; a.do_recv = r.recv; a.same_slot = r.same_slot;
+    a.key = make_key(st, 0);
+    for (uint32_t k = 0; k < st->d_arrays; ++k) a.d[k] = st->d[k];
     if (r.send) {
-        if (am_status s = launch_subset_offsets(st, t, r.slot_send, nullptr, true)) return s;
-        a.key_send = make_key(st, t);
+        if (am_status s = launch_ring_offsets(st, t, r.slot_send)) return s;
+        a.step_lo[1] = (uint32_t)t; a.step_hi[1] = (uint32_t)(t >> 32);
         a.ring_send = st->ring(r.slot_send);
-        a.send_local_off = st->meta_local(r.slot_send);
+        a.send_meta = st->meta_local(r.slot_send);
         a.send_sb_base = st->meta_sb(r.slot_send);
     }
     if (r.recv) {
-        a.key_recv = make_key(st, r.step_recv);
+        a.step_lo[0] = (uint32_t)r.step_recv; a.step_hi[0] = (uint32_t)(r.step_recv >> 32);
         a.ring_recv = st->ring(r.slot_recv);
-        a.recv_local_off = st->meta_local(r.slot_recv);
+        a.recv_meta = st->meta_local(r.slot_recv);
         a.recv_sb_base = st->meta_sb(r.slot_recv);
     }
     return AM_OK;
@@ -339,14 +283,27 @@ am_status fill_averaging(am_state *st, uint64_t t, float lambda_t, const Round &
 
 extern "C" {
 
-const char *am_last_error(void) { return g_last_error.c_str(); }
-const char *am_version(void) { return "asyncmesh-gfx950 0.1"; }
+const char *am_last_error(void) { return g_last_error; }
+const char *am_version(void) { return "asyncmesh-gfx950 0.2 src:" AM_SOURCE_HASH; }
 
 am_status am_workspace_bytes(const am_config *cfg, uint64_t *out_bytes)
 {
     if (am_status s = check_config(cfg)) return s;
     if (!out_bytes) return fail(AM_EINVAL, "out_bytes is NULL");
-    *out_bytes = make_layout(*cfg).total;
+    *out_bytes = am_host::make_layout(*cfg).total;
+    return AM_OK;
+}
+
+am_status am_d_layout_info(const am_config *cfg, uint32_t *out_replicas_per_block, uint32_t *out_arrays,
+                           uint64_t *out_floats_per_array)
+{
+    if (am_status s = check_config(cfg)) return s;
+    uint32_t rb, arrays;
+    uint64_t floats;
+    am_host::d_layout_shape(*cfg, &rb, &arrays, &floats);
+    if (out_replicas_per_block) *out_replicas_per_block = rb;
+    if (out_arrays) *out_arrays = arrays;
+    if (out_floats_per_array) *out_floats_per_array = floats;
     return AM_OK;
 }
 
@@ -354,15 +311,15 @@ am_status am_workspace_bytes(const am_config *cfg, uint64_t *out_bytes)
 
 namespace {
 
-constexpr uint64_t kSnapshotMagic = 0x414D534E41503032ull;     // "AMSNAP02"
+constexpr uint64_t kSnapshotMagic = 0x414D534E41503033ull;     // "AMSNAP03"
 
-// digest (FNV-1a) of the config fields that shape the ring and the subsets
+// digest (FNV-1a) of the config fields that shape the ring, the subsets and the caller's arrays
 uint64_t config_digest(const am_config &c)
 {
     uint64_t fraction_bits;
     std::memcpy(&fraction_bits, &c.fraction, sizeof fraction_bits);
     const uint64_t words[] = { c.n, c.replicas, c.delay, c.avg_interval, c.optimizer, fraction_bits, c.seed,
-                               c.subset_granule == 32 ? 32u : 1u, c.subset_kind };
+                               c.subset_granule == 32 ? 32u : 1u, c.subset_kind, c.d_layout, c.ring_cap_lines };
     uint64_t h = 0xCBF29CE484222325ull;
     for (uint64_t w : words)
         for (int b = 0; b < 8; ++b) { h ^= (w >> (8 * b)) & 0xFFu; h *= 0x100000001B3ull; }
@@ -390,10 +347,18 @@ am_status create_state(const am_config *cfg, const am_buffers *buf, void *hip_st
         if (!aligned(buf->w[i], 16)) return fail(AM_EALIGN, "w[%u] is not 16-byte aligned", i);
         if (need_m) { if (!buf->m[i]) return fail(AM_EINVAL, "m[%u] is NULL", i); if (!aligned(buf->m[i], 16)) return fail(AM_EALIGN, "m[%u] is not 16-byte aligned", i); }
         if (need_v) { if (!buf->v[i]) return fail(AM_EINVAL, "v[%u] is NULL", i); if (!aligned(buf->v[i], 16)) return fail(AM_EALIGN, "v[%u] is not 16-byte aligned", i); }
-        if (need_d) { if (!buf->d[i]) return fail(AM_EINVAL, "d[%u] is NULL", i); if (!aligned(buf->d[i], 16)) return fail(AM_EALIGN, "d[%u] is not 16-byte aligned", i); }
         if (buf->fwd) { if (!buf->fwd[i]) return fail(AM_EINVAL, "fwd[%u] is NULL", i); if (!aligned(buf->fwd[i], fwd_align)) return fail(AM_EALIGN, "fwd[%u] is not %u-byte aligned", i, (unsigned)fwd_align); }
     }
-    const Layout lay = make_layout(*cfg);
+    uint32_t d_rb = 1, d_arrays = 0;
+    uint64_t d_floats = 0;
+    if (need_d) {
+        am_host::d_layout_shape(*cfg, &d_rb, &d_arrays, &d_floats);
+        for (uint32_t k = 0; k < d_arrays; ++k) {
+            if (!buf->d[k]) return fail(AM_EINVAL, "d[%u] is NULL", k);
+            if (!aligned(buf->d[k], 16)) return fail(AM_EALIGN, "d[%u] is not 16-byte aligned", k);
+        }
+    }
+    const Layout lay = am_host::make_layout(*cfg);
     if (!buf->workspace) return fail(AM_EINVAL, "workspace is NULL");
     if (!aligned(buf->workspace, 256)) return fail(AM_EALIGN, "workspace is not 256-byte aligned");
     if (buf->workspace_bytes < lay.total)
@@ -409,15 +374,17 @@ am_status create_state(const am_config *cfg, const am_buffers *buf, void *hip_st
     st->last_t = 0;
     st->next_lines_step = 0;
     st->delay_now = cfg->delay;
+    st->overflow_seen = false;
     for (uint32_t i = 0; i < AM_MAX_REPLICAS; ++i) { st->opt_steps[i] = 0; st->mu_product[i] = 1.0; }
-    st->threshold = subset_threshold(cfg->fraction);
+    st->threshold = am_host::subset_threshold(cfg->fraction);
     st->profiling = false;
-    st->ev_used = 0;
+    st->ev_created = st->ev_used = 0;
+    st->d_arrays = d_arrays; st->d_rb = d_rb; st->d_floats = d_floats;
     for (uint32_t i = 0; i < AM_MAX_REPLICAS; ++i) {
         st->w[i] = i < R ? buf->w[i] : nullptr;
         st->m[i] = (i < R && need_m) ? buf->m[i] : nullptr;
         st->v[i] = (i < R && need_v) ? buf->v[i] : nullptr;
-        st->d[i] = (i < R && need_d) ? buf->d[i] : nullptr;
+        st->d[i] = i < d_arrays ? buf->d[i] : nullptr;
         st->fwd[i] = (i < R && buf->fwd) ? buf->fwd[i] : nullptr;
     }
 
@@ -443,7 +410,7 @@ am_status am_init_state(const am_config *cfg, const am_buffers *buf, void *hip_s
     am_state *st = nullptr;
     if (am_status s = create_state(cfg, buf, hip_stream, &st)) return s;
     const uint32_t R = cfg->replicas;
-    const bool need_m = st->m[0] != nullptr, need_v = st->v[0] != nullptr, need_d = st->d[0] != nullptr;
+    const bool need_m = st->m[0] != nullptr, need_v = st->v[0] != nullptr;
     const Layout &lay = st->lay;
     hipError_t e = hipSuccess;
 
@@ -452,8 +419,9 @@ am_status am_init_state(const am_config *cfg, const am_buffers *buf, void *hip_s
     for (uint32_t i = 0; i < R && e == hipSuccess; ++i) {
         if (need_m) e = hipMemsetAsync(st->m[i], 0, bytes, st->stream);
         if (need_v && e == hipSuccess) e = hipMemsetAsync(st->v[i], 0, bytes, st->stream);
-        if (need_d && e == hipSuccess) e = hipMemsetAsync(st->d[i], 0, bytes, st->stream);
     }
+    for (uint32_t k = 0; k < st->d_arrays && e == hipSuccess; ++k)
+        e = hipMemsetAsync(st->d[k], 0, (size_t)st->d_floats * sizeof(float), st->stream);
     if (e == hipSuccess) e = hipMemsetAsync(st->ws, 0, lay.total, st->stream);
     if (e != hipSuccess) { delete st; return fail(AM_EHIP, "hipMemsetAsync: %s", hipGetErrorString(e)); }
     *out = st;
@@ -479,7 +447,7 @@ am_status am_resume_state(const am_config *cfg, const am_buffers *buf, void *hip
     if (am_status s = check_config(cfg)) return s;
     if (!snapshot) return fail(AM_EINVAL, "snapshot is NULL");
     if (snapshot->magic != kSnapshotMagic) return fail(AM_EINVAL, "snapshot has an unknown layout (magic %016llx)", (unsigned long long)snapshot->magic);
-    if (snapshot->config_digest != config_digest(*cfg)) return fail(AM_EINVAL, "snapshot was exported under a different config (n, replicas, delay, avg_interval, optimizer, fraction, seed or subset rule differ)");
+    if (snapshot->config_digest != config_digest(*cfg)) return fail(AM_EINVAL, "snapshot was exported under a different config (n, replicas, delay, avg_interval, optimizer, fraction, seed, subset rule, d_layout or ring_cap_lines differ)");
     if (snapshot->delay_now > cfg->delay) return fail(AM_EINVAL, "snapshot delay %u exceeds the configured delay %u", snapshot->delay_now, cfg->delay);
     for (uint32_t i = 0; i < AM_MAX_REPLICAS; ++i)
         if (!(snapshot->mu_product[i] >= 0.0 && snapshot->mu_product[i] <= 1.0)) return fail(AM_EINVAL, "snapshot mu_product[%u]=%g not in [0, 1]", i, snapshot->mu_product[i]);
@@ -531,6 +499,7 @@ am_status step_impl(am_state *st, uint64_t t, const void *const *grads, float lr
                     float grad_scale, const float *dev_replica_scale, const uint32_t *active)
 {
     if (!st) return fail(AM_EINVAL, "state is NULL");
+    if (st->overflow_seen) return fail(AM_EOVERFLOW, "a subset did not fit its ring slot (reported by am_read_flags): the state no longer follows the method");
     if (!aligned(dev_replica_scale, 4)) return fail(AM_EALIGN, "dev_replica_scale is not 4-byte aligned");
     if (!grads) return fail(AM_EINVAL, "grads is NULL");
     if (t != st->last_t + 1) return fail(AM_EORDER, "step %llu after step %llu", (unsigned long long)t, (unsigned long long)st->last_t);
@@ -547,11 +516,23 @@ am_status step_impl(am_state *st, uint64_t t, const void *const *grads, float lr
         if (!aligned(grads[i], galign)) return fail(AM_EALIGN, "grads[%u] is not %u-byte aligned", i, (unsigned)galign);
     }
 
+    // the two events that bracket the kernel exist before anything is enqueued
+    hipEvent_t ev0 = nullptr, ev1 = nullptr;
+    const bool timed = st->profiling && st->ev_used + 2 <= 2 * kMaxProfiledLaunches;
+    if (timed) {
+        while (st->ev_created < st->ev_used + 2) {
+            AM_HIP(hipEventCreate(&st->ev_pool[st->ev_created]));
+            ++st->ev_created;
+        }
+        ev0 = st->ev_pool[st->ev_used];
+        ev1 = st->ev_pool[st->ev_used + 1];
+    }
+
     am::StepArgs a;
     std::memset(&a, 0, sizeof a);
     for (uint32_t i = 0; i < c.replicas; ++i) {
-        a.w[i] = st->w[i]; a.m[i] = st->m[i]; a.v[i] = st->v[i]; a.d[i] = st->d[i];
-        a.fwd[i] = st->fwd[i]; a.g[i] = grads[i];
+        a.rep[i].w = st->w[i]; a.rep[i].m = st->m[i]; a.rep[i].v = st->v[i];
+        a.rep[i].fwd = st->fwd[i]; a.rep[i].g = grads[i];
     }
     a.lookahead = c.lookahead != 0; a.gamma = (double)c.gamma;
     a.replica_scale = dev_replica_scale;
@@ -577,19 +558,19 @@ am_status step_impl(am_state *st, uint64_t t, const void *const *grads, float lr
         const uint64_t k = active ? st->opt_steps[i] + 1 : t;
         steps_next[i] = k;
         if (c.optimizer == AM_OPT_SGD) {
-            a.c_m[i] = lrd; a.c_g[i] = lrd * gs;
+            a.rep[i].c_m = lrd; a.rep[i].c_g = lrd * gs;
             continue;
         }
         const double bc1 = 1.0 - std::pow(b1, (double)k), bc2 = 1.0 - std::pow(b2, (double)k);
-        a.c_v[i] = 1.0 / std::sqrt(bc2);
+        a.rep[i].c_v = 1.0 / std::sqrt(bc2);
         if (c.optimizer == AM_OPT_ADAMW) {
-            a.c_g[i] = 0.0; a.c_m[i] = lrd / bc1;
+            a.rep[i].c_g = 0.0; a.rep[i].c_m = lrd / bc1;
         } else {
             const double mu_t = b1 * (1.0 - 0.5 * std::pow(0.96, (double)k * c.momentum_decay));
             const double mu_t1 = b1 * (1.0 - 0.5 * std::pow(0.96, (double)(k + 1) * c.momentum_decay));
             mu_prod_next[i] = st->mu_product[i] * mu_t;
-            a.c_g[i] = lrd * (1.0 - mu_t) / (1.0 - mu_prod_next[i]) * gs;
-            a.c_m[i] = lrd * mu_t1 / (1.0 - mu_prod_next[i] * mu_t1);
+            a.rep[i].c_g = lrd * (1.0 - mu_t) / (1.0 - mu_prod_next[i]) * gs;
+            a.rep[i].c_m = lrd * mu_t1 / (1.0 - mu_prod_next[i] * mu_t1);
         }
     }
 
@@ -599,26 +580,16 @@ am_status step_impl(am_state *st, uint64_t t, const void *const *grads, float lr
     const bool do_next = (t + 1) % c.avg_interval == 0;      // the next step sends: size its tiles on the way
     a.do_next = do_next;
     if (do_next) {
-        a.key_next = make_key(st, t + 1);
+        a.step_lo[2] = (uint32_t)(t + 1); a.step_hi[2] = (uint32_t)((t + 1) >> 32);
         a.next_lines = st->next_lines();
     }
 
-    hipEvent_t ev0 = nullptr, ev1 = nullptr;
-    if (st->profiling) {
-        while (st->ev_pool.size() < st->ev_used + 2) {
-            hipEvent_t e;
-            AM_HIP(hipEventCreate(&e));
-            st->ev_pool.push_back(e);
-        }
-        ev0 = st->ev_pool[st->ev_used];
-        ev1 = st->ev_pool[st->ev_used + 1];
-        AM_HIP(hipEventRecord(ev0, st->stream));
-    }
+    if (timed) AM_HIP(hipEventRecord(ev0, st->stream));
     am_status s;
     if (c.optimizer == AM_OPT_SGD) s = c.beta1 == 0.f ? launch_step_grad<am::kOptSgdPlain>(st, a) : launch_step_grad<am::kOptSgdMomentum>(st, a);
     else s = launch_step_grad<am::kOptAdam>(st, a);
     if (s) return s;
-    if (st->profiling) {
+    if (timed) {
         AM_HIP(hipEventRecord(ev1, st->stream));
         st->ev_used += 2;
     }
@@ -647,6 +618,7 @@ am_status am_step_masked(am_state *st, uint64_t t, const void *const *grads, flo
 am_status am_sparse_average(am_state *st, uint64_t t, float lambda_t)
 {
     if (!st) return fail(AM_EINVAL, "state is NULL");
+    if (st->overflow_seen) return fail(AM_EOVERFLOW, "a subset did not fit its ring slot (reported by am_read_flags): the state no longer follows the method");
     if (t != st->last_t + 1) return fail(AM_EORDER, "step %llu after step %llu", (unsigned long long)t, (unsigned long long)st->last_t);
     if (!(lambda_t >= 0.f && lambda_t <= 1.f)) return fail(AM_EINVAL, "lambda_t=%g not in [0, 1]", lambda_t);
     const Round r = plan_round(st, t);
@@ -654,13 +626,9 @@ am_status am_sparse_average(am_state *st, uint64_t t, float lambda_t)
         // the fused kernel with the optimizer pass left out: w^ = w, only touched lines move
         am::StepArgs a;
         std::memset(&a, 0, sizeof a);
-        for (uint32_t i = 0; i < st->cfg.replicas; ++i) { a.w[i] = st->w[i]; a.d[i] = st->d[i]; }
+        for (uint32_t i = 0; i < st->cfg.replicas; ++i) a.rep[i].w = st->w[i];
         if (am_status s = fill_averaging(st, t, lambda_t, r, a)) return s;
-        // every wave hashes the tile's subsets itself and little memory moves per tile: two waves measured best
-        const uint32_t waves = st->cfg.replicas < 2u ? st->cfg.replicas : 2u;
-        const size_t lds = (size_t)(st->cfg.replicas + waves) * am::kTileCoords * sizeof(float);
-        am::k_step<am::kOptNone, false, am::kFwdNone><<<dim3(st->lay.ntiles), dim3(64u * waves), lds, st->stream>>>(a);
-        AM_HIP(hipGetLastError());
+        if (am_status s = launch_step_layout<am::kOptNone, false, am::kFwdNone>(st, a)) return s;
     }
     st->last_t = t;
     return AM_OK;
@@ -717,8 +685,13 @@ am_status am_diagnostics(am_state *st, double *dev_out3)
     if (!aligned(dev_out3, 8)) return fail(AM_EALIGN, "dev_out3 is not 8-byte aligned");
     am::DiagArgs a;
     std::memset(&a, 0, sizeof a);
-    for (uint32_t i = 0; i < st->cfg.replicas; ++i) { a.w[i] = st->w[i]; a.d[i] = st->d[i]; }
-    a.n = st->cfg.n; a.replicas = st->cfg.replicas; a.has_d = st->d[0] != nullptr;
+    a.has_d = st->d_arrays != 0;
+    a.d_stride = st->d_rb;
+    for (uint32_t i = 0; i < st->cfg.replicas; ++i) {
+        a.w[i] = st->w[i];
+        if (a.has_d) a.d[i] = st->d_rb == 1 ? st->d[i] : st->d[i / st->d_rb] + i % st->d_rb;
+    }
+    a.n = st->cfg.n; a.replicas = st->cfg.replicas;
     const uint64_t want = (st->cfg.n + 255) / 256;
     const uint32_t blocks = (uint32_t)(want < 1024 ? want : 1024);
     am::k_diag_partial<<<blocks, 256, 0, st->stream>>>(a, st->reduce_partials());
@@ -733,6 +706,7 @@ am_status am_read_flags(am_state *st, uint32_t *out_flags)
     if (!st || !out_flags) return fail(AM_EINVAL, "NULL argument");
     AM_HIP(hipMemcpyAsync(out_flags, st->flags(), sizeof(uint32_t), hipMemcpyDeviceToHost, st->stream));
     AM_HIP(hipStreamSynchronize(st->stream));
+    if (*out_flags & 1u) st->overflow_seen = true;
     return AM_OK;
 }
 
@@ -744,12 +718,26 @@ am_status am_set_profiling(am_state *st, int on)
     return AM_OK;
 }
 
+am_status am_get_profile_times(am_state *st, float *out_ms, uint64_t capacity, uint64_t *out_launches)
+{
+    if (!st || !out_launches || (!out_ms && capacity)) return fail(AM_EINVAL, "NULL argument");
+    AM_HIP(hipStreamSynchronize(st->stream));
+    for (uint32_t k = 0; k + 1 < st->ev_used; k += 2) {
+        float ms = 0.f;
+        AM_HIP(hipEventElapsedTime(&ms, st->ev_pool[k], st->ev_pool[k + 1]));
+        if (k / 2 < capacity) out_ms[k / 2] = ms;
+    }
+    *out_launches = st->ev_used / 2;
+    st->ev_used = 0;
+    return AM_OK;
+}
+
 am_status am_get_profile(am_state *st, double *out_kernel_ms, uint64_t *out_launches)
 {
     if (!st || !out_kernel_ms || !out_launches) return fail(AM_EINVAL, "NULL argument");
     AM_HIP(hipStreamSynchronize(st->stream));
     double total = 0.0;
-    for (size_t k = 0; k + 1 < st->ev_used; k += 2) {
+    for (uint32_t k = 0; k + 1 < st->ev_used; k += 2) {
         float ms = 0.f;
         AM_HIP(hipEventElapsedTime(&ms, st->ev_pool[k], st->ev_pool[k + 1]));
         total += ms;
@@ -771,7 +759,7 @@ am_status am_ring_info(const am_state *st, uint64_t *out_capacity, uint32_t *out
 am_status am_destroy(am_state *st)
 {
     if (!st) return AM_OK;
-    for (hipEvent_t e : st->ev_pool) (void)hipEventDestroy(e);
+    for (uint32_t k = 0; k < st->ev_created; ++k) (void)hipEventDestroy(st->ev_pool[k]);
     delete st;
     return AM_OK;
 }

@@ -44,5 +44,6 @@ def bf16_bits_to_f32(h: np.ndarray) -> np.ndarray:
 def tiled(pool: np.ndarray, n: int, offset: int = 0) -> np.ndarray:
     """n values read cyclically from pool starting at offset (how the large benchmark tensors are
     filled from a small host-generated pool)."""
-    idx = (np.arange(n, dtype=np.int64) + offset) % pool.size
-    return pool[idx]
+    start = offset % pool.size
+    reps = (start + n + pool.size - 1) // pool.size
+    return np.tile(pool, reps)[start:start + n].copy()

@@ -19,9 +19,11 @@ def golden_dir():
 
 @pytest.fixture(scope="session")
 def amlib():
-    """The built C-ABI library through its binding; built here only when nothing has been built yet."""
-    from paper_2601_22442_amd.build import LIB, build_library
+    """The built C-ABI library through its binding.  Built here only when nothing has been built yet;
+    a library that does not carry the digest of the source files beside it is refused, not rebuilt."""
+    from paper_2601_22442_amd.build import LIB, build_library, check_library_is_current
     if not LIB.exists():
         build_library(force=True)
     import paper_2601_22442_amd as am
+    check_library_is_current(am.version())
     return am

@@ -14,6 +14,12 @@ TOL_F32 = 1e-6
 TOL_BF16 = 1e-2
 EMPTY_P = 1e-12
 
+# memory layout of the EMA vectors: one array per replica, or replicas interleaved per coordinate;
+# tests that do not name one run with the interleaved layout (the benchmark's)
+PER_REPLICA, INTERLEAVED = 0, 1
+both_layouts = pytest.mark.parametrize("d_layout", [pytest.param(PER_REPLICA, id="d_per_replica"),
+                                                    pytest.param(INTERLEAVED, id="d_interleaved")])
+
 
 def rel_err(got: np.ndarray, ref: np.ndarray) -> float:
     got = got.astype(np.float64); ref = ref.astype(np.float64)
@@ -30,8 +36,10 @@ def make_pair(am, n, R, w0=None, fwd_bf16=False, grad_bf16=False, force_fwd=Fals
     configuration fields that carry the same name (and the same enum values) on both sides."""
     if w0 is None:
         w0 = si.stage_weights(n, kw.get("seed", 0))
+    kw = dict(kw)
+    d_layout = kw.pop("d_layout", INTERLEAVED)          # a layout changes no value: the oracle has none
     cfg = am.make_config(n, R, fwd_dtype=am.BF16 if fwd_bf16 else am.F32,
-                         grad_dtype=am.BF16 if grad_bf16 else am.F32, **kw)
+                         grad_dtype=am.BF16 if grad_bf16 else am.F32, d_layout=d_layout, **kw)
     with_fwd = bool(kw.get("lookahead", False)) or fwd_bf16 or force_fwd
     st = am.init_state(cfg, torch.from_numpy(np.ascontiguousarray(w0)).cuda(), with_fwd=with_fwd)
     orc = O.Oracle(n, R, fwd_bf16=fwd_bf16, grad_bf16=grad_bf16, **kw)
@@ -62,11 +70,32 @@ def compare(st, orc, where=""):
             assert e < TOL_F32, f"{where} {name}[{i}] rel err {e:.3e}"
         if st.fwd is not None:
             bf = st.fwd[i].dtype == torch.bfloat16
-            e = rel_err(st.fwd[i].float().cpu().numpy(), orc.fwd(i))
+            got = st.fwd[i].float().cpu().numpy()
+            e = rel_err(got, orc.fwd(i))
             worst["fwd"] = max(worst.get("fwd", 0.0), e)
             assert e < (TOL_BF16 if bf else TOL_F32), f"{where} fwd[{i}] rel err {e:.3e}"
+            if bf:
+                fresh = not st.cfg.lookahead and not getattr(st, "fwd_is_stale", False)     # fwd = bf16(w) right after a fused step
+                check_bf16_rounded_once(got, orc.fwd(i), st.w[i].cpu().numpy() if fresh else None, f"{where} fwd[{i}]")
     assert st.read_flags() == 0
     return worst
+
+
+def check_bf16_rounded_once(got, ref, w_gpu, where):
+    """bf16 outputs are the ONE rounding of the fp64 value.  They can differ from the oracle's only
+    where the fp32 quantities behind them already differ in their last bit (the refined square root
+    and quotient are not correctly rounded), which moves a bf16 result with probability 2^-16 each:
+    so almost every element is bit-equal, no element is more than one bf16 step off, and without
+    look-ahead the output is exactly the bf16 rounding of the GPU's own fp32 weights."""
+    if got.size == 0:
+        return
+    diff = got != ref
+    assert diff.mean() <= 1e-3, f"{where}: {int(diff.sum())} of {got.size} bf16 values differ from the oracle's"
+    if diff.any():
+        step = np.abs(ref[diff]).astype(np.float64) * 2.0 ** -7      # at most one step of 8 significant bits
+        assert np.all(np.abs(got[diff].astype(np.float64) - ref[diff]) <= step), where
+    if w_gpu is not None:
+        assert np.array_equal(got, si.bf16_bits_to_f32(si.to_bf16_bits(w_gpu))), where
 
 
 def run_steps(am, n, R, steps, lr=3e-4, lam=0.5, grad_scale=1.0, check_every=1, **kw):
@@ -129,39 +158,56 @@ def test_subset_indices_beyond_2_to_30(amlib):
 # --------------------------------------------------------------------------------------------
 # fused step
 # --------------------------------------------------------------------------------------------
-def test_config_tiny(amlib):
+@both_layouts
+def test_config_tiny(amlib, d_layout):
     """1,048,576 fp32 params, R=4, staleness 1, 5 % per step, Adam-style state, 10 steps, seed 0."""
-    st, orc = run_steps(amlib, 1_048_576, 4, 10, delay=1, fraction=0.05, seed=0, optimizer=O.OPT_ADAMW)
+    st, orc = run_steps(amlib, 1_048_576, 4, 10, delay=1, fraction=0.05, seed=0, optimizer=O.OPT_ADAMW, d_layout=d_layout)
     assert any(np.any(orc.d(i)) for i in range(4))           # the EMA path did real work
 
 
 @pytest.mark.parametrize("n", [1, 2, 3, 4, 5, 255, 256, 257, 1023, 4099, 131_072 + 7, 3 * 131_072 + 1])
-def test_ragged_sizes(amlib, n):
-    run_steps(amlib, n, 3, 5, delay=1, fraction=0.3, seed=n, optimizer=O.OPT_ADAMW, lookahead=True, gamma=0.9)
+@both_layouts
+def test_ragged_sizes(amlib, n, d_layout):
+    run_steps(amlib, n, 3, 5, delay=1, fraction=0.3, seed=n, optimizer=O.OPT_ADAMW, lookahead=True, gamma=0.9, d_layout=d_layout)
 
 
-@pytest.mark.parametrize("R", [1, 2, 3, 5, 8, 16, 32])
-def test_replica_counts(amlib, R):
-    run_steps(amlib, 10_007, R, 6, delay=2, fraction=0.2, seed=R, optimizer=O.OPT_ADAMW)
+@both_layouts
+@pytest.mark.parametrize("R", [1, 2, 3, 4, 5, 7, 8, 9, 12, 16, 17, 24, 31, 32])
+def test_replica_counts(amlib, R, d_layout):
+    run_steps(amlib, 10_007, R, 6, delay=2, fraction=0.2, seed=R, optimizer=O.OPT_ADAMW, d_layout=d_layout)
+
+
+@both_layouts
+@pytest.mark.parametrize("R", [9, 16, 20, 32])
+def test_more_than_one_block_of_replicas_without_delay(amlib, R, d_layout):
+    """tau = 0 with more than 8 replicas: one workgroup walks all the blocks of its tile."""
+    run_steps(amlib, 20_011, R, 5, delay=0, fraction=0.2, seed=R, optimizer=O.OPT_ADAMW, lookahead=True, gamma=0.9,
+              d_layout=d_layout)
+    run_steps(amlib, 5_003, R, 4, delay=0, avg_interval=2, fraction=1.0, seed=R, optimizer=O.OPT_SGD, beta1=0.9,
+              d_layout=d_layout)
 
 
 @pytest.mark.parametrize("tau,K", [(0, 1), (0, 3), (1, 1), (1, 2), (3, 1), (2, 3), (7, 1)])
-def test_delay_and_interval(amlib, tau, K):
+@both_layouts
+def test_delay_and_interval(amlib, tau, K, d_layout):
     run_steps(amlib, 20_011, 4, 3 * (tau + 1) * K + 2, delay=tau, avg_interval=K, fraction=0.25, seed=5,
-              optimizer=O.OPT_ADAMW, lookahead=True, gamma=0.5)
+              optimizer=O.OPT_ADAMW, lookahead=True, gamma=0.5, d_layout=d_layout)
 
 
 @pytest.mark.parametrize("p", [EMPTY_P, 0.01, 0.05, 0.5, 1.0])
-def test_fractions(amlib, p):
-    run_steps(amlib, 50_021, 4, 6, delay=1, fraction=p, seed=3, optimizer=O.OPT_ADAMW)
+@both_layouts
+def test_fractions(amlib, p, d_layout):
+    run_steps(amlib, 50_021, 4, 6, delay=1, fraction=p, seed=3, optimizer=O.OPT_ADAMW, d_layout=d_layout)
+    run_steps(amlib, 50_021, 8, 4, delay=1, fraction=p, seed=4, optimizer=O.OPT_ADAMW, d_layout=d_layout)
 
 
 @pytest.mark.parametrize("opt,b1", [(O.OPT_SGD, 0.0), (O.OPT_SGD, 0.9), (O.OPT_ADAMW, 0.9), (O.OPT_ADAMW, 0.99),
                                     (O.OPT_NADAMW, 0.99)])
 @pytest.mark.parametrize("corr", [O.CORR_NONE, O.CORR_EMA])
-def test_optimizers_and_corrections(amlib, opt, b1, corr):
+@both_layouts
+def test_optimizers_and_corrections(amlib, opt, b1, corr, d_layout):
     run_steps(amlib, 30_011, 3, 8, lr=1e-3, delay=2, fraction=0.2, seed=11, optimizer=opt, beta1=b1,
-              correction=corr, lookahead=True, gamma=0.9, weight_decay=0.01)
+              correction=corr, lookahead=True, gamma=0.9, weight_decay=0.01, d_layout=d_layout)
 
 
 def test_block_granule_variant(amlib):
@@ -279,22 +325,25 @@ def test_lambda_and_grad_scale(amlib):
 
 @pytest.mark.parametrize("fwd_bf16,grad_bf16,look", [(True, True, True), (True, False, False), (False, True, True),
                                                      (False, False, False)])
-def test_dtypes(amlib, fwd_bf16, grad_bf16, look):
+@both_layouts
+def test_dtypes(amlib, fwd_bf16, grad_bf16, look, d_layout):
     run_steps(amlib, 40_009, 4, 6, delay=1, fraction=0.1, seed=8, fwd_bf16=fwd_bf16, grad_bf16=grad_bf16,
-              lookahead=look, gamma=0.9, force_fwd=True)
+              lookahead=look, gamma=0.9, force_fwd=True, d_layout=d_layout)
 
 
-def test_config_small_model_stage(amlib):
+@both_layouts
+def test_config_small_model_stage(amlib, d_layout):
     """12 d^2 = 7,077,888 params (d=768), R=4, staleness 2, 10 %, look-ahead on, 100 steps."""
     run_steps(amlib, 7_077_888, 4, 100, check_every=25, delay=2, fraction=0.10, seed=0,
-              optimizer=O.OPT_ADAMW, lookahead=True, gamma=0.9)
+              optimizer=O.OPT_ADAMW, lookahead=True, gamma=0.9, d_layout=d_layout)
 
 
-def test_config_bf16_stage_reduced(amlib):
+@both_layouts
+def test_config_bf16_stage_reduced(amlib, d_layout):
     """bf16 gradients and forward weights over fp32 masters, R=16, staleness 8, 1 % (the large
     configuration's settings on a stage the oracle finishes in seconds)."""
     run_steps(amlib, 1_000_003, 16, 12, check_every=4, delay=8, fraction=0.01, seed=0, fwd_bf16=True,
-              grad_bf16=True)
+              grad_bf16=True, d_layout=d_layout)
 
 
 def test_wide_dynamic_range(amlib):
@@ -349,28 +398,55 @@ def _tiled_dev(pool_dev, n, offset):
 
 
 def _full_size_case(am, n, R, tau, p, steps, windows, bf16=False, lookahead=True, seed=0, optimizer=O.OPT_ADAMW,
-                    beta1=0.9):
+                    beta1=0.9, d_layout=INTERLEAVED, whole_subset=False):
     """Run `steps` fused steps of a full-size stage in the launch shape the benchmark times and compare
     windows of it with oracle instances that evaluate just those coordinate ranges (exact: the
-    method is coordinate-wise given (seed, step, global coordinate))."""
+    method is coordinate-wise given (seed, step, global coordinate)).  windows = "all": consecutive
+    windows that cover every coordinate of the stage, replayed one after the other once the GPU is done."""
     pool_n = 1 << 20
     w_pool = si.stage_weights(pool_n, seed)
     cfg = am.make_config(n, R, delay=tau, fraction=p, seed=seed, lookahead=lookahead, gamma=0.9,
-                         optimizer=optimizer, beta1=beta1,
+                         optimizer=optimizer, beta1=beta1, d_layout=d_layout,
                          fwd_dtype=am.BF16 if bf16 else am.F32, grad_dtype=am.BF16 if bf16 else am.F32)
     st = am.init_state(cfg, _tiled_dev(torch.from_numpy(w_pool).cuda(), n, 0))
-    oracles = []
-    for lo, ln in windows:
+    sweep = windows == "all"
+    if sweep:
+        ln = 3_000_017                                   # not a multiple of the tile: window edges fall inside tiles
+        windows = [(lo, min(ln, n - lo)) for lo in range(0, n, ln)]
+
+    def make_oracle(lo, ln):
         orc = O.Oracle(ln, R, delay=tau, fraction=p, seed=seed, lookahead=lookahead, gamma=0.9, mu0=lo,
                        optimizer=optimizer, beta1=beta1, fwd_bf16=bf16, grad_bf16=bf16)
         orc.set_w(si.tiled(w_pool, ln, lo))
-        oracles.append(orc)
-    for t in range(1, steps + 1):
-        print(f"  full-size n={n} R={R} step {t}", flush=True)
+        return orc
+
+    def step_inputs(t):
         pools = si.replica_grads(pool_n, R, t, seed)
         if bf16:
             pools = [si.to_bf16_bits(x) for x in pools]
-        offs = [(7919 * (i + 1) * t) % pool_n for i in range(R)]
+        return pools, [(7919 * (i + 1) * t) % pool_n for i in range(R)]
+
+    def check_window(lo, ln, orc):
+        for i in range(R):
+            for name in ("w", "m", "v", "d", "fwd"):
+                if getattr(st, name) is None:
+                    continue
+                got = getattr(st, name)[i][lo:lo + ln].float().cpu().numpy()
+                ref = getattr(orc, name)(i)
+                e = rel_err(got, ref)
+                tol = TOL_BF16 if (bf16 and name == "fwd") else TOL_F32
+                assert e < tol, f"window {lo} {name}[{i}] rel err {e:.3e}"
+                if bf16 and name == "fwd":
+                    check_bf16_rounded_once(got, ref, None if lookahead else st.w[i][lo:lo + ln].cpu().numpy(),
+                                            f"window {lo} fwd[{i}]")
+
+    oracles = [] if sweep else [make_oracle(lo, ln) for lo, ln in windows]
+    inputs = {}
+    for t in range(1, steps + 1):
+        print(f"  full-size n={n} R={R} step {t}", flush=True)
+        pools, offs = step_inputs(t)
+        if sweep:
+            inputs[t] = (pools, offs)
         gd = []
         for i in range(R):
             dev = torch.from_numpy(pools[i].view(np.int16) if bf16 else pools[i]).cuda()
@@ -381,37 +457,53 @@ def _full_size_case(am, n, R, tau, p, steps, windows, bf16=False, lookahead=True
             orc.step(t, [si.tiled(pools[i], ln, lo + offs[i]) for i in range(R)], 3e-4, 0.5)
         torch.cuda.synchronize()
         del gd
-    for (lo, ln), orc in zip(windows, oracles):
-        for i in range(R):
-            for name in ("w", "m", "v", "d", "fwd"):
-                if getattr(st, name) is None:
-                    continue
-                got = getattr(st, name)[i][lo:lo + ln].float().cpu().numpy()
-                e = rel_err(got, getattr(orc, name)(i))
-                tol = TOL_BF16 if (bf16 and name == "fwd") else TOL_F32
-                assert e < tol, f"window {lo} {name}[{i}] rel err {e:.3e}"
-        assert any(np.any(orc.d(i)) for i in range(R))
     assert st.read_flags() == 0
-    # the whole-stage subset agrees with the oracle on the windows and with Binomial(n, p) overall
+    if sweep:
+        any_d = False
+        for k, (lo, ln) in enumerate(windows):
+            if k % 8 == 0:
+                print(f"  oracle window {k + 1} of {len(windows)}", flush=True)
+            orc = make_oracle(lo, ln)
+            for t in range(1, steps + 1):
+                pools, offs = inputs[t]
+                orc.step(t, [si.tiled(pools[i], ln, lo + offs[i]) for i in range(R)], 3e-4, 0.5)
+            check_window(lo, ln, orc)
+            any_d = any_d or any(np.any(orc.d(i)) for i in range(R))
+            orc.close()
+        assert any_d
+    else:
+        for (lo, ln), orc in zip(windows, oracles):
+            check_window(lo, ln, orc)
+            assert any(np.any(orc.d(i)) for i in range(R))
+    # the subset of one step: against the oracle's enumeration, whole or on the windows, and against Binomial(n, p)
     idx, k = st.subset_indices(3, capacity=int(n * p * 1.05) + 1000)
     got = idx.cpu().numpy().astype(np.uint64)
     assert abs(k - n * p) < 6 * (n * p * (1 - p)) ** 0.5
-    for lo, ln in windows:
-        assert np.array_equal(got[(got >= lo) & (got < lo + ln)], O.subset(seed, 3, ln, p, mu0=lo))
+    if whole_subset:
+        assert np.array_equal(got, O.subset(seed, 3, n, p))
+    else:
+        for lo, ln in windows[:: max(1, len(windows) // 4)]:
+            assert np.array_equal(got[(got >= lo) & (got < lo + ln)], O.subset(seed, 3, ln, p, mu0=lo))
 
 
-def test_full_size_stage_on_sampled_windows(amlib):
-    """125,829,120 fp32 params, R=8, staleness 4, 5 %: the benchmark's workload."""
+def test_full_size_stage_every_coordinate(amlib):
+    """125,829,120 fp32 params, R=8, staleness 4, 5 %: the benchmark's workload and layout, every
+    element of w, m, v, d, fwd of every replica against the oracle, and the whole index list of one subset."""
+    _full_size_case(amlib, 125_829_120, 8, 4, 0.05, 7, "all", whole_subset=True)
+
+
+def test_full_size_stage_on_sampled_windows_with_per_replica_d(amlib):
+    """The same workload with one EMA array per replica, on windows."""
     n = 125_829_120
     _full_size_case(amlib, n, 8, 4, 0.05, 7,
-                    [(0, 70_000), (131_072 * 211 - 3_000, 70_000), (62_914_560 - 5, 40_000), (n - 70_001, 70_001)])
+                    [(0, 70_000), (131_072 * 211 - 3_000, 70_000), (62_914_560 - 5, 40_000), (n - 70_001, 70_001)],
+                    d_layout=PER_REPLICA)
 
 
-def test_full_size_bf16_stage_on_sampled_windows(amlib):
-    """Same stage with bf16 gradients / forward weights over fp32 masters, R=16, staleness 8, 1 %."""
-    n = 125_829_120
-    _full_size_case(amlib, n, 16, 8, 0.01, 11, [(0, 50_000), (77_777_777, 50_000), (n - 50_001, 50_001)],
-                    bf16=True, lookahead=False)
+def test_full_size_bf16_stage_every_coordinate(amlib):
+    """Same stage with bf16 gradients / forward weights over fp32 masters, R=16, staleness 8, 1 %:
+    every element against the oracle."""
+    _full_size_case(amlib, 125_829_120, 16, 8, 0.01, 11, "all", bf16=True, lookahead=False)
 
 
 def test_full_size_1b_stage_on_sampled_windows(amlib):
@@ -442,12 +534,13 @@ def test_largest_stage_the_library_accepts(amlib):
     (10_007, 4, 2, 1, 0.05, O.CORR_EMA), (10_007, 5, 1, 2, 0.3, O.CORR_NONE), (131_072 + 9, 8, 3, 1, 0.05, O.CORR_EMA),
     (50_000, 16, 1, 1, 1.0, O.CORR_EMA), (50_000, 32, 2, 1, 0.01, O.CORR_EMA), (50_000, 7, 1, 1, EMPTY_P, O.CORR_EMA),
 ])
-def test_sparse_average_alone(amlib, n, R, tau, K, p, corr):
+@both_layouts
+def test_sparse_average_alone(amlib, n, R, tau, K, p, corr, d_layout):
     """The caller runs its own optimizer (here: adds a seeded perturbation to w between calls)."""
     am = amlib
     w0 = np.stack([si.stage_weights(n, 100 + i) for i in range(R)])
     st, orc = make_pair(am, n, R, w0=w0, delay=tau, avg_interval=K, fraction=p, seed=17, correction=corr,
-                        optimizer=O.OPT_SGD, beta1=0.0)
+                        optimizer=O.OPT_SGD, beta1=0.0, d_layout=d_layout)
     for t in range(1, 3 * (tau + 1) * K + 2):
         bump = si.replica_grads(n, R, t, 17)
         for i in range(R):
@@ -481,14 +574,36 @@ def test_fused_steps_and_stand_alone_averaging_interleaved(amlib):
 @pytest.mark.parametrize("n", [1, 5, 1000, 1_000_003])
 @pytest.mark.parametrize("bf16", [False, True])
 def test_lookahead_alone(amlib, n, bf16):
+    """The stateless look-ahead has no approximate step: its output is the oracle's bit for bit, in
+    fp32 and in bf16 (ONE rounding of the fp64 value)."""
     am = amlib
     w = si.stage_weights(n, 1); wp = si.stage_weights(n, 2)
     out = am.lookahead(torch.from_numpy(w).cuda(), torch.from_numpy(wp).cuda(), 0.9, am.BF16 if bf16 else am.F32)
     if bf16:
-        ref = si.bf16_bits_to_f32(O.lookahead(w, wp, O.f32(0.9), bf16=True))
-        assert rel_err(out.float().cpu().numpy(), ref) < TOL_BF16
+        got = out.view(torch.int16).cpu().numpy().view(np.uint16)
+        assert np.array_equal(got, O.lookahead(w, wp, O.f32(0.9), bf16=True))
     else:
-        assert rel_err(out.cpu().numpy(), O.lookahead(w, wp, O.f32(0.9))) < TOL_F32
+        assert np.array_equal(out.cpu().numpy(), O.lookahead(w, wp, O.f32(0.9)))
+
+
+def test_lookahead_alone_rounds_to_bf16_once(amlib):
+    """Values a hair above or below a bf16 tie, where rounding to fp32 first lands ON the tie and a
+    second rounding then goes the wrong way: w = a bf16 tie (9 significant bits), w_prev one fp32 step
+    away, gamma = 2^-10, so that w + gamma (w - w_prev) = tie +- 2^-10 fp32 steps."""
+    am = amlib
+    rng = np.random.default_rng(3)
+    k = rng.integers(128, 256, 20_000) * 2 + 1                       # odd 9-bit integers: halfway between two bf16 values
+    e = rng.integers(-20, 10, 20_000)
+    w = (k * 2.0 ** (e - 8.0)).astype(np.float32) * rng.choice([-1.0, 1.0], 20_000).astype(np.float32)
+    away = rng.choice([np.float32(np.inf), np.float32(-np.inf)], 20_000)
+    wp = np.nextafter(w, away).astype(np.float32)
+    g = 2.0 ** -10
+    out = am.lookahead(torch.from_numpy(w).cuda(), torch.from_numpy(wp).cuda(), g, am.BF16)
+    got = out.view(torch.int16).cpu().numpy().view(np.uint16)
+    want = O.lookahead(w, wp, g, bf16=True)
+    assert np.array_equal(got, want)
+    twice = si.to_bf16_bits((w.astype(np.float64) + g * (w.astype(np.float64) - wp.astype(np.float64))).astype(np.float32))
+    assert (twice != want).mean() > 0.2                                # rounding twice would have been caught
 
 
 # --------------------------------------------------------------------------------------------
@@ -507,14 +622,16 @@ def test_step_order_and_argument_errors(amlib):
         st.step(1, g, 1e-3)
     assert e.value.status == -4
     with pytest.raises(am.AsyncMeshError) as e:
-        st.step(2, [g[0], g[1][1:]], 1e-3)                      # misaligned gradient pointer
+        st.step(2, [g[0], torch.zeros(n + 1, device="cuda")[1:]], 1e-3)       # misaligned gradient pointer
     assert e.value.status == -2
+    with pytest.raises(ValueError):
+        st.step(2, [g[0], g[1][1:]], 1e-3)                      # too short: refused by the binding, before any launch
     with pytest.raises(am.AsyncMeshError) as e:
         st.step(2, g, 1e-3, lambda_t=1.5)
     assert e.value.status == -1
     st.step(2, g, 1e-3)                                         # failed calls left the state untouched
     cap, slots = st.ring_info()
-    assert slots == 2 and 4 * 32 <= cap <= 4 * 256           # 4 tiles, between 1 and 8 lines each
+    assert slots == 2 and 4 * 32 <= cap <= 4 * 256 * 2       # 4 tiles of two interleaved replicas, between 1 and 16 lines each
 
 
 def test_runs_on_the_stream_given_at_init(amlib):
@@ -620,7 +737,7 @@ def test_a_thousand_steps_stay_within_the_bar(amlib):
     assert max(worst.values()) < TOL_F32
 
 
-@pytest.mark.parametrize("case", range(96))
+@pytest.mark.parametrize("case", range(128))
 def test_random_configurations(amlib, case):
     """Seeded random draws over the whole configuration space (sizes, replicas, delay, interval,
     fraction, optimizer, correction, message precision, sampling rule, dtypes, idle replicas)."""
@@ -639,7 +756,8 @@ def test_random_configurations(amlib, case):
               correction=int(rng.choice([O.CORR_NONE, O.CORR_EMA, O.CORR_EAGER])),
               msg_dtype=int(rng.choice([O.MSG_F32, O.MSG_BF16, O.MSG_E4M3])),
               subset_granule=32 if rule == 1 else 1,
-              subset_kind=am.SUBSET_STRATIFIED if rule == 2 else am.SUBSET_BERNOULLI)
+              subset_kind=am.SUBSET_STRATIFIED if rule == 2 else am.SUBSET_BERNOULLI,
+              d_layout=int(rng.integers(0, 2)))
     print(f"case {case}: n={n} R={R} bf16={bf16} {kw}", flush=True)
     st, orc = make_pair(am, n, R, grad_bf16=bf16, fwd_bf16=bf16, **kw)
     if st.fwd is not None:                       # am_sparse_average leaves fwd alone; the oracle's starts at zero
@@ -655,18 +773,22 @@ def test_random_configurations(amlib, case):
             orc.step_masked(t, g, lr, lam, mask, grad_scale=0.5)
         elif rng.integers(0, 4) == 0:
             st.sparse_average(t, lam); orc.sparse_average(t, lam)
+            st.fwd_is_stale = True                  # am_sparse_average leaves fwd alone
         else:
             st.step(t, gd, lr, lam); orc.step(t, g, lr, lam)
+            st.fwd_is_stale = False
         compare(st, orc, f"case {case} t={t}")
 
 
+@both_layouts
 @pytest.mark.parametrize("opt,K", [(O.OPT_NADAMW, 1), (O.OPT_ADAMW, 2)])
-def test_checkpoint_and_resume(amlib, opt, K):
+def test_checkpoint_and_resume(amlib, opt, K, d_layout):
     """A run that is checkpointed after step 5 and resumed on other memory continues bit for bit as
     the uninterrupted run does (and both agree with the oracle)."""
     am = amlib
     n, R, tau, seed, total = 60_017, 4, 2, 31, 13
-    kw = dict(delay=tau, avg_interval=K, fraction=0.1, seed=seed, optimizer=opt, lookahead=(opt != O.OPT_NADAMW), gamma=0.9)
+    kw = dict(delay=tau, avg_interval=K, fraction=0.1, seed=seed, optimizer=opt, lookahead=(opt != O.OPT_NADAMW), gamma=0.9,
+              d_layout=d_layout)
     a, orc = make_pair(am, n, R, **kw)
     saved = None
     mask_at = lambda t: 0b1111 if (t % 2 or opt != O.OPT_NADAMW) else 0b1011    # NADAMW case: replica 2 idles in even ticks
@@ -678,7 +800,7 @@ def test_checkpoint_and_resume(amlib, opt, K):
         if t == 5:
             torch.cuda.synchronize()
             clone = lambda ts: None if ts is None else [x.clone() for x in ts]
-            saved = (a.export_state(), clone(a.w), clone(a.m), clone(a.v), clone(a.d), clone(a.fwd), a.workspace.clone())
+            saved = (a.export_state(), clone(a.w), clone(a.m), clone(a.v), clone(a.d_storage), clone(a.fwd), a.workspace.clone())
     compare(a, orc, "uninterrupted")
     snap, w, m, v, d, fwd, ws = saved
     assert snap.last_t == 5 and snap.delay_now == 1

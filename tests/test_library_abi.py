@@ -29,33 +29,54 @@ def test_every_declared_symbol_is_exported(amlib):
 
 def test_config_struct_matches_header_layout(amlib):
     from paper_2601_22442_amd.binding import Config
-    assert C.sizeof(Config) == 104
+    assert C.sizeof(Config) == 112
     assert Config.fraction.offset == 24 and Config.seed.offset == 32
     assert Config.beta1.offset == 40 and Config.gamma.offset == 56
     assert Config.grad_dtype.offset == 72 and Config.momentum_decay.offset == 80 and Config.subset_granule.offset == 88
     assert Config.msg_dtype.offset == 92 and Config.subset_kind.offset == 96
+    assert Config.d_layout.offset == 100 and Config.ring_cap_lines.offset == 104
 
 
 def test_workspace_bytes_and_capacity_formula(amlib):
-    """A ring slot holds, per replica, whole 128-byte lines: ceil(X/32) per tile of 256 coordinates,
-    X ~ Binomial(256, p); room for the expected total plus 12 standard deviations."""
+    """A ring slot keeps the replicas of a block side by side: per block, a tile of 256 coordinates owns
+    ceil(X rb / 32) whole 128-byte lines, X ~ Binomial(256, p); room for the expected total plus 12
+    standard deviations."""
     am = amlib
     n, R, tau, p = 125_829_120, 8, 4, 0.05
     ntiles = n // 256
     pmf = [math.comb(256, k) * p ** k * (1 - p) ** (256 - k) for k in range(257)]
-    lines = [(k + 31) // 32 for k in range(257)]
+    lines = [(k * 8 + 31) // 32 for k in range(257)]
     mean = sum(a * b for a, b in zip(pmf, lines))
     var = sum(a * b * b for a, b in zip(pmf, lines)) - mean ** 2
     cap_lines = math.ceil(ntiles * mean + 12 * math.sqrt(ntiles * var)) + 64
-    ring = (tau + 1) * cap_lines * 32 * R * 4
+    ring = (tau + 1) * cap_lines * 32 * 4
     b = am.workspace_bytes(am.make_config(n, R, delay=tau, fraction=p))
-    assert ring < b < ring * 1.01 + (1 << 20)                     # plus the small offset tables
-    # stratified variant: a tile meets at most floor(255/20) + 2 = 14 blocks -> one line per tile, no margin needed
+    assert ring < b < ring + (16 << 20)                           # plus the offset tables (4 bytes per tile and slot)
+    assert 3.5 < mean < 3.7                                        # 12.8 values of 8 replicas: about 3.6 lines a tile
+    # 16 replicas = two blocks of 8, each with its own lines
+    b16 = am.workspace_bytes(am.make_config(n, 16, delay=tau, fraction=p))
+    assert 2 * ring < b16 < 2 * ring + (16 << 20)
+    # stratified variant: a tile meets at most floor(255/20) + 2 = 14 blocks -> ceil(14 * 8 / 32) = 4 lines, no margin needed
     bs = am.workspace_bytes(am.make_config(n, R, delay=tau, fraction=p, subset_kind=am.SUBSET_STRATIFIED))
-    ring_s = (tau + 1) * ntiles * 32 * R * 4
+    ring_s = (tau + 1) * ntiles * 4 * 32 * 4
     assert ring_s <= bs < ring_s + (64 << 20)
     full = am.workspace_bytes(am.make_config(1000, 2, delay=0, fraction=1.0))
-    assert full >= 4 * 256 * 2 * 4                                 # p = 1: every tile owns all its 8 lines
+    assert full >= 4 * 256 * 2 * 4                                 # p = 1: every tile owns all its lines
+    # a caller-named slot size is taken as given (and clipped to what p = 1 would need)
+    small = am.workspace_bytes(am.make_config(n, R, delay=tau, fraction=p, ring_cap_lines=1000))
+    assert small < b and (tau + 1) * 1000 * 128 <= small < (tau + 1) * 1000 * 128 + (16 << 20)
+    assert am.workspace_bytes(am.make_config(1000, 2, fraction=0.1, ring_cap_lines=10 ** 9)) == \
+        am.workspace_bytes(am.make_config(1000, 2, fraction=1.0))
+
+
+def test_d_layout_info(amlib):
+    am = amlib
+    assert am.d_layout_info(am.make_config(1000, 8)) == (1, 8, 1000)
+    assert am.d_layout_info(am.make_config(1000, 8, d_layout=am.D_INTERLEAVED)) == (8, 1, 1024 * 8)
+    assert am.d_layout_info(am.make_config(1000, 3, d_layout=am.D_INTERLEAVED)) == (4, 1, 1024 * 4)
+    assert am.d_layout_info(am.make_config(256, 1, d_layout=am.D_INTERLEAVED)) == (1, 1, 256)
+    assert am.d_layout_info(am.make_config(257, 20, d_layout=am.D_INTERLEAVED)) == (8, 3, 512 * 8)
+    assert am.d_layout_info(am.make_config(5, 32, d_layout=am.D_INTERLEAVED)) == (8, 4, 256 * 8)
 
 
 @pytest.mark.parametrize("kw,needle", [
@@ -64,7 +85,7 @@ def test_workspace_bytes_and_capacity_formula(amlib):
     (dict(optimizer=7), "optimizer"), (dict(correction=5), "correction"), (dict(beta1=1.0), "beta1"),
     (dict(fwd_dtype=3), "dtype"), (dict(subset_granule=16), "granule"),
     (dict(subset_kind=2), "subset_kind"), (dict(subset_kind=1, subset_granule=32), "stratified"),
-    (dict(subset_kind=1, fraction=1e-10), "block"),
+    (dict(subset_kind=1, fraction=1e-10), "block"), (dict(d_layout=2), "d_layout"),
 ])
 def test_bad_configs_are_rejected(amlib, kw, needle):
     am = amlib
@@ -127,7 +148,7 @@ def test_snapshot_record_layout_and_checks(amlib):
     snap = B.Snapshot(magic=123)
     assert B.lib.am_resume_state(C.byref(cfg), C.byref(bufs), None, C.byref(snap), C.byref(h)) == -1
     assert "layout" in B.lib.am_last_error().decode()
-    snap = B.Snapshot(magic=0x414D534E41503032, config_digest=1)
+    snap = B.Snapshot(magic=0x414D534E41503033, config_digest=1)
     assert B.lib.am_resume_state(C.byref(cfg), C.byref(bufs), None, C.byref(snap), C.byref(h)) == -1
     assert "different config" in B.lib.am_last_error().decode()
     assert B.lib.am_resume_state(C.byref(cfg), C.byref(bufs), None, None, C.byref(h)) == -1
@@ -180,7 +201,7 @@ def test_header_is_plain_c_and_the_binding_mirrors_its_layout(amlib, tmp_path):
 #include "asyncmesh.h"
 int main(void) {
     printf("%zu %zu %zu %zu %zu\n", sizeof(am_config), offsetof(am_config, fraction), offsetof(am_config, momentum_decay),
-           offsetof(am_config, subset_kind), sizeof(am_buffers));
+           offsetof(am_config, ring_cap_lines), sizeof(am_buffers));
     printf("%zu %zu %zu\n", sizeof(am_snapshot), offsetof(am_snapshot, opt_steps), offsetof(am_snapshot, mu_product));
     am_config c = {0};
     c.n = 125829120u; c.replicas = 8; c.delay = 4; c.avg_interval = 1; c.optimizer = AM_OPT_ADAMW; c.fraction = 0.05;
@@ -200,7 +221,7 @@ int main(void) {
                     "-L", str(lib_dir), "-lasyncmesh", f"-Wl,-rpath,{lib_dir}"], check=True)
     out = subprocess.run([str(exe)], capture_output=True, text=True, check=True).stdout.splitlines()
     assert out[0].split() == [str(C.sizeof(B.Config)), str(B.Config.fraction.offset), str(B.Config.momentum_decay.offset),
-                              str(B.Config.subset_kind.offset), str(C.sizeof(B.Buffers))]
+                              str(B.Config.ring_cap_lines.offset), str(C.sizeof(B.Buffers))]
     assert out[1].split() == [str(C.sizeof(B.Snapshot)), str(B.Snapshot.opt_steps.offset), str(B.Snapshot.mu_product.offset)]
     status, nbytes = out[2].split()
     assert status == "0" and int(nbytes) == am_bytes(amlib)
@@ -209,3 +230,40 @@ int main(void) {
 
 def am_bytes(am):
     return am.workspace_bytes(am.make_config(125_829_120, 8, delay=4, fraction=0.05))
+
+
+def test_library_carries_the_digest_of_its_sources(amlib):
+    """am_version() ends with a digest of the source files the library was built from; the test
+    fixture has already refused a library whose digest is not that of the files in the tree."""
+    from paper_2601_22442_amd.build import source_hash
+    v = amlib.version()
+    assert v.startswith("asyncmesh-gfx950 ") and v.endswith("src:" + source_hash())
+    from paper_2601_22442_amd.build import check_library_is_current
+    with pytest.raises(RuntimeError):
+        check_library_is_current("asyncmesh-gfx950 0.2 src:0123456789abcdef")
+
+
+def test_binding_refuses_wrong_gradients_before_any_launch(amlib):
+    """The C side sees raw pointers only, so the binding checks count, dtype, size, device and
+    contiguity of the gradients (no GPU needed: the checks run on meta-data alone)."""
+    import torch
+    am = amlib
+    from paper_2601_22442_amd import binding as B
+
+    class FakeStage(B.Stage):
+        def __init__(self, cfg):
+            self.cfg, self.device = cfg, torch.device("cpu")
+            self.n, self.R = int(cfg.n), int(cfg.replicas)
+            self._handle = C.c_void_p(None)
+
+    st = FakeStage(am.make_config(100, 2))
+    ok = [torch.zeros(100) for _ in range(2)]
+    for bad in ([ok[0]], [ok[0], torch.zeros(99)], [ok[0], torch.zeros(100, dtype=torch.bfloat16)],
+                [ok[0], torch.zeros(200)[::2]], [ok[0], None]):
+        with pytest.raises(ValueError):
+            st._check_grads(bad)
+    st16 = FakeStage(am.make_config(100, 2, grad_dtype=am.BF16))
+    with pytest.raises(ValueError):
+        st16._check_grads(ok)
+    with pytest.raises(ValueError):
+        B._check_tensors("w", ok, 2, 101, torch.float32, torch.device("cpu"))
