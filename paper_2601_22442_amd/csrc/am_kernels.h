@@ -136,11 +136,15 @@ k_subset_write(SubsetKey key, uint64_t n, uint32_t ntiles, const uint32_t *__res
 enum : int { kOptSgdPlain = 0, kOptSgdMomentum = 1, kOptAdam = 2, kOptNone = 3 };   // kOptNone: w^ = w (averaging only)
 enum : int { kFwdNone = 0, kFwdF32 = 1, kFwdBf16 = 2 };
 
-// What one replica's wave needs to know about its replica: 64 bytes, one scalar load.
+// What one replica's wave needs to know about its replica: 64 bytes, one scalar load.  The record
+// of replica b rb + k sits in slot 8 b + k of StepArgs::rep, whatever rb is, so that a wave finds its
+// record from its block and wave numbers alone, in the same breath as the kernel's other arguments.
+// Slots of absent replicas (R not a multiple of rb) repeat the record of the block's first replica:
+// their waves may load through it, and store nothing.
 struct ReplicaArgs {
     float *w, *m, *v;
     void *fwd;
-    const void *g;
+    const void *g;              // NULL: the replica makes no local step in this launch (w^ = w; m, v kept)
     // bias corrections of the optimizer, per replica: replicas of unequal speed have made unequal
     // numbers of optimizer steps
     double c_g, c_m, c_v;
@@ -154,8 +158,6 @@ struct StepArgs {
     uint32_t rb, rb_shift;                         // replicas per block (1, 2, 4 or 8) and its log2
     uint32_t nblocks;                              // ceil(replicas / rb)
     uint32_t blocks_per_wg;                        // 1 (grid = tiles x blocks), or nblocks when tau = 0 (grid = tiles)
-    uint32_t active_mask;                          // bit i clear: replica i makes no local step in this launch
-                                                   // (w^ = w; m, v kept; its gradient pointer is not read)
     uint32_t lookahead;
     // averaging
     uint32_t do_send, do_recv, ema, same_slot;     // ema: a correction vector d is kept; same_slot: tau = 0,
@@ -222,7 +224,7 @@ __device__ __forceinline__ void local_step(const StepArgs &a, const ReplicaArgs 
 {
     // A replica that is idle in this tick goes through the same arithmetic with the coefficients of
     // the identity (m' = m, v' = v, w^ = w exactly); its gradient was not loaded.
-    const bool idle = OPT != kOptNone && !((a.active_mask >> i) & 1u);
+    const bool idle = OPT != kOptNone && r.g == nullptr;
     const double rs = (OPT != kOptNone && a.replica_scale && !idle) ? (double)a.replica_scale[i] : 1.0;
     const double a_m = idle ? 1.0 : a.a_m, b_m = idle ? 0.0 : a.b_m;
     const double a_v = idle ? 1.0 : a.a_v, b_v = idle ? 0.0 : a.b_v;
@@ -234,7 +236,7 @@ __device__ __forceinline__ void local_step(const StepArgs &a, const ReplicaArgs 
             w_hat.v[j] = in.w.v[j];
             continue;
         }
-        const double gj = rs * (double)in.g.v[j];              // grad_scale is folded into b_m, b_v, c_g
+        const double gj = idle ? 0.0 : rs * (double)in.g.v[j]; // grad_scale is folded into b_m, b_v, c_g; idle: what was loaded is not a gradient
         const double wo = (double)in.w.v[j];
         double step;                                           // what is subtracted besides the decay
         if (OPT == kOptSgdPlain) {
@@ -282,14 +284,15 @@ struct TileLds {
 
 // Issues the loads of replica i's dense operands for one group.
 template <int OPT, bool GRAD_BF16>
-__device__ __forceinline__ void load_group(const StepArgs &a, const ReplicaArgs &r, uint32_t i, uint64_t tbase, uint32_t loff, int nvalid, GroupIn &in)
+__device__ __forceinline__ void load_group(const ReplicaArgs &r, uint64_t tbase, uint32_t loff, int nvalid, GroupIn &in)
 {
     in.w = load_f32x4(r.w + tbase, loff, nvalid);
-    if ((a.active_mask >> i) & 1u)
-        in.g = GRAD_BF16 ? load_bf16x4(static_cast<const uint16_t *>(r.g) + tbase, loff, nvalid)
-                         : load_f32x4(static_cast<const float *>(r.g) + tbase, loff, nvalid);
-    else
-        in.g.v[0] = in.g.v[1] = in.g.v[2] = in.g.v[3] = 0.f;
+    // An idle replica has no gradient: its wave reads its weights in their place (memory that is
+    // surely there; the optimizer step drops the value), without a branch, so that no load waits
+    // for another.
+    const void *gp = r.g == nullptr ? static_cast<const void *>(r.w) : r.g;
+    in.g = GRAD_BF16 ? load_bf16x4(static_cast<const uint16_t *>(gp) + tbase, loff, nvalid)
+                     : load_f32x4(static_cast<const float *>(gp) + tbase, loff, nvalid);
     if (OPT != kOptSgdPlain) in.m = load_f32x4(r.m + tbase, loff, nvalid);
     if (OPT == kOptAdam) in.v = load_f32x4(r.v + tbase, loff, nvalid);
 }
@@ -302,7 +305,7 @@ __device__ __forceinline__ void load_group_sparse(const StepArgs &a, uint32_t i,
                                                   const GroupSubsets &s, GroupIn &in)
 {
     if (!DIL && a.ema && s.line_recv) in.d = load_f32x4(a.d[i] + tbase, loff, nvalid);
-    if (OPT == kOptNone && (s.mask_send != 0u || s.line_recv)) in.w = load_f32x4(a.rep[i].w + tbase, loff, nvalid);
+    if (OPT == kOptNone && (s.mask_send != 0u || s.line_recv)) in.w = load_f32x4(a.rep[8u * (i >> a.rb_shift) + (i & (a.rb - 1u))].w + tbase, loff, nvalid);
 }
 
 // Replica i (slot `slot` of its block) of one group, from loaded operands to stored results.
@@ -469,31 +472,13 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint32_t tile
 
     // ---- dense operands of my replica of the first block: nothing else is requested before them
     uint32_t i = b0 * rb + wave;
-    ReplicaArgs rep = a.rep[i < R ? i : 0u];               // my replica's pointers and coefficients, one scalar load
+    ReplicaArgs rep = a.rep[8u * b0 + wave];               // my replica's pointers and coefficients, one scalar load
     GroupIn in;
-    if (OPT != kOptNone && i < R) load_group<OPT, GRAD_BF16>(a, rep, i, tbase, loff, nvalid, in);
+    // (no condition on i < R: the record of an absent replica names the arrays of the block's first
+    // replica, whose values its wave loads and never uses -- with a condition the compiler parks
+    // the conversions of the loaded values, and with them a wait for memory, right behind the loads)
+    if (OPT != kOptNone) load_group<OPT, GRAD_BF16>(rep, tbase, loff, nvalid, in);
     __builtin_amdgcn_sched_barrier(0);
-
-    // ---- the tile's words in the offset tables of the two slots (scalar loads)
-    uint32_t word_s = 0, base_s = 0, word_r = 0, base_r = 0;
-    if (a.do_send) { word_s = uniform_load(a.send_meta, tile); base_s = uniform_load(a.send_sb_base, tile / kTilesPerSuperblock); }
-    if (a.do_recv && !TAU0) { word_r = uniform_load(a.recv_meta, tile); base_r = uniform_load(a.recv_sb_base, tile / kTilesPerSuperblock); }
-
-    // ---- where the tile's lines sit in the two slots.  A tile whose lines would pass the slot
-    //      capacity is left out, at send and at receive alike.
-    uint32_t first_s = base_s + (word_s & 0xFFFFFFu), lines_s = word_s >> 24;
-    uint32_t first_r = base_r + (word_r & 0xFFFFFFu), lines_r = word_r >> 24;
-    bool keep_s = a.do_send != 0u, keep_r = a.do_recv != 0u;
-    if ((uint64_t)first_s + lines_s > a.cap_lines) { keep_s = false; lines_s = 0; }
-    if (recv_is_send) { first_r = first_s; lines_r = lines_s; keep_r = keep_s; }
-    else if ((uint64_t)first_r + lines_r > a.cap_lines) { keep_r = false; lines_r = 0; }
-
-    // ---- what every replica sent tau rounds ago: straight into LDS
-    if (a.do_recv && !TAU0 && flat < lines_r * 8u) {
-        const float *src = a.ring_recv + (uint64_t)first_r * kLineFloats + flat * 4u;
-        for (uint32_t b = 0; b < a.nblocks; ++b)
-            lds_dma_16(src + b * block_floats, L.recv + b * tile_floats + wave * 256u);
-    }
 
     // ---- subsets: bit j of a lane's mask = coordinate 4 group + j is received / sent now.
     //      Jobs: 0 = the received subset, 1 = the sent one, 2 = the size of what the next step sends.
@@ -507,8 +492,8 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint32_t tile
     for (uint32_t job = 0; job < 3u; ++job) {
         const bool shared = job == 0u ? kShareRecv : job == 1u ? kShareSend : true;
         if (shared && wave != (job & (rb - 1u))) continue;
-        if (job == 0u && !keep_r) continue;
-        if (job == 1u && (!keep_s || recv_is_send)) continue;
+        if (job == 0u && !a.do_recv) continue;
+        if (job == 1u && (!a.do_send || recv_is_send)) continue;
         if (job == 2u && !(a.do_next && b0 == 0u)) continue;
         SubsetKey key = a.key;
         const uint32_t which = (job == 0u && recv_is_send) ? 1u : job;
@@ -542,6 +527,31 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint32_t tile
             if (lane == 0) a.next_lines[tile] = (count * rb + kLineFloats - 1u) / kLineFloats;
         }
     }
+    // ---- the tile's words in the offset tables of the two slots (scalar loads)
+    uint32_t word_s = 0, base_s = 0, word_r = 0, base_r = 0;
+    if (a.do_send) { word_s = uniform_load(a.send_meta, tile); base_s = uniform_load(a.send_sb_base, tile / kTilesPerSuperblock); }
+    if (a.do_recv && !TAU0) { word_r = uniform_load(a.recv_meta, tile); base_r = uniform_load(a.recv_sb_base, tile / kTilesPerSuperblock); }
+
+    // ---- where the tile's lines sit in the two slots.  A tile whose lines would pass the slot
+    //      capacity is left out, at send and at receive alike.
+    uint32_t first_s = base_s + (word_s & 0xFFFFFFu), lines_s = word_s >> 24;
+    uint32_t first_r = base_r + (word_r & 0xFFFFFFu), lines_r = word_r >> 24;
+    bool keep_s = a.do_send != 0u, keep_r = a.do_recv != 0u;
+    if ((uint64_t)first_s + lines_s > a.cap_lines) { keep_s = false; lines_s = 0; }
+    if (recv_is_send) { first_r = first_s; lines_r = lines_s; keep_r = keep_s; }
+    else if ((uint64_t)first_r + lines_r > a.cap_lines) { keep_r = false; lines_r = 0; }
+
+    // ---- what every replica sent tau rounds ago: straight into LDS.  The chunks are dealt out from
+    //      the last wave down: the first waves are busy hashing.
+    const uint32_t wave_r = rb - 1u - wave;
+    if (a.do_recv && !TAU0 && wave_r * 64u + lane < lines_r * 8u) {
+        const float *src = a.ring_recv + (uint64_t)first_r * kLineFloats + (wave_r * 64u + lane) * 4u;
+        for (uint32_t b = 0; b < a.nblocks; ++b)
+            lds_dma_16(src + b * block_floats, L.recv + b * tile_floats + wave_r * 256u);
+    }
+    if (!keep_r) s.mask_recv = 0u;                          // (masks a wave hashed for itself)
+    if (!keep_s) s.mask_send = 0u;
+
     if (!kShareRecv) {                                     // loads of per-replica arrays that the masks steer
         const uint64_t any_recv = __ballot(s.mask_recv != 0u);
         s.line_recv = ((any_recv >> (lane & ~7u)) & 0xFFull) != 0ull;
@@ -584,10 +594,10 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint32_t tile
                 if (b == b0) {
                     pre = in;
                 } else {
-                    if (OPT != kOptNone) load_group<OPT, GRAD_BF16>(a, a.rep[ib], ib, tbase, loff, nvalid, pre);
+                    if (OPT != kOptNone) load_group<OPT, GRAD_BF16>(a.rep[8u * b + wave], tbase, loff, nvalid, pre);
                     load_group_sparse<OPT, DIL>(a, ib, tbase, loff, nvalid, s, pre);
                 }
-                local_step<OPT>(a, a.rep[ib], ib, pre, w_hat, m_new, v_new);
+                local_step<OPT>(a, a.rep[8u * b + wave], ib, pre, w_hat, m_new, v_new);
                 uint32_t c = s.rank_recv;
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
@@ -627,8 +637,8 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint32_t tile
             if (DIL && flat < d_lines * 8u)
                 lds_dma_16(a.d[b] + (uint64_t)tile * tile_floats + d_chunk_off, L.d + wave * 256u);
             if (i < R) {
-                rep = a.rep[i];
-                if (OPT != kOptNone) load_group<OPT, GRAD_BF16>(a, rep, i, tbase, loff, nvalid, in);
+                rep = a.rep[8u * b + wave];
+                if (OPT != kOptNone) load_group<OPT, GRAD_BF16>(rep, tbase, loff, nvalid, in);
                 load_group_sparse<OPT, DIL>(a, i, tbase, loff, nvalid, s, in);
             }
             lds_dma_wait();
@@ -654,7 +664,7 @@ __host__ __device__ inline uint32_t step_lds_floats(uint32_t rb, uint32_t nblock
     return nblocks * kTileCoords * rb + (d_interleaved ? kTileCoords * rb : 0u) + kTileCoords * rb + 64u + 32u + kTileCoords;
 }
 
-// grid = tiles x blocks (tau = 0: tiles); blockDim = 64 rb; dynamic LDS = step_lds_floats() floats
+// grid = (tiles, blocks) (tau = 0: (tiles, 1)); blockDim = 64 rb; dynamic LDS = step_lds_floats() floats
 // (at most 80 registers, so that three workgroups of eight waves fit a compute unit)
 template <int OPT, bool GRAD_BF16, int FWD, bool DIL, bool TAU0>
 __global__ void __launch_bounds__(512, 6)
@@ -663,8 +673,7 @@ k_step(const StepArgs a)
     extern __shared__ __attribute__((aligned(16))) float lds[];
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    uint32_t tile = blockIdx.x, b0 = 0;
-    if (!TAU0 && a.nblocks > 1u) { tile = blockIdx.x / a.nblocks; b0 = blockIdx.x - tile * a.nblocks; }
+    const uint32_t tile = blockIdx.x, b0 = TAU0 ? 0u : blockIdx.y;
     const uint32_t tile_floats = kTileCoords * a.rb;
     TileLds L;
     L.recv = lds;

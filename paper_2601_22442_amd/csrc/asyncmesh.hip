@@ -218,8 +218,16 @@ am_status launch_step_tau(am_state *st, const am::StepArgs &a)
 {
     const am_host::Blocks &B = st->lay.blocks;
     const bool tau0 = a.do_recv && a.same_slot;
-    const dim3 grid(st->lay.ntiles * (tau0 ? 1u : B.nblocks)), block(64u * B.rb);
-    const size_t lds = (size_t)am::step_lds_floats(B.rb, B.nblocks, DIL) * sizeof(float);
+    const dim3 grid(st->lay.ntiles, tau0 ? 1u : B.nblocks), block(64u * B.rb);
+    size_t lds = (size_t)am::step_lds_floats(B.rb, B.nblocks, DIL) * sizeof(float);
+    if (const char *e = std::getenv("AM_EXPERIMENT_LDS_KB")) {          // EXPERIMENT ONLY
+        const size_t want = (size_t)std::atoi(e) * 1024;
+        if (want > lds) lds = want;
+        if (lds > 64 * 1024) {
+            (void)hipFuncSetAttribute((const void *)am::k_step<OPT, GBF, FWD, DIL, false>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+            (void)hipFuncSetAttribute((const void *)am::k_step<OPT, GBF, FWD, DIL, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        }
+    }
     if (tau0) am::k_step<OPT, GBF, FWD, DIL, true><<<grid, block, lds, st->stream>>>(a);
     else am::k_step<OPT, GBF, FWD, DIL, false><<<grid, block, lds, st->stream>>>(a);
     AM_HIP(hipGetLastError());
@@ -530,13 +538,16 @@ am_status step_impl(am_state *st, uint64_t t, const void *const *grads, float lr
 
     am::StepArgs a;
     std::memset(&a, 0, sizeof a);
+    const am_host::Blocks &B = st->lay.blocks;
+    auto slot = [&B](uint32_t i) { return 8u * (i / B.rb) + i % B.rb; };     // where replica i's record sits
     for (uint32_t i = 0; i < c.replicas; ++i) {
-        a.rep[i].w = st->w[i]; a.rep[i].m = st->m[i]; a.rep[i].v = st->v[i];
-        a.rep[i].fwd = st->fwd[i]; a.rep[i].g = grads[i];
+        am::ReplicaArgs &r = a.rep[slot(i)];
+        r.w = st->w[i]; r.m = st->m[i]; r.v = st->v[i];
+        r.fwd = st->fwd[i];
+        r.g = ((mask >> i) & 1u) ? grads[i] : nullptr;                      // NULL = idle in this launch
     }
     a.lookahead = c.lookahead != 0; a.gamma = (double)c.gamma;
     a.replica_scale = dev_replica_scale;
-    a.active_mask = mask;
     const double gs = (double)grad_scale;        // folded into the coefficients that multiply g
 
     // per-step scalars, evaluated once in double; those that depend on a replica's own step count per replica
@@ -558,21 +569,25 @@ am_status step_impl(am_state *st, uint64_t t, const void *const *grads, float lr
         const uint64_t k = active ? st->opt_steps[i] + 1 : t;
         steps_next[i] = k;
         if (c.optimizer == AM_OPT_SGD) {
-            a.rep[i].c_m = lrd; a.rep[i].c_g = lrd * gs;
+            a.rep[slot(i)].c_m = lrd; a.rep[slot(i)].c_g = lrd * gs;
             continue;
         }
         const double bc1 = 1.0 - std::pow(b1, (double)k), bc2 = 1.0 - std::pow(b2, (double)k);
-        a.rep[i].c_v = 1.0 / std::sqrt(bc2);
+        a.rep[slot(i)].c_v = 1.0 / std::sqrt(bc2);
         if (c.optimizer == AM_OPT_ADAMW) {
-            a.rep[i].c_g = 0.0; a.rep[i].c_m = lrd / bc1;
+            a.rep[slot(i)].c_g = 0.0; a.rep[slot(i)].c_m = lrd / bc1;
         } else {
             const double mu_t = b1 * (1.0 - 0.5 * std::pow(0.96, (double)k * c.momentum_decay));
             const double mu_t1 = b1 * (1.0 - 0.5 * std::pow(0.96, (double)(k + 1) * c.momentum_decay));
             mu_prod_next[i] = st->mu_product[i] * mu_t;
-            a.rep[i].c_g = lrd * (1.0 - mu_t) / (1.0 - mu_prod_next[i]) * gs;
-            a.rep[i].c_m = lrd * mu_t1 / (1.0 - mu_prod_next[i] * mu_t1);
+            a.rep[slot(i)].c_g = lrd * (1.0 - mu_t) / (1.0 - mu_prod_next[i]) * gs;
+            a.rep[slot(i)].c_m = lrd * mu_t1 / (1.0 - mu_prod_next[i] * mu_t1);
         }
     }
+
+    for (uint32_t b = 0; b < B.nblocks; ++b)                  // slots of absent replicas: loads through them must be harmless
+        for (uint32_t k = 0; k < B.rb; ++k)
+            if (b * B.rb + k >= c.replicas) a.rep[8u * b + k] = a.rep[8u * b];
 
     const Round r = plan_round(st, t);
     if (am_status s = fill_averaging(st, t, lambda_t, r, a)) return s;
@@ -626,7 +641,7 @@ am_status am_sparse_average(am_state *st, uint64_t t, float lambda_t)
         // the fused kernel with the optimizer pass left out: w^ = w, only touched lines move
         am::StepArgs a;
         std::memset(&a, 0, sizeof a);
-        for (uint32_t i = 0; i < st->cfg.replicas; ++i) a.rep[i].w = st->w[i];
+        for (uint32_t i = 0; i < st->cfg.replicas; ++i) a.rep[8u * (i / st->lay.blocks.rb) + i % st->lay.blocks.rb].w = st->w[i];
         if (am_status s = fill_averaging(st, t, lambda_t, r, a)) return s;
         if (am_status s = launch_step_layout<am::kOptNone, false, am::kFwdNone>(st, a)) return s;
     }
