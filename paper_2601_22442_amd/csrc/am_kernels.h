@@ -167,6 +167,8 @@ struct StepArgs {
     uint32_t cap_lines;                            // lines (of 32 floats) per block in a ring slot
     const uint32_t *send_meta, *send_sb_base;      // tile's word: lines << 24 | offset in its superblock; first line = sb_base[tile >> 9] + offset
     const uint32_t *recv_meta, *recv_sb_base;
+    uint64_t *send_lines;                          // interleaved d: per tile, which of its lines of d hold a coordinate of the subset sent now
+    const uint64_t *recv_lines;                    //   (bit = first lane of the line); read tau rounds later, before any hashing
     float *ring_send;                              // slot written now: [block][line][32], a line = [coordinate][rb]
     const float *ring_recv;                        // slot sent tau rounds ago
     uint32_t *next_lines;                          // [ntiles], written when do_next
@@ -488,6 +490,32 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint32_t tile
     s.line_recv = false;
     const uint32_t lpl = 8u >> sh;                                         // lanes (groups) per 128-byte line of d
     const uint32_t leader = lane & ~(lpl - 1u);
+    // interleaved d: the lines of the tile that hold a received coordinate go straight into LDS (one
+    // wave).  Which lines those are was noted when the subset was sent, so the request leaves
+    // before any hashing (tau = 0: known only once this step's subset is hashed).
+    auto request_d_lines = [&](const uint64_t leaders) {
+        const uint32_t nlines = (uint32_t)__popcll(leaders);
+        if (nlines) {
+            if ((leaders >> lane) & 1ull) L.list[__popcll(leaders & ((1ull << lane) - 1ull))] = lane >> (3u - sh);
+            wave_lds_sync();
+            const float *src = a.d[b0] + (uint64_t)tile * tile_floats + (lane & 7u) * 4u;
+            for (uint32_t q0 = 0; q0 < nlines; q0 += 8u) {
+                const uint32_t q = q0 + (lane >> 3);
+                if (q < nlines) lds_dma_16(src + L.list[q] * kLineFloats, L.d + q0 * kLineFloats);
+            }
+        }
+    };
+    auto lines_of = [&](const uint32_t mask) {              // bit = first lane of a line of d that holds a coordinate of the mask
+        const uint64_t any = __ballot(mask != 0u);
+        const bool touched = ((any >> leader) & ((1ull << lpl) - 1ull)) != 0ull;
+        return (uint64_t)__ballot(touched && lane == leader);
+    };
+    if (DIL && !TAU0 && a.ema && a.do_recv && wave == 0u) {
+        // (only first lanes of lines can be named, whatever the word in memory says)
+        const uint64_t first_lanes = sh == 3u ? ~0ull : sh == 2u ? 0x5555555555555555ull : sh == 1u ? 0x1111111111111111ull : 0x0101010101010101ull;
+        request_d_lines(uniform_load64(a.recv_lines, tile) & first_lanes);
+    }
+
 #pragma unroll
     for (uint32_t job = 0; job < 3u; ++job) {
         const bool shared = job == 0u ? kShareRecv : job == 1u ? kShareSend : true;
@@ -502,25 +530,18 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint32_t tile
         if (job == 0u) {
             s.mask_recv = mask;
             if (kShareRecv) L.masks[64u + lane] = (uint8_t)mask;
-            // interleaved d: the lines of the tile that hold a received coordinate, straight into LDS (one wave)
-            if (DIL && a.ema && wave == 0u) {
-                const uint64_t any_recv = __ballot(mask != 0u);
-                const bool touched = ((any_recv >> leader) & ((1ull << lpl) - 1ull)) != 0ull;
-                const uint64_t leaders = __ballot(touched && lane == leader);
-                const uint32_t nlines = (uint32_t)__popcll(leaders);
-                if (nlines) {
-                    if (touched && lane == leader) L.list[__popcll(leaders & ((1ull << leader) - 1ull))] = lane >> (3u - sh);
-                    wave_lds_sync();
-                    const float *src = a.d[b0] + (uint64_t)tile * tile_floats + (lane & 7u) * 4u;
-                    for (uint32_t q0 = 0; q0 < nlines; q0 += 8u) {
-                        const uint32_t q = q0 + (lane >> 3);
-                        if (q < nlines) lds_dma_16(src + L.list[q] * kLineFloats, L.d + q0 * kLineFloats);
-                    }
-                }
+            if (DIL && TAU0 && a.ema && wave == 0u) {      // tau = 0: the subset received is the one sent now
+                const uint64_t leaders = lines_of(mask);
+                request_d_lines(leaders);
+                if (lane == 0u) a.send_lines[tile] = leaders;      // a later step may receive this slot with a delay
             }
         } else if (job == 1u) {
             s.mask_send = mask;
             if (kShareSend) L.masks[lane] = (uint8_t)mask;
+            if (DIL && !TAU0 && a.ema && b0 == 0u && wave == (1u & (rb - 1u))) {     // for the step that receives this subset
+                const uint64_t leaders = lines_of(mask);
+                if (lane == 0u) a.send_lines[tile] = leaders;
+            }
         } else {
             uint32_t count;
             (void)wave_prefix_mask4(mask, count);

@@ -140,6 +140,7 @@ struct am_state {
     uint32_t *next_lines() const { return reinterpret_cast<uint32_t *>(ws + lay.off_next); }
     uint32_t *meta_local(uint32_t slot) const { return reinterpret_cast<uint32_t *>(ws + lay.off_meta + lay.meta_stride * slot); }
     uint32_t *meta_sb(uint32_t slot) const { return reinterpret_cast<uint32_t *>(ws + lay.off_meta + lay.meta_stride * slot + lay.meta_sb_off); }
+    uint64_t *meta_lines(uint32_t slot) const { return reinterpret_cast<uint64_t *>(ws + lay.off_meta + lay.meta_stride * slot + lay.meta_lines_off); }
     float *ring(uint32_t slot) const { return reinterpret_cast<float *>(ws + lay.off_ring + lay.ring_stride * slot); }
 };
 
@@ -219,15 +220,7 @@ am_status launch_step_tau(am_state *st, const am::StepArgs &a)
     const am_host::Blocks &B = st->lay.blocks;
     const bool tau0 = a.do_recv && a.same_slot;
     const dim3 grid(st->lay.ntiles, tau0 ? 1u : B.nblocks), block(64u * B.rb);
-    size_t lds = (size_t)am::step_lds_floats(B.rb, B.nblocks, DIL) * sizeof(float);
-    if (const char *e = std::getenv("AM_EXPERIMENT_LDS_KB")) {          // EXPERIMENT ONLY
-        const size_t want = (size_t)std::atoi(e) * 1024;
-        if (want > lds) lds = want;
-        if (lds > 64 * 1024) {
-            (void)hipFuncSetAttribute((const void *)am::k_step<OPT, GBF, FWD, DIL, false>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-            (void)hipFuncSetAttribute((const void *)am::k_step<OPT, GBF, FWD, DIL, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        }
-    }
+    const size_t lds = (size_t)am::step_lds_floats(B.rb, B.nblocks, DIL) * sizeof(float);
     if (tau0) am::k_step<OPT, GBF, FWD, DIL, true><<<grid, block, lds, st->stream>>>(a);
     else am::k_step<OPT, GBF, FWD, DIL, false><<<grid, block, lds, st->stream>>>(a);
     AM_HIP(hipGetLastError());
@@ -277,12 +270,14 @@ am_status fill_averaging(am_state *st, uint64_t t, float lambda_t, const Round &
         a.ring_send = st->ring(r.slot_send);
         a.send_meta = st->meta_local(r.slot_send);
         a.send_sb_base = st->meta_sb(r.slot_send);
+        a.send_lines = st->meta_lines(r.slot_send);
     }
     if (r.recv) {
         a.step_lo[0] = (uint32_t)r.step_recv; a.step_hi[0] = (uint32_t)(r.step_recv >> 32);
         a.ring_recv = st->ring(r.slot_recv);
         a.recv_meta = st->meta_local(r.slot_recv);
         a.recv_sb_base = st->meta_sb(r.slot_recv);
+        a.recv_lines = st->meta_lines(r.slot_recv);
     }
     return AM_OK;
 }

@@ -51,11 +51,12 @@ def test_workspace_bytes_and_capacity_formula(amlib):
     cap_lines = math.ceil(ntiles * mean + 12 * math.sqrt(ntiles * var)) + 64
     ring = (tau + 1) * cap_lines * 32 * 4
     b = am.workspace_bytes(am.make_config(n, R, delay=tau, fraction=p))
-    assert ring < b < ring + (16 << 20)                           # plus the offset tables (4 bytes per tile and slot)
+    tables = (tau + 2) * ntiles * 12 + ntiles * 4                 # per slot (and one spare): 4 + 8 bytes per tile; next step's sizes
+    assert ring + tables <= b < ring + tables + (1 << 20)
     assert 3.5 < mean < 3.7                                        # 12.8 values of 8 replicas: about 3.6 lines a tile
     # 16 replicas = two blocks of 8, each with its own lines
     b16 = am.workspace_bytes(am.make_config(n, 16, delay=tau, fraction=p))
-    assert 2 * ring < b16 < 2 * ring + (16 << 20)
+    assert 2 * ring + tables <= b16 < 2 * ring + tables + (1 << 20)
     # stratified variant: a tile meets at most floor(255/20) + 2 = 14 blocks -> ceil(14 * 8 / 32) = 4 lines, no margin needed
     bs = am.workspace_bytes(am.make_config(n, R, delay=tau, fraction=p, subset_kind=am.SUBSET_STRATIFIED))
     ring_s = (tau + 1) * ntiles * 4 * 32 * 4
@@ -64,7 +65,7 @@ def test_workspace_bytes_and_capacity_formula(amlib):
     assert full >= 4 * 256 * 2 * 4                                 # p = 1: every tile owns all its lines
     # a caller-named slot size is taken as given (and clipped to what p = 1 would need)
     small = am.workspace_bytes(am.make_config(n, R, delay=tau, fraction=p, ring_cap_lines=1000))
-    assert small < b and (tau + 1) * 1000 * 128 <= small < (tau + 1) * 1000 * 128 + (16 << 20)
+    assert small < b and (tau + 1) * 1000 * 128 + tables <= small < (tau + 1) * 1000 * 128 + tables + (1 << 20)
     assert am.workspace_bytes(am.make_config(1000, 2, fraction=0.1, ring_cap_lines=10 ** 9)) == \
         am.workspace_bytes(am.make_config(1000, 2, fraction=1.0))
 
