@@ -62,6 +62,18 @@ def tiled_on_device(torch, pool, n, offset):
     return pool.repeat(reps)[offset:offset + n].clone()
 
 
+def fill_tiled(torch, out, pool, offset):
+    """out[k] = pool[(k + offset) mod len(pool)], written in place in pieces of one pool length, so that
+    no temporary of the size of a state array is ever allocated (the big arrays are the first and only
+    large allocations of the process and get whole, aligned stretches of memory)."""
+    n, m = out.numel(), pool.numel()
+    start = offset % m
+    rolled = torch.roll(pool, -start).to(out.dtype)
+    for lo in range(0, n, m):
+        k = min(m, n - lo)
+        out[lo:lo + k].copy_(rolled[:k])
+
+
 def sample_windows(n):
     """Coordinate ranges on which the oracle replays the run: the whole stage when it is small, else its
     head, an unaligned stretch in the middle and its tail."""
@@ -194,18 +206,18 @@ def main():
                          grad_dtype=am.BF16 if w["bf16"] else am.F32)
     pool_n = 1 << 20
     w_pool_host = si.stage_weights(pool_n, 0)
+    # the big arrays first (state, then gradients), each its own allocation, filled in place afterwards
+    st = am.init_state(cfg, None)
+    nsets = 1 if n * R * 4 > 24e9 else 2        # two gradient sets per replica, cycled (traffic per step is unchanged); one where two do not fit
+    gdt = torch.bfloat16 if w["bf16"] else torch.float32
+    gsets = [[torch.empty(n, dtype=gdt, device=dev) for _ in range(R)] for _ in range(nsets)]
     w_pool = torch.from_numpy(w_pool_host).to(dev)
-    st = am.init_state(cfg, tiled_on_device(torch, w_pool, n, 0))
-    # two gradient sets per replica, cycled (traffic per step is unchanged); one set where two do not fit
-    gsets = []
-    nsets = 1 if n * R * 4 > 24e9 else 2
+    for i in range(R):
+        fill_tiled(torch, st.w[i], w_pool, 0)
     for s in range(nsets):
         pools = si.replica_grads(pool_n, R, s + 1, 0)
-        gs = []
         for i in range(R):
-            g = tiled_on_device(torch, torch.from_numpy(pools[i]).to(dev), n, (7919 * (i + 1) * (s + 1)) % pool_n)
-            gs.append(g.to(torch.bfloat16) if w["bf16"] else g)
-        gsets.append(gs)
+            fill_tiled(torch, gsets[s][i], torch.from_numpy(pools[i]).to(dev), (7919 * (i + 1) * (s + 1)) % pool_n)
     torch.cuda.synchronize()
 
     warm = max(args.warmup, tau + 1)          # timed region starts with send and receive both live

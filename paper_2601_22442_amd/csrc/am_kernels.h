@@ -315,11 +315,10 @@ __device__ __forceinline__ void load_group_sparse(const StepArgs &a, uint32_t i,
 template <int OPT, int FWD, bool DIL, bool TAU0>
 __device__ __forceinline__ void step_replica(const StepArgs &a, const ReplicaArgs &r, uint32_t i, uint32_t slot, uint64_t tbase, uint32_t loff, int nvalid,
                                              const GroupSubsets &s, const bool tile_receives, const float (&abar)[4], GroupIn &in,
-                                             const float *recv_block, const TileLds &L)
+                                             F4 &w_hat, F4 &m_new, F4 &v_new, const float *recv_block, const TileLds &L)
 {
     const uint32_t rb = a.rb;
-    F4 w_hat, m_new, v_new;
-    local_step<OPT>(a, r, i, in, w_hat, m_new, v_new);
+    if (TAU0 || !DIL) local_step<OPT>(a, r, i, in, w_hat, m_new, v_new);      // (else: done by the caller while it waited)
     // the moments are final: out they go, before the averaging needs registers
     if (OPT == kOptSgdMomentum || OPT == kOptAdam) store_f32x4(r.m + tbase, loff, nvalid, m_new);
     if (OPT == kOptAdam) store_f32x4(r.v + tbase, loff, nvalid, v_new);
@@ -626,6 +625,10 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint32_t tile
             }
         }
     }
+    // the local optimizer step needs nothing but the wave's own operands: it runs while the lines
+    // for LDS and the other waves' operands are still on their way
+    F4 w_hat, m_new, v_new;
+    if (!TAU0 && DIL) local_step<OPT>(a, rep, i, in, w_hat, m_new, v_new);      // (per-replica d: its entries are in registers too)
     lds_dma_wait();
     __syncthreads();
     if (!recv_is_send) finish_subsets();
@@ -665,7 +668,7 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint32_t tile
             lds_dma_wait();
             __syncthreads();
         }
-        if (i < R) step_replica<OPT, FWD, DIL, TAU0>(a, rep, i, wave, tbase, loff, nvalid, s, count_recv != 0u, abar, in, L.recv + b * tile_floats, L);
+        if (i < R) step_replica<OPT, FWD, DIL, TAU0>(a, rep, i, wave, tbase, loff, nvalid, s, count_recv != 0u, abar, in, w_hat, m_new, v_new, L.recv + b * tile_floats, L);
         __syncthreads();
         // whole lines leave with 16 bytes per thread
         if (flat < lines_s * 8u) {
