@@ -833,3 +833,59 @@ def test_kernel_profiling_hooks(amlib):
     st.set_profiling(False)
     st.step(6, g, 1e-3)
     assert st.get_profile()[1] == 0
+
+
+def test_ring_slot_overflow_drops_whole_tiles_and_is_loud(amlib):
+    """A caller-named slot size (ring_cap_lines) that is too small: the tiles past the capacity are
+    left out of the round at send and at receive alike (they evolve as if never averaged), the
+    tiles before it follow the method exactly, the sticky flag is raised, and once it has been
+    read as set the next step is refused."""
+    am = amlib
+    n, R, tau, p, seed, steps, cap = 100_003, 4, 1, 0.2, 19, 6, 700
+    rb = 4
+    w0 = si.stage_weights(n, seed)
+    cfg = am.make_config(n, R, delay=tau, fraction=p, seed=seed, lookahead=True, gamma=0.9, d_layout=INTERLEAVED,
+                         ring_cap_lines=cap)
+    st = am.init_state(cfg, torch.from_numpy(w0).cuda())
+    assert st.ring_info()[0] == cap * 32
+    full = O.Oracle(n, R, delay=tau, fraction=p, seed=seed, lookahead=True, gamma=0.9); full.set_w(w0)
+    never = O.Oracle(n, R, delay=tau, fraction=EMPTY_P, seed=seed, lookahead=True, gamma=0.9); never.set_w(w0)
+    first_dropped = []
+    for t in range(1, steps + 1):
+        g, gd = grads_for(n, R, t, seed, False)
+        st.step(t, gd, 1e-3, 0.5); full.step(t, g, 1e-3, 0.5); never.step(t, g, 1e-3, 0.5)
+        counts = np.bincount((O.subset(seed, t, n, p) // 256).astype(np.int64), minlength=-(-n // 256))
+        lines = -(-counts * rb // 32)
+        start = np.cumsum(lines) - lines
+        first_dropped.append(int(np.argmax(start + lines > cap)))
+        assert (start + lines > cap).any()
+    lo, hi = min(first_dropped) * 256, (max(first_dropped) + 1) * 256
+    assert 0 < lo <= hi < n - 10_000
+    for i in range(R):
+        for name in ("w", "m", "v", "d", "fwd"):
+            got = getattr(st, name)[i].cpu().numpy()
+            assert rel_err(got[:lo], getattr(full, name)(i)[:lo]) < TOL_F32, (name, i, "kept tiles")
+            assert rel_err(got[hi:], getattr(never, name)(i)[hi:]) < TOL_F32, (name, i, "dropped tiles")
+    assert not np.any(st.d[0].cpu().numpy()[hi:]) and np.any(st.d[0].cpu().numpy()[:lo])
+    assert st.read_flags() & 1
+    with pytest.raises(am.AsyncMeshError) as e:
+        st.step(steps + 1, grads_for(n, R, steps + 1, seed, False)[1], 1e-3, 0.5)
+    assert e.value.status == -6
+    with pytest.raises(am.AsyncMeshError) as e:
+        st.sparse_average(steps + 1, 0.5)
+    assert e.value.status == -6
+
+
+def test_profiling_pool_is_bounded(amlib):
+    """More launches than the event pool holds: the later ones run untimed, nothing grows."""
+    am = amlib
+    n, R = 4096, 1
+    st = am.init_state(am.make_config(n, R, fraction=0.1, optimizer=am.OPT_SGD, beta1=0.0, correction=am.CORR_NONE), torch.zeros(n))
+    g = [torch.zeros(n, device="cuda")]
+    st.set_profiling(True)
+    for t in range(1, 4200):
+        st.step(t, g, 1e-3)
+    times = st.get_profile_times()
+    assert len(times) == 4096 and all(x > 0 for x in times)
+    st.step(4200, g, 1e-3)
+    assert len(st.get_profile_times()) == 1
