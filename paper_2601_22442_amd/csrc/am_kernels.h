@@ -457,8 +457,13 @@ template <int OPT, bool GRAD_BF16, int FWD, bool DIL, bool TAU0, bool FULL>
 __device__ __forceinline__ void step_tile(const StepArgs &a, const uint32_t tile, const uint32_t b0, const uint32_t wave,
                                           const uint32_t lane, const TileLds &L)
 {
-    constexpr bool kShareRecv = DIL && OPT != kOptNone;    // one wave hashes the received subset for all
-    constexpr bool kShareSend = OPT != kOptNone;           // one wave hashes the sent subset for all
+    // One wave hashes the sent subset for all; so it is with the received subset, unless its masks steer
+    // loads of per-replica arrays that should leave before the barrier (per-replica layout of d in the
+    // fused step).  The averaging-only call has no dense loads to wait for anyway: its waves share the
+    // masks through one more barrier and load what the masks name after it.
+    constexpr bool kEarlyMasks = OPT == kOptNone;
+    constexpr bool kShareRecv = DIL || kEarlyMasks;
+    constexpr bool kShareSend = true;
     const uint32_t R = a.replicas, rb = a.rb, sh = a.rb_shift;
     const uint32_t flat = wave * 64u + lane;                               // 64 rb threads; thread f owns 16-byte chunk f
     const uint64_t group = (uint64_t)tile * 64u + lane;
@@ -572,16 +577,6 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint32_t tile
     if (!keep_r) s.mask_recv = 0u;                          // (masks a wave hashed for itself)
     if (!keep_s) s.mask_send = 0u;
 
-    if (!kShareRecv) {                                     // loads of per-replica arrays that the masks steer
-        const uint64_t any_recv = __ballot(s.mask_recv != 0u);
-        s.line_recv = ((any_recv >> (lane & ~7u)) & 0xFFull) != 0ull;
-        if (!kShareSend && recv_is_send) s.mask_send = s.mask_recv;
-        if (i < R) load_group_sparse<OPT, DIL>(a, i, tbase, loff, nvalid, s, in);
-    }
-
-    // ---- staging lines of the send start at zero: line tails and the slots of absent replicas stay zero
-    if (flat < lines_s * 8u) *reinterpret_cast<v4f *>(L.send + flat * 4u) = v4f{0.f, 0.f, 0.f, 0.f};
-
     // the masks of the hashing waves, ranks inside the tile, and where the group's d entries sit in LDS
     uint32_t count_recv = 0, d_lines = 0;
     auto finish_subsets = [&]() {
@@ -601,10 +596,24 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint32_t tile
         }
     };
 
+    if (kEarlyMasks && !recv_is_send) {                    // averaging only: masks through LDS, then the loads they name
+        __syncthreads();
+        finish_subsets();
+        if (i < R) load_group_sparse<OPT, DIL>(a, i, tbase, loff, nvalid, s, in);
+    } else if (!kShareRecv) {                              // loads of per-replica arrays that the masks steer
+        const uint64_t any_recv = __ballot(s.mask_recv != 0u);
+        s.line_recv = ((any_recv >> (lane & ~7u)) & 0xFFull) != 0ull;
+        if (i < R) load_group_sparse<OPT, DIL>(a, i, tbase, loff, nvalid, s, in);
+    }
+
+    // ---- staging lines of the send start at zero: line tails and the slots of absent replicas stay zero
+    if (flat < lines_s * 8u) *reinterpret_cast<v4f *>(L.send + flat * 4u) = v4f{0.f, 0.f, 0.f, 0.f};
+
     // ---- tau = 0: the average is of this step's w^ : every wave puts those of its replicas in place
     if (recv_is_send) {
         if (kShareRecv) __syncthreads();                   // the masks are in LDS
         finish_subsets();
+        if (kEarlyMasks && i < R) load_group_sparse<OPT, DIL>(a, i, tbase, loff, nvalid, s, in);
         if (count_recv) {
             for (uint32_t b = 0; b < a.nblocks; ++b) {
                 const uint32_t ib = b * rb + wave;
@@ -631,7 +640,7 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint32_t tile
     if (!TAU0 && DIL) local_step<OPT>(a, rep, i, in, w_hat, m_new, v_new);      // (per-replica d: its entries are in registers too)
     lds_dma_wait();
     __syncthreads();
-    if (!recv_is_send) finish_subsets();
+    if (!recv_is_send && !kEarlyMasks) finish_subsets();
 
     // ---- old average of the coordinates received now: thread c forms the mean of the coordinate of
     //      rank c once for the whole workgroup (in fp64, in replica order); after one more barrier every
