@@ -128,12 +128,6 @@ __device__ __forceinline__ uint32_t uniform_load(const uint32_t *p, uint32_t idx
     return ((const_u32_ptr)(uintptr_t)p)[idx];
 }
 
-__device__ __forceinline__ uint64_t uniform_load64(const uint64_t *p, uint32_t idx)
-{
-    typedef const uint64_t __attribute__((address_space(4))) *const_u64_ptr;
-    return ((const_u64_ptr)(uintptr_t)p)[idx];
-}
-
 // Direct global -> LDS load of 16 bytes per active lane: lane l of the wave writes
 // lds_wave_base[4 l .. 4 l + 3] (lds_wave_base must be the same for all lanes); no registers are
 // held while the load is in flight.  The data is in LDS once the wave's vector-memory counter has

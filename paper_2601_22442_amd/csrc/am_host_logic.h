@@ -77,14 +77,13 @@ inline uint64_t slot_capacity_lines(uint64_t ntiles, double p, uint32_t rb, bool
 }
 
 // workspace = [flags 256 B][reduction partials 32 x 1024 doubles][next_lines u32[ntiles]][meta x (slots + 1)][ring values x slots]
-//   meta = tile words u32[ntiles] | sb_base u32[nsb + 1] | touched lines of d u64[ntiles]
-//          (the extra block serves am_subset_indices)
+//   meta = tile words u32[ntiles] | sb_base u32[nsb + 1]      (the extra block serves am_subset_indices)
 //   ring slot = nblocks * cap_lines * 32 fp32: [block][line][32], a line = [coordinate][replica in block]
 struct Layout {
     uint32_t ntiles, nsb, slots;
     Blocks blocks;
     uint64_t cap_lines;
-    uint64_t off_flags, off_reduce, off_next, off_meta, meta_stride, meta_sb_off, meta_lines_off, off_ring, ring_stride, total;
+    uint64_t off_flags, off_reduce, off_next, off_meta, meta_stride, meta_sb_off, off_ring, ring_stride, total;
 };
 
 inline Layout make_layout(const am_config &c)
@@ -103,8 +102,7 @@ inline Layout make_layout(const am_config &c)
     L.off_next = L.off_reduce + (uint64_t)AM_MAX_REPLICAS * 1024 * 8;
     L.off_meta = L.off_next + round_up((uint64_t)L.ntiles * 4, 256);
     L.meta_sb_off = round_up((uint64_t)L.ntiles * 4, 256);
-    L.meta_lines_off = L.meta_sb_off + round_up(((uint64_t)L.nsb + 1) * 4, 256);
-    L.meta_stride = L.meta_lines_off + round_up((uint64_t)L.ntiles * 8, 256);
+    L.meta_stride = L.meta_sb_off + round_up(((uint64_t)L.nsb + 1) * 4, 256);
     L.off_ring = L.off_meta + L.meta_stride * (L.slots + 1);
     L.ring_stride = round_up(L.cap_lines * am::kLineFloats * L.blocks.nblocks * 4, 256);
     L.total = L.off_ring + L.ring_stride * L.slots;

@@ -167,8 +167,6 @@ struct StepArgs {
     uint32_t cap_lines;                            // lines (of 32 floats) per block in a ring slot
     const uint32_t *send_meta, *send_sb_base;      // tile's word: lines << 24 | offset in its superblock; first line = sb_base[tile >> 9] + offset
     const uint32_t *recv_meta, *recv_sb_base;
-    uint64_t *send_lines;                          // interleaved d: per tile, which of its lines of d hold a coordinate of the subset sent now
-    const uint64_t *recv_lines;                    //   (bit = first lane of the line); read tau rounds later, before any hashing
     float *ring_send;                              // slot written now: [block][line][32], a line = [coordinate][rb]
     const float *ring_recv;                        // slot sent tau rounds ago
     uint32_t *next_lines;                          // [ntiles], written when do_next
@@ -318,10 +316,11 @@ __device__ __forceinline__ void step_replica(const StepArgs &a, const ReplicaArg
                                              F4 &w_hat, F4 &m_new, F4 &v_new, const float *recv_block, const TileLds &L)
 {
     const uint32_t rb = a.rb;
-    if (TAU0 || !DIL) local_step<OPT>(a, r, i, in, w_hat, m_new, v_new);      // (else: done by the caller while it waited)
-    // the moments are final: out they go, before the averaging needs registers
-    if (OPT == kOptSgdMomentum || OPT == kOptAdam) store_f32x4(r.m + tbase, loff, nvalid, m_new);
-    if (OPT == kOptAdam) store_f32x4(r.v + tbase, loff, nvalid, v_new);
+    if (TAU0 || !DIL || OPT == kOptNone) local_step<OPT>(a, r, i, in, w_hat, m_new, v_new);      // (else: done by the caller while it waited)
+    if (TAU0 || !DIL) {                                    // the moments are final: out they go, before the averaging needs registers
+        if (OPT == kOptSgdMomentum || OPT == kOptAdam) store_f32x4(r.m + tbase, loff, nvalid, m_new);
+        if (OPT == kOptAdam) store_f32x4(r.v + tbase, loff, nvalid, v_new);
+    }
 
     if (s.mask_send) {                                     // send: into the staging lines, [rank][rb]
         uint32_t c = s.rank_send;
@@ -494,9 +493,10 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint32_t tile
     s.line_recv = false;
     const uint32_t lpl = 8u >> sh;                                         // lanes (groups) per 128-byte line of d
     const uint32_t leader = lane & ~(lpl - 1u);
-    // interleaved d: the lines of the tile that hold a received coordinate go straight into LDS (one
-    // wave).  Which lines those are was noted when the subset was sent, so the request leaves
-    // before any hashing (tau = 0: known only once this step's subset is hashed).
+    // interleaved d: the lines of the tile that hold a received coordinate go straight into LDS, requested
+    // by the wave that hashes the received subset as soon as it knows them.  (Noting the touched lines
+    // in memory when a subset is sent and reading them back before hashing was measured slower: the
+    // scalar load of the note holds the hashing wave up for longer than the hashing takes.)
     auto request_d_lines = [&](const uint64_t leaders) {
         const uint32_t nlines = (uint32_t)__popcll(leaders);
         if (nlines) {
@@ -514,12 +514,6 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint32_t tile
         const bool touched = ((any >> leader) & ((1ull << lpl) - 1ull)) != 0ull;
         return (uint64_t)__ballot(touched && lane == leader);
     };
-    if (DIL && !TAU0 && a.ema && a.do_recv && wave == 0u) {
-        // (only first lanes of lines can be named, whatever the word in memory says)
-        const uint64_t first_lanes = sh == 3u ? ~0ull : sh == 2u ? 0x5555555555555555ull : sh == 1u ? 0x1111111111111111ull : 0x0101010101010101ull;
-        request_d_lines(uniform_load64(a.recv_lines, tile) & first_lanes);
-    }
-
 #pragma unroll
     for (uint32_t job = 0; job < 3u; ++job) {
         const bool shared = job == 0u ? kShareRecv : job == 1u ? kShareSend : true;
@@ -534,18 +528,10 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint32_t tile
         if (job == 0u) {
             s.mask_recv = mask;
             if (kShareRecv) L.masks[64u + lane] = (uint8_t)mask;
-            if (DIL && TAU0 && a.ema && wave == 0u) {      // tau = 0: the subset received is the one sent now
-                const uint64_t leaders = lines_of(mask);
-                request_d_lines(leaders);
-                if (lane == 0u) a.send_lines[tile] = leaders;      // a later step may receive this slot with a delay
-            }
+            if (DIL && a.ema && wave == 0u) request_d_lines(lines_of(mask));
         } else if (job == 1u) {
             s.mask_send = mask;
             if (kShareSend) L.masks[lane] = (uint8_t)mask;
-            if (DIL && !TAU0 && a.ema && b0 == 0u && wave == (1u & (rb - 1u))) {     // for the step that receives this subset
-                const uint64_t leaders = lines_of(mask);
-                if (lane == 0u) a.send_lines[tile] = leaders;
-            }
         } else {
             uint32_t count;
             (void)wave_prefix_mask4(mask, count);
@@ -637,9 +623,14 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint32_t tile
     // the local optimizer step needs nothing but the wave's own operands: it runs while the lines
     // for LDS and the other waves' operands are still on their way
     F4 w_hat, m_new, v_new;
-    if (!TAU0 && DIL) local_step<OPT>(a, rep, i, in, w_hat, m_new, v_new);      // (per-replica d: its entries are in registers too)
+    if (!TAU0 && DIL && OPT != kOptNone) local_step<OPT>(a, rep, i, in, w_hat, m_new, v_new);      // (per-replica d: its entries are in registers too)
     lds_dma_wait();
     __syncthreads();
+    constexpr bool kEarlyLocal = !TAU0 && DIL && OPT != kOptNone;
+    if (kEarlyLocal && i < R) {                            // the moments are final: out they go at once
+        if (OPT == kOptSgdMomentum || OPT == kOptAdam) store_f32x4(rep.m + tbase, loff, nvalid, m_new);
+        if (OPT == kOptAdam) store_f32x4(rep.v + tbase, loff, nvalid, v_new);
+    }
     if (!recv_is_send && !kEarlyMasks) finish_subsets();
 
     // ---- old average of the coordinates received now: thread c forms the mean of the coordinate of

@@ -140,7 +140,6 @@ struct am_state {
     uint32_t *next_lines() const { return reinterpret_cast<uint32_t *>(ws + lay.off_next); }
     uint32_t *meta_local(uint32_t slot) const { return reinterpret_cast<uint32_t *>(ws + lay.off_meta + lay.meta_stride * slot); }
     uint32_t *meta_sb(uint32_t slot) const { return reinterpret_cast<uint32_t *>(ws + lay.off_meta + lay.meta_stride * slot + lay.meta_sb_off); }
-    uint64_t *meta_lines(uint32_t slot) const { return reinterpret_cast<uint64_t *>(ws + lay.off_meta + lay.meta_stride * slot + lay.meta_lines_off); }
     float *ring(uint32_t slot) const { return reinterpret_cast<float *>(ws + lay.off_ring + lay.ring_stride * slot); }
 };
 
@@ -270,14 +269,12 @@ am_status fill_averaging(am_state *st, uint64_t t, float lambda_t, const Round &
         a.ring_send = st->ring(r.slot_send);
         a.send_meta = st->meta_local(r.slot_send);
         a.send_sb_base = st->meta_sb(r.slot_send);
-        a.send_lines = st->meta_lines(r.slot_send);
     }
     if (r.recv) {
         a.step_lo[0] = (uint32_t)r.step_recv; a.step_hi[0] = (uint32_t)(r.step_recv >> 32);
         a.ring_recv = st->ring(r.slot_recv);
         a.recv_meta = st->meta_local(r.slot_recv);
         a.recv_sb_base = st->meta_sb(r.slot_recv);
-        a.recv_lines = st->meta_lines(r.slot_recv);
     }
     return AM_OK;
 }

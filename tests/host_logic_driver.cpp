@@ -19,12 +19,12 @@ uint64_t hl_capacity(uint64_t ntiles, double p, uint32_t rb, int by_line, uint64
 }
 
 // out[0..11]: ntiles, nsb, slots, cap_lines, off_flags, off_reduce, off_next, off_meta, meta_stride, off_ring, ring_stride, total
-// out[12..13]: meta_sb_off, meta_lines_off
+// out[12]: meta_sb_off
 void hl_layout(const am_config *c, uint64_t *out)
 {
     const am_host::Layout L = am_host::make_layout(*c);
     const uint64_t v[] = { L.ntiles, L.nsb, L.slots, L.cap_lines, L.off_flags, L.off_reduce, L.off_next, L.off_meta,
-                           L.meta_stride, L.off_ring, L.ring_stride, L.total, L.meta_sb_off, L.meta_lines_off };
+                           L.meta_stride, L.off_ring, L.ring_stride, L.total, L.meta_sb_off };
     for (unsigned k = 0; k < sizeof v / sizeof v[0]; ++k) out[k] = v[k];
 }
 

@@ -87,9 +87,9 @@ def test_workspace_regions_do_not_overlap_and_match_the_library(hl, amlib):
         R = rng.randrange(1, 33)
         cfg = _config(n=n, replicas=R, delay=rng.randrange(0, 9), fraction=rng.choice([1e-6, 0.01, 0.05, 0.5, 1.0]),
                       subset_kind=rng.randrange(0, 2), ring_cap_lines=rng.choice([0, 0, 17, 10 ** 12]))
-        out = (C.c_uint64 * 14)()
+        out = (C.c_uint64 * 13)()
         hl.hl_layout(C.byref(cfg), out)
-        ntiles, nsb, slots, cap, off_flags, off_reduce, off_next, off_meta, meta_stride, off_ring, ring_stride, total, sb_off, lines_off = out
+        ntiles, nsb, slots, cap, off_flags, off_reduce, off_next, off_meta, meta_stride, off_ring, ring_stride, total, sb_off = out
         assert ntiles == -(-n // 256) and nsb == -(-ntiles // 512) and slots == cfg.delay + 1
         rb = min(8, 1 << (R - 1).bit_length()); nblocks = -(-R // rb)
         if cfg.ring_cap_lines:
@@ -97,7 +97,7 @@ def test_workspace_regions_do_not_overlap_and_match_the_library(hl, amlib):
         regions = [(off_flags, 256), (off_reduce, 32 * 1024 * 8), (off_next, ntiles * 4)]
         for s in range(slots + 1):
             base = off_meta + s * meta_stride
-            regions += [(base, ntiles * 4), (base + sb_off, (nsb + 1) * 4), (base + lines_off, ntiles * 8)]
+            regions += [(base, ntiles * 4), (base + sb_off, (nsb + 1) * 4)]
         for s in range(slots):
             regions.append((off_ring + s * ring_stride, cap * 128 * nblocks))
         regions.sort()

@@ -51,7 +51,7 @@ def test_workspace_bytes_and_capacity_formula(amlib):
     cap_lines = math.ceil(ntiles * mean + 12 * math.sqrt(ntiles * var)) + 64
     ring = (tau + 1) * cap_lines * 32 * 4
     b = am.workspace_bytes(am.make_config(n, R, delay=tau, fraction=p))
-    tables = (tau + 2) * ntiles * 12 + ntiles * 4                 # per slot (and one spare): 4 + 8 bytes per tile; next step's sizes
+    tables = (tau + 2) * ntiles * 4 + ntiles * 4                  # per slot (and one spare): 4 bytes per tile; next step's sizes
     assert ring + tables <= b < ring + tables + (1 << 20)
     assert 3.5 < mean < 3.7                                        # 12.8 values of 8 replicas: about 3.6 lines a tile
     # 16 replicas = two blocks of 8, each with its own lines
