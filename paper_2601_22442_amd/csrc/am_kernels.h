@@ -163,6 +163,8 @@ struct StepArgs {
     uint32_t do_send, do_recv, ema, same_slot;     // ema: a correction vector d is kept; same_slot: tau = 0,
                                                    // the average is of this step's w^
     uint32_t do_next;                              // also count the lines each tile will send next step
+    uint32_t dense_w;                              // averaging alone: read every line of w at once (most lines hold a selected
+                                                   // coordinate anyway) instead of waiting for the masks to name the lines
     uint32_t msg_dtype;                            // precision of the exchanged values: 0 fp32, 1 bf16, 2 E4M3
     uint32_t cap_lines;                            // lines (of 32 floats) per block in a ring slot
     const uint32_t *send_meta, *send_sb_base;      // tile's word: lines << 24 | offset in its superblock; first line = sb_base[tile >> 9] + offset
@@ -267,6 +269,7 @@ __device__ __forceinline__ void wave_lds_sync()
 struct GroupSubsets {
     uint32_t mask_send, mask_recv;      // bit j: coordinate 4*group + j is sent / received now
     uint32_t rank_send, rank_recv;      // rank of the first such coordinate among those of the tile
+    bool dense_w;                       // averaging alone: w is already in registers
     bool line_recv;                     // the 128-byte line of a per-replica array (8 lanes) holding the group receives something
     uint32_t d_slot;                    // interleaved d: float offset, in the LDS staging area, of the group's first entry
 };
@@ -305,7 +308,7 @@ __device__ __forceinline__ void load_group_sparse(const StepArgs &a, uint32_t i,
                                                   const GroupSubsets &s, GroupIn &in)
 {
     if (!DIL && a.ema && s.line_recv) in.d = load_f32x4(a.d[i] + tbase, loff, nvalid);
-    if (OPT == kOptNone && (s.mask_send != 0u || s.line_recv)) in.w = load_f32x4(a.rep[8u * (i >> a.rb_shift) + (i & (a.rb - 1u))].w + tbase, loff, nvalid);
+    if (OPT == kOptNone && !s.dense_w && (s.mask_send != 0u || s.line_recv)) in.w = load_f32x4(a.rep[8u * (i >> a.rb_shift) + (i & (a.rb - 1u))].w + tbase, loff, nvalid);
 }
 
 // Replica i (slot `slot` of its block) of one group, from loaded operands to stored results.
@@ -483,6 +486,8 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint32_t tile
     // replica, whose values its wave loads and never uses -- with a condition the compiler parks
     // the conversions of the loaded values, and with them a wait for memory, right behind the loads)
     if (OPT != kOptNone) load_group<OPT, GRAD_BF16>(rep, tbase, loff, nvalid, in);
+    const bool dense_w = OPT == kOptNone && !TAU0 && a.dense_w != 0u;
+    if (dense_w && i < R) in.w = load_f32x4(rep.w + tbase, loff, nvalid);      // (the averaging-only call leaves the records of absent replicas empty)
     __builtin_amdgcn_sched_barrier(0);
 
     // ---- subsets: bit j of a lane's mask = coordinate 4 group + j is received / sent now.
@@ -491,6 +496,7 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint32_t tile
     GroupSubsets s;
     s.mask_send = s.mask_recv = s.rank_send = s.rank_recv = s.d_slot = 0;
     s.line_recv = false;
+    s.dense_w = dense_w;
     const uint32_t lpl = 8u >> sh;                                         // lanes (groups) per 128-byte line of d
     const uint32_t leader = lane & ~(lpl - 1u);
     // interleaved d: the lines of the tile that hold a received coordinate go straight into LDS, requested
@@ -582,7 +588,8 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint32_t tile
         }
     };
 
-    if (kEarlyMasks && !recv_is_send) {                    // averaging only: masks through LDS, then the loads they name
+    const bool early_masks = kEarlyMasks && !(DIL && dense_w);     // (nothing left for the masks to steer: one barrier fewer)
+    if (early_masks && !recv_is_send) {                    // averaging only: masks through LDS, then the loads they name
         __syncthreads();
         finish_subsets();
         if (i < R) load_group_sparse<OPT, DIL>(a, i, tbase, loff, nvalid, s, in);
@@ -631,7 +638,7 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint32_t tile
         if (OPT == kOptSgdMomentum || OPT == kOptAdam) store_f32x4(rep.m + tbase, loff, nvalid, m_new);
         if (OPT == kOptAdam) store_f32x4(rep.v + tbase, loff, nvalid, v_new);
     }
-    if (!recv_is_send && !kEarlyMasks) finish_subsets();
+    if (!recv_is_send && !early_masks) finish_subsets();
 
     // ---- old average of the coordinates received now: thread c forms the mean of the coordinate of
     //      rank c once for the whole workgroup (in fp64, in replica order); after one more barrier every

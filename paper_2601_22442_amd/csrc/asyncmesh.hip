@@ -635,6 +635,9 @@ am_status am_sparse_average(am_state *st, uint64_t t, float lambda_t)
         std::memset(&a, 0, sizeof a);
         for (uint32_t i = 0; i < st->cfg.replicas; ++i) a.rep[8u * (i / st->lay.blocks.rb) + i % st->lay.blocks.rb].w = st->w[i];
         if (am_status s = fill_averaging(st, t, lambda_t, r, a)) return s;
+        // more than half of the lines of w hold a selected coordinate: read them all, without waiting for the masks
+        a.dense_w = am_host::touched_line_fraction(st->cfg.fraction, st->cfg.subset_granule == 32,
+                                                   st->cfg.subset_kind == AM_SUBSET_STRATIFIED ? am_host::stratified_block(st->cfg.fraction) : 0) > 0.5;
         if (am_status s = launch_step_layout<am::kOptNone, false, am::kFwdNone>(st, a)) return s;
     }
     st->last_t = t;

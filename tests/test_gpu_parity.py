@@ -533,6 +533,7 @@ def test_largest_stage_the_library_accepts(amlib):
     (1, 1, 0, 1, 1.0, O.CORR_EMA), (257, 2, 1, 1, 0.5, O.CORR_EMA), (10_007, 3, 0, 1, 0.2, O.CORR_EMA),
     (10_007, 4, 2, 1, 0.05, O.CORR_EMA), (10_007, 5, 1, 2, 0.3, O.CORR_NONE), (131_072 + 9, 8, 3, 1, 0.05, O.CORR_EMA),
     (50_000, 16, 1, 1, 1.0, O.CORR_EMA), (50_000, 32, 2, 1, 0.01, O.CORR_EMA), (50_000, 7, 1, 1, EMPTY_P, O.CORR_EMA),
+    (50_000, 8, 1, 1, 0.0215, O.CORR_EMA), (50_000, 8, 1, 1, 0.0213, O.CORR_EMA),      # either side of where w is read whole
 ])
 @both_layouts
 def test_sparse_average_alone(amlib, n, R, tau, K, p, corr, d_layout):
