@@ -43,7 +43,7 @@ DESCRIPTION = {
 # figures were measured on and by (workload, layout of the EMA vectors): a library built from other
 # sources gets no traffic figure from here.
 MEASURED_TRAFFIC = {
-    "source_hash": "5721e82769729c39",
+    "source_hash": "88f5376c61f9d809",
     "bytes": {"stage125m/interleaved": 34.24e9, "stage125m/per-replica": 39.23e9,
               "bf16/interleaved": 57.54e9, "model1b/interleaved": 285.41e9},
 }
@@ -174,6 +174,9 @@ def main():
                     help="1: coordinates drawn independently (the paper); 32: variant, whole 128-byte lines drawn")
     ap.add_argument("--subset-kind", default="bernoulli", choices=("bernoulli", "stratified"),
                     help="bernoulli: independent draws (the paper); stratified: variant, one coordinate per block of round(1/p)")
+    ap.add_argument("--averaging-only", action="store_true",
+                    help="time am_sparse_average (the averaging alone, on weights the caller steps itself) instead of the "
+                         "fused step; not the headline metric, no CPU leg")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (replicas are simulated as HBM-resident copies on it); "
@@ -211,6 +214,8 @@ def main():
     st = am.init_state(cfg, None)
     nsets = 1 if n * R * 4 > 24e9 else 2        # two gradient sets per replica, cycled (traffic per step is unchanged); one where two do not fit
     gdt = torch.bfloat16 if w["bf16"] else torch.float32
+    if args.averaging_only:
+        nsets = 0
     gsets = [[torch.empty(n, dtype=gdt, device=dev) for _ in range(R)] for _ in range(nsets)]
     w_pool = torch.from_numpy(w_pool_host).to(dev)
     for i in range(R):
@@ -221,11 +226,18 @@ def main():
             fill_tiled(torch, gsets[s][i], torch.from_numpy(pools[i]).to(dev), (7919 * (i + 1) * (s + 1)) % pool_n)
     torch.cuda.synchronize()
 
+    if args.averaging_only:
+        def one_step(t):
+            st.sparse_average(t, 0.5)
+    else:
+        def one_step(t):
+            st.step(t, gsets[t % nsets], 3e-4, 0.5)
+
     warm = max(args.warmup, tau + 1)          # timed region starts with send and receive both live
     t = 0
     for _ in range(warm):
         t += 1
-        st.step(t, gsets[t % nsets], 3e-4, 0.5)
+        one_step(t)
     torch.cuda.synchronize()
 
     # exactly args.steps timed steps, as up to REPEATS consecutive segments
@@ -236,23 +248,38 @@ def main():
     for k in seg_steps:
         torch.cuda.synchronize()
         t0 = time.perf_counter()
+        events = []
         for _ in range(k):
             t += 1
-            st.step(t, gsets[t % nsets], 3e-4, 0.5)
+            if args.averaging_only:              # events on the library's stream (torch's current one, named at init)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                one_step(t)
+                e1.record()
+                events.append((e0, e1))
+            else:
+                one_step(t)
         torch.cuda.synchronize()
         seg_ms.append((time.perf_counter() - t0) * 1e3 / k)
-        launch_ms += st.get_profile_times()          # HIP events around each launch of the fused kernel, on its stream
+        if args.averaging_only:                  # the whole call: offsets pass + scan + k_average
+            launch_ms += [e0.elapsed_time(e1) for e0, e1 in events]
+        else:
+            launch_ms += st.get_profile_times()      # HIP events around each launch of the fused kernel, on its stream
     st.set_profiling(False)
     assert len(launch_ms) == args.steps
     assert st.read_flags() == 0, "a subset overflowed its ring slot"
 
     bpp = algorithmic_bytes_per_param(w)
+    if args.averaging_only:
+        # per selected coordinate and replica: read w^ 4 + write w 4 + sent 4 + received 4 + d 4 + 4 (no d without correction)
+        bpp = (16.0 if args.no_correction else 24.0) * p
     bytes_per_launch = bpp * R * n
     ms_per_step = statistics.median(seg_ms)
     kernel_ms_mean = sum(launch_ms) / len(launch_ms)
     achieved = bytes_per_launch / (kernel_ms_mean * 1e-3) / 1e9
     out = {
-        "metric": "fused AsyncMesh step: params/s and achieved HBM GB/s (% peak), 125M stage",
+        "metric": ("am_sparse_average alone: params/s and achieved HBM GB/s (% peak)" if args.averaging_only else
+                   "fused AsyncMesh step: params/s and achieved HBM GB/s (% peak), 125M stage"),
         "value": R * n / (ms_per_step * 1e-3),
         "unit": "params/s",
         "n_gpus": 1, "steps": args.steps, "warmup": warm, "ms_per_step": ms_per_step,
@@ -268,7 +295,7 @@ def main():
                    "subset_granule": args.subset_granule, "subset_kind": args.subset_kind, "bf16": w["bf16"], "algorithmic_bytes_per_param": bpp},
         "step_GBps": bytes_per_launch / (ms_per_step * 1e-3) / 1e9,
         "step_frac_of_hbm_peak": bytes_per_launch / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-        "roofline": {"kernel": "k_step", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS,
+        "roofline": {"kernel": "k_average (+ offsets pass)" if args.averaging_only else "k_step", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
                      "kernel_ms": kernel_ms_mean, "kernel_ms_median": statistics.median(launch_ms),
                      "kernel_ms_min": min(launch_ms), "kernel_ms_max": max(launch_ms), "launches": len(launch_ms),
@@ -277,12 +304,21 @@ def main():
     default_settings = (p == WORKLOADS[args.workload]["p"] and tau == WORKLOADS[args.workload]["tau"] and args.avg_interval == 1
                         and not args.no_correction and args.subset_granule == 1 and args.subset_kind == "bernoulli")
     traffic = MEASURED_TRAFFIC["bytes"].get(f"{args.workload}/{args.d_layout}")
+    if args.averaging_only:
+        # what whole 128-byte lines make of it: every line of w (and of a per-replica d) that holds a selected
+        # coordinate is read and rewritten, ring lines and interleaved d lines hold 32 / rb coordinates
+        rb = min(8, 1 << max(0, R - 1).bit_length())
+        q_w = 1.0 - (1.0 - p) ** 32
+        q_d = 0.0 if args.no_correction else (1.0 - (1.0 - p) ** (32 // rb) if args.d_layout == "interleaved" else q_w)
+        out["config"]["entry"] = "am_sparse_average"
+        out["roofline"]["line_granular_bytes_per_launch"] = R * n * 4.0 * (2.0 * q_w + 2.0 * q_d + 2.0 * p)
+        traffic = None
     if traffic is not None and default_settings and MEASURED_TRAFFIC["source_hash"] == digest:
         # counter-measured bytes of this very configuration and this very library, over this run's kernel time
         out["roofline"]["traffic"] = traffic
         out["roofline"]["traffic_from_profile_GBps"] = traffic / (kernel_ms_mean * 1e-3) / 1e9
         out["roofline"]["traffic_from_profile_frac"] = traffic / (kernel_ms_mean * 1e-3) / 1e9 / HBM_PEAK_GBPS
-    if not args.skip_cpu:
+    if not args.skip_cpu and not args.averaging_only:
         out["cpu_baseline"] = cpu_baseline(w, args, st, gsets, t, w_pool_host)
     print(json.dumps(out))
 

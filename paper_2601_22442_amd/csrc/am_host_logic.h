@@ -76,15 +76,6 @@ inline uint64_t slot_capacity_lines(uint64_t ntiles, double p, uint32_t rb, bool
     return cap >= (double)all ? all : (uint64_t)cap;
 }
 
-// Fraction of the 128-byte lines (32 coordinates) of a per-replica array that hold a selected coordinate.
-inline double touched_line_fraction(double p, bool by_line, uint64_t strat_block)
-{
-    if (p >= 1.0) return 1.0;
-    if (by_line) return p;
-    if (strat_block) return strat_block <= am::kLineFloats ? 1.0 : (double)am::kLineFloats / (double)strat_block;
-    return 1.0 - std::pow(1.0 - p, (double)am::kLineFloats);
-}
-
 // workspace = [flags 256 B][reduction partials 32 x 1024 doubles][next_lines u32[ntiles]][meta x (slots + 1)][ring values x slots]
 //   meta = tile words u32[ntiles] | sb_base u32[nsb + 1]      (the extra block serves am_subset_indices)
 //   ring slot = nblocks * cap_lines * 32 fp32: [block][line][32], a line = [coordinate][replica in block]

@@ -163,8 +163,6 @@ struct StepArgs {
     uint32_t do_send, do_recv, ema, same_slot;     // ema: a correction vector d is kept; same_slot: tau = 0,
                                                    // the average is of this step's w^
     uint32_t do_next;                              // also count the lines each tile will send next step
-    uint32_t dense_w;                              // averaging alone: read every line of w at once (most lines hold a selected
-                                                   // coordinate anyway) instead of waiting for the masks to name the lines
     uint32_t msg_dtype;                            // precision of the exchanged values: 0 fp32, 1 bf16, 2 E4M3
     uint32_t cap_lines;                            // lines (of 32 floats) per block in a ring slot
     const uint32_t *send_meta, *send_sb_base;      // tile's word: lines << 24 | offset in its superblock; first line = sb_base[tile >> 9] + offset
@@ -269,7 +267,6 @@ __device__ __forceinline__ void wave_lds_sync()
 struct GroupSubsets {
     uint32_t mask_send, mask_recv;      // bit j: coordinate 4*group + j is sent / received now
     uint32_t rank_send, rank_recv;      // rank of the first such coordinate among those of the tile
-    bool dense_w;                       // averaging alone: w is already in registers
     bool line_recv;                     // the 128-byte line of a per-replica array (8 lanes) holding the group receives something
     uint32_t d_slot;                    // interleaved d: float offset, in the LDS staging area, of the group's first entry
 };
@@ -308,7 +305,7 @@ __device__ __forceinline__ void load_group_sparse(const StepArgs &a, uint32_t i,
                                                   const GroupSubsets &s, GroupIn &in)
 {
     if (!DIL && a.ema && s.line_recv) in.d = load_f32x4(a.d[i] + tbase, loff, nvalid);
-    if (OPT == kOptNone && !s.dense_w && (s.mask_send != 0u || s.line_recv)) in.w = load_f32x4(a.rep[8u * (i >> a.rb_shift) + (i & (a.rb - 1u))].w + tbase, loff, nvalid);
+    if (OPT == kOptNone && (s.mask_send != 0u || s.line_recv)) in.w = load_f32x4(a.rep[8u * (i >> a.rb_shift) + (i & (a.rb - 1u))].w + tbase, loff, nvalid);
 }
 
 // Replica i (slot `slot` of its block) of one group, from loaded operands to stored results.
@@ -447,8 +444,8 @@ __device__ __forceinline__ float replica_mean(const StepArgs &a, const float *re
 // same for every wave of the workgroup, so (fused step) one wave hashes the received subset, one
 // the sent one, one the next step's, and the others read the 4-bit masks from LDS after the barrier
 // they have to pass anyway.  (Where the masks steer loads of per-replica arrays -- the per-replica
-// layout of d, the averaging-only call -- every wave still hashes what it needs itself, so that
-// those loads go out before the barrier.)
+// layout of d -- every wave still hashes the received subset itself, so that those loads go out
+// before the barrier.)
 //
 // FULL = every coordinate of the tile exists (all but possibly the last tile of the stage): all
 // dense accesses are unconditional 128-bit ones.
@@ -461,8 +458,9 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint32_t tile
 {
     // One wave hashes the sent subset for all; so it is with the received subset, unless its masks steer
     // loads of per-replica arrays that should leave before the barrier (per-replica layout of d in the
-    // fused step).  The averaging-only call has no dense loads to wait for anyway: its waves share the
-    // masks through one more barrier and load what the masks name after it.
+    // fused step).  Without an optimizer pass (averaging alone with tau = 0; tau > 0 is k_average's)
+    // there are no dense loads to wait for: the waves share the masks and load what the masks name.
+    static_assert(OPT != kOptNone || TAU0, "averaging alone runs here only with tau = 0");
     constexpr bool kEarlyMasks = OPT == kOptNone;
     constexpr bool kShareRecv = DIL || kEarlyMasks;
     constexpr bool kShareSend = true;
@@ -486,8 +484,6 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint32_t tile
     // replica, whose values its wave loads and never uses -- with a condition the compiler parks
     // the conversions of the loaded values, and with them a wait for memory, right behind the loads)
     if (OPT != kOptNone) load_group<OPT, GRAD_BF16>(rep, tbase, loff, nvalid, in);
-    const bool dense_w = OPT == kOptNone && !TAU0 && a.dense_w != 0u;
-    if (dense_w && i < R) in.w = load_f32x4(rep.w + tbase, loff, nvalid);      // (the averaging-only call leaves the records of absent replicas empty)
     __builtin_amdgcn_sched_barrier(0);
 
     // ---- subsets: bit j of a lane's mask = coordinate 4 group + j is received / sent now.
@@ -496,7 +492,6 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint32_t tile
     GroupSubsets s;
     s.mask_send = s.mask_recv = s.rank_send = s.rank_recv = s.d_slot = 0;
     s.line_recv = false;
-    s.dense_w = dense_w;
     const uint32_t lpl = 8u >> sh;                                         // lanes (groups) per 128-byte line of d
     const uint32_t leader = lane & ~(lpl - 1u);
     // interleaved d: the lines of the tile that hold a received coordinate go straight into LDS, requested
@@ -588,12 +583,7 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint32_t tile
         }
     };
 
-    const bool early_masks = kEarlyMasks && !(DIL && dense_w);     // (nothing left for the masks to steer: one barrier fewer)
-    if (early_masks && !recv_is_send) {                    // averaging only: masks through LDS, then the loads they name
-        __syncthreads();
-        finish_subsets();
-        if (i < R) load_group_sparse<OPT, DIL>(a, i, tbase, loff, nvalid, s, in);
-    } else if (!kShareRecv) {                              // loads of per-replica arrays that the masks steer
+    if (!kShareRecv) {                                     // loads of per-replica arrays that the masks steer
         const uint64_t any_recv = __ballot(s.mask_recv != 0u);
         s.line_recv = ((any_recv >> (lane & ~7u)) & 0xFFull) != 0ull;
         if (i < R) load_group_sparse<OPT, DIL>(a, i, tbase, loff, nvalid, s, in);
@@ -638,7 +628,7 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint32_t tile
         if (OPT == kOptSgdMomentum || OPT == kOptAdam) store_f32x4(rep.m + tbase, loff, nvalid, m_new);
         if (OPT == kOptAdam) store_f32x4(rep.v + tbase, loff, nvalid, v_new);
     }
-    if (!recv_is_send && !early_masks) finish_subsets();
+    if (!recv_is_send) finish_subsets();
 
     // ---- old average of the coordinates received now: thread c forms the mean of the coordinate of
     //      rank c once for the whole workgroup (in fp64, in replica order); after one more barrier every
@@ -717,6 +707,201 @@ k_step(const StepArgs a)
         step_tile<OPT, GRAD_BF16, FWD, DIL, TAU0, true>(a, tile, b0, wave, lane, L);
     else
         step_tile<OPT, GRAD_BF16, FWD, DIL, TAU0, false>(a, tile, b0, wave, lane, L);
+}
+
+// =============================================================================================
+// Averaging alone, tau > 0 (am_sparse_average): steps a3-a8 on weights the caller has already stepped.
+//
+// Only lines that hold a selected coordinate move, so the call lives on how many of those lines are
+// in flight, not on bytes.  The fused kernel's shape (a wave per replica, staging in LDS, four
+// barriers a tile) keeps four tiles per compute unit in flight; here ONE wave owns one (tile, block
+// of replicas) and keeps the block's RB replicas side by side in registers: lane l holds the four
+// coordinates of its group for every replica of the block.  The RB values of a coordinate are one
+// aligned stretch of 4 RB bytes in the ring slot and in the interleaved EMA vector ([coordinate][RB]),
+// so the lane reads and writes them with one or two 128-bit accesses: no LDS, no barrier, two dozen
+// tiles per compute unit in flight.  (Several lanes write parts of one line within a few
+// instructions of each other; these are ordinary cached stores, which the L2 merges.)
+// Arithmetic and its order are those of the fused kernel: mean in fp64 in replica order, rounded to
+// fp32; d <- coef_d d + coef_s (w^ - sent) and w = mean + d in fp64, rounded once each.
+// =============================================================================================
+template <int RB>
+__device__ __forceinline__ void load_block_values(const float *p, float (&x)[RB])
+{
+    if constexpr (RB == 8) {
+        const v4f lo = *reinterpret_cast<const v4f *>(p), hi = *reinterpret_cast<const v4f *>(p + 4);
+        x[0] = lo.x; x[1] = lo.y; x[2] = lo.z; x[3] = lo.w; x[4] = hi.x; x[5] = hi.y; x[6] = hi.z; x[7] = hi.w;
+    } else if constexpr (RB == 4) {
+        const v4f lo = *reinterpret_cast<const v4f *>(p);
+        x[0] = lo.x; x[1] = lo.y; x[2] = lo.z; x[3] = lo.w;
+    } else if constexpr (RB == 2) {
+        const v2f lo = *reinterpret_cast<const v2f *>(p);
+        x[0] = lo.x; x[1] = lo.y;
+    } else {
+        x[0] = p[0];
+    }
+}
+
+template <int RB>
+__device__ __forceinline__ void store_block_values(float *p, const float (&x)[RB])
+{
+    if constexpr (RB == 8) {
+        *reinterpret_cast<v4f *>(p) = v4f{x[0], x[1], x[2], x[3]};
+        *reinterpret_cast<v4f *>(p + 4) = v4f{x[4], x[5], x[6], x[7]};
+    } else if constexpr (RB == 4) {
+        *reinterpret_cast<v4f *>(p) = v4f{x[0], x[1], x[2], x[3]};
+    } else if constexpr (RB == 2) {
+        *reinterpret_cast<v2f *>(p) = v2f{x[0], x[1]};
+    } else {
+        p[0] = x[0];
+    }
+}
+
+// grid = (ceil(tiles / 4), blocks); blockDim = 256: four waves, each with a tile of its own (no LDS).
+// DIL: the EMA vectors are interleaved ([coordinate][RB] per block); else one flat array per replica.
+template <bool DIL, int RB>
+__global__ void __launch_bounds__(256)
+k_average(const StepArgs a)
+{
+    constexpr uint32_t kPerLine = kLineFloats / RB;                        // coordinates a ring line holds
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const uint32_t tile = blockIdx.x * 4u + wave, b0 = blockIdx.y;
+    if (tile >= a.ntiles) return;
+    const uint32_t R = a.replicas;
+    const uint64_t group = (uint64_t)tile * 64u + lane;
+    const uint64_t mu = group * 4u;
+    const int nvalid = mu >= a.n ? 0 : (a.n - mu >= 4u ? 4 : (int)(a.n - mu));
+    const uint64_t tbase = (uint64_t)tile * kTileCoords;
+    const uint32_t loff = lane * 4u;
+    const uint64_t block_floats = (uint64_t)a.cap_lines * kLineFloats;     // one block's part of a ring slot
+
+    // ---- the subsets: bit j of a lane's mask = coordinate 4 group + j is received / sent now
+    uint32_t mask_recv = 0, mask_send = 0;
+    SubsetKey key = a.key;
+    if (a.do_recv) {
+        key.step_lo = a.step_lo[0]; key.step_hi = a.step_hi[0];
+        mask_recv = member_mask(key, group, nvalid);
+    }
+    if (a.do_send) {
+        key.step_lo = a.step_lo[1]; key.step_hi = a.step_hi[1];
+        mask_send = member_mask(key, group, nvalid);
+    }
+    if (a.do_next && b0 == 0u) {                                           // how many lines the tile sends next step
+        key.step_lo = a.step_lo[2]; key.step_hi = a.step_hi[2];
+        uint32_t count;
+        (void)wave_prefix_mask4(member_mask(key, group, nvalid), count);
+        if (lane == 0) a.next_lines[tile] = (count * RB + kLineFloats - 1u) / kLineFloats;
+    }
+
+    // ---- where the tile's lines sit in the two slots; a tile whose lines would pass the slot
+    //      capacity is left out, at send and at receive alike
+    uint32_t word_s = 0, base_s = 0, word_r = 0, base_r = 0;
+    if (a.do_send) { word_s = uniform_load(a.send_meta, tile); base_s = uniform_load(a.send_sb_base, tile / kTilesPerSuperblock); }
+    if (a.do_recv) { word_r = uniform_load(a.recv_meta, tile); base_r = uniform_load(a.recv_sb_base, tile / kTilesPerSuperblock); }
+    const uint32_t first_s = base_s + (word_s & 0xFFFFFFu), first_r = base_r + (word_r & 0xFFFFFFu);
+    uint32_t lines_s = word_s >> 24, lines_r = word_r >> 24;
+    if ((uint64_t)first_s + lines_s > a.cap_lines) { lines_s = 0; mask_send = 0u; }
+    if ((uint64_t)first_r + lines_r > a.cap_lines) { lines_r = 0; mask_recv = 0u; }
+
+    uint32_t count_send, count_recv;
+    const uint32_t rank_send = wave_prefix_mask4(mask_send, count_send);
+    const uint32_t rank_recv = wave_prefix_mask4(mask_recv, count_recv);
+    const uint64_t any_recv = __ballot(mask_recv != 0u);
+    const bool line_recv = ((any_recv >> (lane & ~7u)) & 0xFFull) != 0ull;    // my 128-byte line of a per-replica array receives
+    const bool need_w = mask_send != 0u || line_recv;
+
+    // ---- the weights (and, per-replica layout, the EMA entries) of the block's replicas
+    F4 w[RB], dv[RB];
+#pragma unroll
+    for (int k = 0; k < RB; ++k) {
+        const uint32_t i = b0 * RB + k;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) w[k].v[j] = dv[k].v[j] = 0.f;         // (an absent replica sends zeros)
+        if (i < R && need_w) w[k] = load_f32x4(a.rep[8u * b0 + k].w + tbase, loff, nvalid);
+        if (!DIL && a.ema && i < R && line_recv) dv[k] = load_f32x4(a.d[i] + tbase, loff, nvalid);
+    }
+
+    // ---- send: the RB values of a selected coordinate, side by side, at the coordinate's rank;
+    //      the rest of the tile's last line is zero
+    if (a.do_send && lines_s != 0u) {
+        float *slot = a.ring_send + b0 * block_floats + (uint64_t)first_s * kLineFloats;
+        uint32_t c = rank_send;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (((mask_send >> j) & 1u) && c < lines_s * kPerLine) {       // (the rank is below that by construction of the table)
+                float x[RB];
+#pragma unroll
+                for (int k = 0; k < RB; ++k) x[k] = w[k].v[j];
+                store_block_values<RB>(slot + (uint64_t)c * RB, x);
+                ++c;
+            }
+        }
+        if (count_send + lane < lines_s * kPerLine) {                      // fewer than kPerLine <= 32 lanes
+            float x[RB];
+#pragma unroll
+            for (int k = 0; k < RB; ++k) x[k] = 0.f;
+            store_block_values<RB>(slot + (uint64_t)(count_send + lane) * RB, x);
+        }
+    }
+
+    // ---- receive: old average of what every replica sent (+ EMA of staleness)
+    if (count_recv != 0u) {                                                // same for the whole wave
+        const float *slot = a.ring_recv + (uint64_t)first_r * kLineFloats;
+        const double inv_replicas = 1.0 / (double)R;
+        uint32_t c = rank_recv;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (((mask_recv >> j) & 1u) && c < lines_r * kPerLine) {       // (as above)
+                double sum = 0.;
+                float own[RB];
+                for (uint32_t b = 0; b < a.nblocks; ++b) {
+                    float x[RB];
+                    load_block_values<RB>(slot + b * block_floats + (uint64_t)c * RB, x);
+                    const uint32_t nrep = R - b * RB;                      // replicas present in this block (>= RB: all)
+#pragma unroll
+                    for (int k = 0; k < RB; ++k) {
+                        if (b == b0) own[k] = x[k];                        // my own staleness term takes the exact value
+                        const float q = a.msg_dtype != 0u ? quantize_message(x[k], a.msg_dtype) : x[k];
+                        if ((uint32_t)k < nrep) sum += (double)q;
+                    }
+                }
+                const float abar = (float)(sum * inv_replicas);
+                if (a.ema) {
+                    float d_new[RB];
+                    float *dp = nullptr;
+                    if (DIL) {
+                        dp = a.d[b0] + (tbase + loff + (uint32_t)j) * RB;
+                        load_block_values<RB>(dp, d_new);
+                    } else {
+#pragma unroll
+                        for (int k = 0; k < RB; ++k) d_new[k] = dv[k].v[j];
+                    }
+#pragma unroll
+                    for (int k = 0; k < RB; ++k) {
+                        d_new[k] = (float)fma(a.coef_d, (double)d_new[k], a.coef_s * ((double)w[k].v[j] - (double)own[k]));
+                        w[k].v[j] = (float)((double)abar + (double)d_new[k]);
+                        if (!DIL) dv[k].v[j] = d_new[k];
+                    }
+                    if (DIL) store_block_values<RB>(dp, d_new);
+                } else {
+#pragma unroll
+                    for (int k = 0; k < RB; ++k) w[k].v[j] = abar;
+                }
+                ++c;
+            }
+        }
+    }
+
+    // ---- only lines that received are rewritten
+    if (line_recv) {
+#pragma unroll
+        for (int k = 0; k < RB; ++k) {
+            const uint32_t i = b0 * RB + k;
+            if (i >= R) continue;
+            store_f32x4(a.rep[8u * b0 + k].w + tbase, loff, nvalid, w[k]);
+            if (!DIL && a.ema) store_f32x4(a.d[i] + tbase, loff, nvalid, dv[k]);
+        }
+    }
 }
 
 // =============================================================================================

@@ -220,8 +220,13 @@ am_status launch_step_tau(am_state *st, const am::StepArgs &a)
     const bool tau0 = a.do_recv && a.same_slot;
     const dim3 grid(st->lay.ntiles, tau0 ? 1u : B.nblocks), block(64u * B.rb);
     const size_t lds = (size_t)am::step_lds_floats(B.rb, B.nblocks, DIL) * sizeof(float);
-    if (tau0) am::k_step<OPT, GBF, FWD, DIL, true><<<grid, block, lds, st->stream>>>(a);
-    else am::k_step<OPT, GBF, FWD, DIL, false><<<grid, block, lds, st->stream>>>(a);
+    if constexpr (OPT == am::kOptNone) {                   // averaging alone: only tau = 0 runs here (else k_average)
+        if (!tau0) return fail(AM_EINVAL, "internal: averaging-only launch of the fused kernel with tau > 0");
+        am::k_step<OPT, GBF, FWD, DIL, true><<<grid, block, lds, st->stream>>>(a);
+    } else {
+        if (tau0) am::k_step<OPT, GBF, FWD, DIL, true><<<grid, block, lds, st->stream>>>(a);
+        else am::k_step<OPT, GBF, FWD, DIL, false><<<grid, block, lds, st->stream>>>(a);
+    }
     AM_HIP(hipGetLastError());
     return AM_OK;
 }
@@ -245,6 +250,22 @@ template <int OPT>
 am_status launch_step_grad(am_state *st, const am::StepArgs &a)
 {
     return st->cfg.grad_dtype == AM_BF16 ? launch_step_fwd<OPT, true>(st, a) : launch_step_fwd<OPT, false>(st, a);
+}
+
+// The averaging-only kernel (tau > 0): one wave per (tile, block of replicas).
+template <bool DIL>
+am_status launch_average(am_state *st, const am::StepArgs &a)
+{
+    const am_host::Blocks &B = st->lay.blocks;
+    const dim3 grid((st->lay.ntiles + 3u) / 4u, B.nblocks), block(256);
+    switch (B.rb) {
+    case 8: am::k_average<DIL, 8><<<grid, block, 0, st->stream>>>(a); break;
+    case 4: am::k_average<DIL, 4><<<grid, block, 0, st->stream>>>(a); break;
+    case 2: am::k_average<DIL, 2><<<grid, block, 0, st->stream>>>(a); break;
+    default: am::k_average<DIL, 1><<<grid, block, 0, st->stream>>>(a); break;
+    }
+    AM_HIP(hipGetLastError());
+    return AM_OK;
 }
 
 // The averaging part of the kernel arguments for step t; launches the offsets pass when t sends.
@@ -629,16 +650,26 @@ am_status am_sparse_average(am_state *st, uint64_t t, float lambda_t)
     if (t != st->last_t + 1) return fail(AM_EORDER, "step %llu after step %llu", (unsigned long long)t, (unsigned long long)st->last_t);
     if (!(lambda_t >= 0.f && lambda_t <= 1.f)) return fail(AM_EINVAL, "lambda_t=%g not in [0, 1]", lambda_t);
     const Round r = plan_round(st, t);
+    const bool do_next = (t + 1) % st->cfg.avg_interval == 0;      // the next step sends: size its tiles on the way
     if (r.send) {
-        // the fused kernel with the optimizer pass left out: w^ = w, only touched lines move
         am::StepArgs a;
         std::memset(&a, 0, sizeof a);
         for (uint32_t i = 0; i < st->cfg.replicas; ++i) a.rep[8u * (i / st->lay.blocks.rb) + i % st->lay.blocks.rb].w = st->w[i];
         if (am_status s = fill_averaging(st, t, lambda_t, r, a)) return s;
-        // more than half of the lines of w hold a selected coordinate: read them all, without waiting for the masks
-        a.dense_w = am_host::touched_line_fraction(st->cfg.fraction, st->cfg.subset_granule == 32,
-                                                   st->cfg.subset_kind == AM_SUBSET_STRATIFIED ? am_host::stratified_block(st->cfg.fraction) : 0) > 0.5;
-        if (am_status s = launch_step_layout<am::kOptNone, false, am::kFwdNone>(st, a)) return s;
+        a.do_next = do_next;
+        if (do_next) {
+            a.step_lo[2] = (uint32_t)(t + 1); a.step_hi[2] = (uint32_t)((t + 1) >> 32);
+            a.next_lines = st->next_lines();
+        }
+        const bool dil = st->cfg.d_layout == AM_D_INTERLEAVED && a.ema;
+        if (r.recv && r.same_slot) {
+            // tau = 0, the average is of this call's own values: the fused kernel with the optimizer pass
+            // left out (w^ = w), whose workgroups see every replica of a tile
+            if (am_status s = launch_step_layout<am::kOptNone, false, am::kFwdNone>(st, a)) return s;
+        } else {
+            if (am_status s = dil ? launch_average<true>(st, a) : launch_average<false>(st, a)) return s;
+        }
+        if (do_next) st->next_lines_step = t + 1;
     }
     st->last_t = t;
     return AM_OK;

@@ -18,8 +18,6 @@ uint64_t hl_capacity(uint64_t ntiles, double p, uint32_t rb, int by_line, uint64
     return am_host::slot_capacity_lines(ntiles, p, rb, by_line != 0, strat_block);
 }
 
-double hl_touched_lines(double p, int by_line, uint64_t strat_block) { return am_host::touched_line_fraction(p, by_line != 0, strat_block); }
-
 // out[0..11]: ntiles, nsb, slots, cap_lines, off_flags, off_reduce, off_next, off_meta, meta_stride, off_ring, ring_stride, total
 // out[12]: meta_sb_off
 void hl_layout(const am_config *c, uint64_t *out)

@@ -529,31 +529,110 @@ def test_largest_stage_the_library_accepts(amlib):
 # --------------------------------------------------------------------------------------------
 # stand-alone entry points
 # --------------------------------------------------------------------------------------------
-@pytest.mark.parametrize("n,R,tau,K,p,corr", [
-    (1, 1, 0, 1, 1.0, O.CORR_EMA), (257, 2, 1, 1, 0.5, O.CORR_EMA), (10_007, 3, 0, 1, 0.2, O.CORR_EMA),
-    (10_007, 4, 2, 1, 0.05, O.CORR_EMA), (10_007, 5, 1, 2, 0.3, O.CORR_NONE), (131_072 + 9, 8, 3, 1, 0.05, O.CORR_EMA),
-    (50_000, 16, 1, 1, 1.0, O.CORR_EMA), (50_000, 32, 2, 1, 0.01, O.CORR_EMA), (50_000, 7, 1, 1, EMPTY_P, O.CORR_EMA),
-    (50_000, 8, 1, 1, 0.0215, O.CORR_EMA), (50_000, 8, 1, 1, 0.0213, O.CORR_EMA),      # either side of where w is read whole
-])
-@both_layouts
-def test_sparse_average_alone(amlib, n, R, tau, K, p, corr, d_layout):
-    """The caller runs its own optimizer (here: adds a seeded perturbation to w between calls)."""
-    am = amlib
+def run_average(am, n, R, steps, seed=17, lam=0.5, **kw):
+    """am_sparse_average on weights the caller steps itself (here: a seeded perturbation between the
+    calls), every element of w and d against the oracle after every call."""
+    print(f"case sparse_average n={n} R={R} steps={steps} {kw}", flush=True)
     w0 = np.stack([si.stage_weights(n, 100 + i) for i in range(R)])
-    st, orc = make_pair(am, n, R, w0=w0, delay=tau, avg_interval=K, fraction=p, seed=17, correction=corr,
-                        optimizer=O.OPT_SGD, beta1=0.0, d_layout=d_layout)
-    for t in range(1, 3 * (tau + 1) * K + 2):
-        bump = si.replica_grads(n, R, t, 17)
+    st, orc = make_pair(am, n, R, w0=w0, seed=seed, optimizer=O.OPT_SGD, beta1=0.0, **kw)
+    for t in range(1, steps + 1):
+        bump = si.replica_grads(n, R, t, seed)
         for i in range(R):
             orc.w(i)[:] += bump[i]
             st.w[i] += torch.from_numpy(bump[i]).cuda()
-        st.sparse_average(t, 0.5)
-        orc.sparse_average(t, 0.5)
+        st.sparse_average(t, lam)
+        orc.sparse_average(t, lam)
         for i in range(R):
             assert rel_err(st.w[i].cpu().numpy(), orc.w(i)) < TOL_F32, (t, i)
             if st.d is not None:
                 assert rel_err(st.d[i].cpu().numpy(), orc.d(i)) < TOL_F32, (t, i)
     assert st.read_flags() == 0
+    return st, orc
+
+
+@pytest.mark.parametrize("n,R,tau,K,p,corr", [
+    (1, 1, 0, 1, 1.0, O.CORR_EMA), (257, 2, 1, 1, 0.5, O.CORR_EMA), (10_007, 3, 0, 1, 0.2, O.CORR_EMA),
+    (10_007, 4, 2, 1, 0.05, O.CORR_EMA), (10_007, 5, 1, 2, 0.3, O.CORR_NONE), (131_072 + 9, 8, 3, 1, 0.05, O.CORR_EMA),
+    (50_000, 16, 1, 1, 1.0, O.CORR_EMA), (50_000, 32, 2, 1, 0.01, O.CORR_EMA), (50_000, 7, 1, 1, EMPTY_P, O.CORR_EMA),
+    (1, 1, 1, 1, 1.0, O.CORR_EMA), (1003, 1, 2, 1, 0.3, O.CORR_EMA), (1003, 8, 2, 1, 0.3, O.CORR_EMA),
+    (40_001, 12, 1, 3, 0.3, O.CORR_EMA), (40_001, 20, 3, 1, 0.1, O.CORR_NONE), (40_001, 9, 0, 2, 0.1, O.CORR_EMA),
+])
+@both_layouts
+def test_sparse_average_alone(amlib, n, R, tau, K, p, corr, d_layout):
+    """The caller runs its own optimizer.  With tau > 0 this is the kernel that keeps a block's replicas
+    side by side in registers; with tau = 0 the fused kernel without its optimizer pass."""
+    run_average(amlib, n, R, 3 * (tau + 1) * K + 2, delay=tau, avg_interval=K, fraction=p, correction=corr, d_layout=d_layout)
+
+
+@pytest.mark.parametrize("msg", [O.MSG_BF16, O.MSG_E4M3])
+@both_layouts
+def test_sparse_average_quantised_exchange(amlib, msg, d_layout):
+    """The mean takes the rounded messages, a replica's own staleness term its exact value."""
+    run_average(amlib, 30_011, 5, 8, delay=2, fraction=0.2, msg_dtype=msg, d_layout=d_layout)
+    run_average(amlib, 30_011, 11, 5, delay=1, fraction=0.2, msg_dtype=msg, d_layout=d_layout)
+
+
+@both_layouts
+def test_sparse_average_eager_correction(amlib, d_layout):
+    run_average(amlib, 25_013, 4, 9, delay=2, fraction=1.0, correction=O.CORR_EAGER, d_layout=d_layout)
+    run_average(amlib, 25_013, 3, 9, delay=1, avg_interval=2, fraction=0.3, correction=O.CORR_EAGER, d_layout=d_layout)
+
+
+def test_sparse_average_delay_changed_at_run_time(amlib):
+    am = amlib
+    n, R = 60_003, 6
+    w0 = np.stack([si.stage_weights(n, 100 + i) for i in range(R)])
+    st, orc = make_pair(am, n, R, w0=w0, delay=3, fraction=0.1, seed=29, optimizer=O.OPT_SGD, beta1=0.0)
+    for t in range(1, 16):
+        if t == 6:
+            st.set_delay(1); orc.set_delay(1)
+        if t == 11:
+            st.set_delay(3); orc.set_delay(3)
+        bump = si.replica_grads(n, R, t, 29)
+        for i in range(R):
+            orc.w(i)[:] += bump[i]
+            st.w[i] += torch.from_numpy(bump[i]).cuda()
+        st.sparse_average(t, 0.5); orc.sparse_average(t, 0.5)
+        for i in range(R):
+            assert rel_err(st.w[i].cpu().numpy(), orc.w(i)) < TOL_F32, (t, i)
+            assert rel_err(st.d[i].cpu().numpy(), orc.d(i)) < TOL_F32, (t, i)
+
+
+@both_layouts
+def test_sparse_average_ring_slot_overflow(amlib, d_layout):
+    """The averaging-only kernel leaves the tiles past a too small slot out at send and receive alike,
+    as the fused one does: the tiles before the first dropped one follow the method, those after
+    the last are never averaged, the flag is raised."""
+    am = amlib
+    n, R, tau, p, seed, steps, cap, rb = 100_003, 4, 1, 0.2, 19, 6, 700, 4
+    w0 = np.stack([si.stage_weights(n, 100 + i) for i in range(R)])
+    cfg = am.make_config(n, R, delay=tau, fraction=p, seed=seed, optimizer=am.OPT_SGD, beta1=0.0, d_layout=d_layout, ring_cap_lines=cap)
+    st = am.init_state(cfg, torch.from_numpy(w0).cuda())
+    full = O.Oracle(n, R, delay=tau, fraction=p, seed=seed, optimizer=O.OPT_SGD, beta1=0.0); full.set_w(w0)
+    never = O.Oracle(n, R, delay=tau, fraction=EMPTY_P, seed=seed, optimizer=O.OPT_SGD, beta1=0.0); never.set_w(w0)
+    first_dropped = []
+    for t in range(1, steps + 1):
+        bump = si.replica_grads(n, R, t, seed)
+        for i in range(R):
+            full.w(i)[:] += bump[i]; never.w(i)[:] += bump[i]
+            st.w[i] += torch.from_numpy(bump[i]).cuda()
+        st.sparse_average(t, 0.5); full.sparse_average(t, 0.5); never.sparse_average(t, 0.5)
+        counts = np.bincount((O.subset(seed, t, n, p) // 256).astype(np.int64), minlength=-(-n // 256))
+        lines = -(-counts * rb // 32)
+        start = np.cumsum(lines) - lines
+        assert (start + lines > cap).any()
+        first_dropped.append(int(np.argmax(start + lines > cap)))
+    lo, hi = min(first_dropped) * 256, (max(first_dropped) + 1) * 256
+    assert 0 < lo <= hi < n - 10_000
+    for i in range(R):
+        for name in ("w", "d"):
+            got = getattr(st, name)[i].cpu().numpy()
+            assert rel_err(got[:lo], getattr(full, name)(i)[:lo]) < TOL_F32, (name, i, "kept tiles")
+            assert rel_err(got[hi:], getattr(never, name)(i)[hi:]) < TOL_F32, (name, i, "dropped tiles")
+    assert st.read_flags() & 1
+    with pytest.raises(am.AsyncMeshError) as e:
+        st.sparse_average(steps + 1, 0.5)
+    assert e.value.status == -6
 
 
 def test_fused_steps_and_stand_alone_averaging_interleaved(amlib):

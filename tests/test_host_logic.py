@@ -22,7 +22,6 @@ def hl(tmp_path_factory):
     L.hl_stratified_block.argtypes = [C.c_double]; L.hl_stratified_block.restype = C.c_uint64
     L.hl_blocks.argtypes = [C.c_uint32] + [C.POINTER(C.c_uint32)] * 3
     L.hl_capacity.argtypes = [C.c_uint64, C.c_double, C.c_uint32, C.c_int, C.c_uint64]; L.hl_capacity.restype = C.c_uint64
-    L.hl_touched_lines.argtypes = [C.c_double, C.c_int, C.c_uint64]; L.hl_touched_lines.restype = C.c_double
     L.hl_layout.argtypes = [C.c_void_p, C.POINTER(C.c_uint64)]
     L.hl_plan_round.argtypes = [C.c_uint64] * 4 + [C.POINTER(C.c_uint64)]
     return L
@@ -78,20 +77,6 @@ def test_slot_capacity_special_cases(hl):
     want = math.ceil(ntiles * 8 * p * rb + 12 * math.sqrt(ntiles * 8 * p * (1 - p)) * rb) + 64
     assert abs(hl.hl_capacity(ntiles, p, rb, 1, 0) - want) <= 1
     assert hl.hl_capacity(1, 0.5, 8, 0, 0) == 64                         # tiny stage: the margin saturates at every line
-
-
-def test_fraction_of_lines_that_hold_a_selected_coordinate(hl):
-    """Decides whether the averaging-only call reads every line of w up front (more than half are needed anyway)."""
-    import numpy as np
-    rng = np.random.default_rng(3)
-    for p in (0.01, 0.0214, 0.05, 0.3):
-        hit = (rng.random((200_000, 32)) < p).any(axis=1).mean()          # brute force over 200,000 lines
-        assert abs(hl.hl_touched_lines(p, 0, 0) - hit) < 4e-3, p
-    assert hl.hl_touched_lines(0.05, 0, 0) > 0.5 > hl.hl_touched_lines(0.02, 0, 0)
-    assert hl.hl_touched_lines(0.3, 1, 0) == 0.3                         # whole lines drawn
-    assert hl.hl_touched_lines(0.05, 0, 20) == 1.0                       # stratified, B = 20 <= 32: every line
-    assert hl.hl_touched_lines(0.01, 0, 100) == 0.32                     # B = 100: 32 of every 100 coordinates share a member's line
-    assert hl.hl_touched_lines(1.0, 0, 0) == 1.0
 
 
 def test_workspace_regions_do_not_overlap_and_match_the_library(hl, amlib):
