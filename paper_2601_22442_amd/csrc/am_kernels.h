@@ -937,35 +937,88 @@ k_lookahead(void *__restrict__ out, const float *__restrict__ w, const float *__
 // =============================================================================================
 struct DiagArgs {
     const float *w[kMaxReplicas];
-    const float *d[kMaxReplicas];      // replica i's entry of coordinate mu is d[i][mu * d_stride]; all NULL when there is no correction vector
+    const float *d[kMaxReplicas];      // d_stride == 1: one array per replica; else one per block of d_stride replicas,
+                                       // [coordinate][d_stride] (padded to whole tiles); all NULL when there is no correction vector
     uint64_t n;
     uint32_t replicas;
     uint32_t has_d;
     uint32_t d_stride;                 // 1 (one array per replica) or the replicas per block (interleaved)
 };
 
-// Workgroup b reduces the coordinates b, b + gridDim, ... (one coordinate per thread per pass) and
-// writes its three partial results; a fixed grid and a fixed order make the result reproducible.
+// The EMA entries of coordinates mu .. mu + 3 of every replica from the interleaved layout: per block
+// the 4 RB values are contiguous (the arrays are padded to whole tiles, so all four coordinates exist).
+template <int RMAX, int RB>
+__device__ __forceinline__ void diag_load_interleaved(const DiagArgs &a, uint64_t mu, F4 (&x)[RMAX])
+{
+#pragma unroll
+    for (int b = 0; b < RMAX / RB; ++b) {
+        if ((uint32_t)(b * RB) >= a.replicas) continue;
+        const v4f *p = reinterpret_cast<const v4f *>(a.d[b] + mu * RB);
+        float t[4 * RB];
+#pragma unroll
+        for (int q = 0; q < RB; ++q) {
+            const v4f u = __builtin_nontemporal_load(p + q);
+            t[4 * q] = u.x; t[4 * q + 1] = u.y; t[4 * q + 2] = u.z; t[4 * q + 3] = u.w;
+        }
+#pragma unroll
+        for (int k = 0; k < RB; ++k)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) x[b * RB + k].v[j] = t[j * RB + k];
+    }
+}
+
+// Every thread takes groups of 4 coordinates (group = thread index, + threads of the grid, ...), holds
+// the group's values of all replicas in registers (RMAX >= replicas of them, all requested before the
+// first is used) and accumulates its three partial results; a fixed grid and a fixed order make the
+// result reproducible.
+template <int RMAX>
 __global__ void __launch_bounds__(256)
 k_diag_partial(const DiagArgs a, double *__restrict__ partial)
 {
     __shared__ double red[3][256];
     double cons = 0., var_sum = 0., var_max = 0.;
-    const uint64_t stride = (uint64_t)gridDim.x * 256u;
-    const double inv_r = 1.0 / (double)a.replicas;
-    for (uint64_t mu = (uint64_t)blockIdx.x * 256u + threadIdx.x; mu < a.n; mu += stride) {
-        double mean = 0.;
-        for (uint32_t i = 0; i < a.replicas; ++i) mean += (double)a.w[i][mu];
-        mean *= inv_r;
-        for (uint32_t i = 0; i < a.replicas; ++i) { const double e = (double)a.w[i][mu] - mean; cons += e * e; }
+    const uint32_t R = a.replicas;
+    const uint64_t stride = (uint64_t)gridDim.x * 256u, ngroups = (a.n + 3u) / 4u;
+    const double inv_r = 1.0 / (double)R;
+    for (uint64_t g = (uint64_t)blockIdx.x * 256u + threadIdx.x; g < ngroups; g += stride) {
+        const uint64_t mu = g * 4u;
+        const int nvalid = a.n - mu >= 4u ? 4 : (int)(a.n - mu);
+        F4 x[RMAX];
+#pragma unroll
+        for (int i = 0; i < RMAX; ++i)
+            if ((uint32_t)i < R) x[i] = load_f32x4(a.w[i], mu, nvalid);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (j >= nvalid) continue;
+            double mean = 0.;
+#pragma unroll
+            for (int i = 0; i < RMAX; ++i) if ((uint32_t)i < R) mean += (double)x[i].v[j];
+            mean *= inv_r;
+#pragma unroll
+            for (int i = 0; i < RMAX; ++i) if ((uint32_t)i < R) { const double e = (double)x[i].v[j] - mean; cons += e * e; }
+        }
         if (a.has_d) {
-            double dm = 0., v = 0.;
-            for (uint32_t i = 0; i < a.replicas; ++i) dm += (double)a.d[i][mu * a.d_stride];
-            dm *= inv_r;
-            for (uint32_t i = 0; i < a.replicas; ++i) { const double e = (double)a.d[i][mu * a.d_stride] - dm; v += e * e; }
-            v *= inv_r;
-            var_sum += v;
-            var_max = v > var_max ? v : var_max;
+#pragma unroll
+            for (int i = 0; i < RMAX; ++i) {
+                if ((uint32_t)i >= R) continue;
+                if (a.d_stride == 1u) x[i] = load_f32x4(a.d[i], mu, nvalid);
+            }
+            if (a.d_stride == 8u) diag_load_interleaved<RMAX, 8>(a, mu, x);
+            else if (a.d_stride == 4u) diag_load_interleaved<RMAX, 4>(a, mu, x);
+            else if (a.d_stride == 2u) diag_load_interleaved<RMAX, 2>(a, mu, x);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (j >= nvalid) continue;
+                double dm = 0., v = 0.;
+#pragma unroll
+                for (int i = 0; i < RMAX; ++i) if ((uint32_t)i < R) dm += (double)x[i].v[j];
+                dm *= inv_r;
+#pragma unroll
+                for (int i = 0; i < RMAX; ++i) if ((uint32_t)i < R) { const double e = (double)x[i].v[j] - dm; v += e * e; }
+                v *= inv_r;
+                var_sum += v;
+                var_max = v > var_max ? v : var_max;
+            }
         }
     }
     red[0][threadIdx.x] = cons; red[1][threadIdx.x] = var_sum; red[2][threadIdx.x] = var_max;

@@ -685,7 +685,9 @@ am_status am_lookahead(void *out, uint32_t out_dtype, const float *w, const floa
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const uint64_t ngroups = (n + 3) / 4;
     const uint64_t blocks_needed = (ngroups + 255) / 256;
-    const uint32_t grid = (uint32_t)(blocks_needed < 256 * 16 ? blocks_needed : 256 * 16);
+    // one group per thread (measured on MI355X: a one-shot grid streams faster than a few resident workgroups
+    // that loop); the kernel's loop takes over only beyond 2^31 - 1 workgroups, which no accepted n reaches
+    const uint32_t grid = (uint32_t)(blocks_needed < 0x7FFFFFFFull ? blocks_needed : 0x7FFFFFFFull);
     if (out_dtype == AM_BF16) am::k_lookahead<true><<<grid, 256, 0, s>>>(out, w, w_prev, n, (double)gamma);
     else am::k_lookahead<false><<<grid, 256, 0, s>>>(out, w, w_prev, n, (double)gamma);
     AM_HIP(hipGetLastError());
@@ -728,14 +730,14 @@ am_status am_diagnostics(am_state *st, double *dev_out3)
     std::memset(&a, 0, sizeof a);
     a.has_d = st->d_arrays != 0;
     a.d_stride = st->d_rb;
-    for (uint32_t i = 0; i < st->cfg.replicas; ++i) {
-        a.w[i] = st->w[i];
-        if (a.has_d) a.d[i] = st->d_rb == 1 ? st->d[i] : st->d[i / st->d_rb] + i % st->d_rb;
-    }
+    for (uint32_t i = 0; i < st->cfg.replicas; ++i) a.w[i] = st->w[i];
+    for (uint32_t k = 0; k < st->d_arrays; ++k) a.d[k] = st->d[k];          // per replica, or (interleaved) per block
     a.n = st->cfg.n; a.replicas = st->cfg.replicas;
-    const uint64_t want = (st->cfg.n + 255) / 256;
-    const uint32_t blocks = (uint32_t)(want < 1024 ? want : 1024);
-    am::k_diag_partial<<<blocks, 256, 0, st->stream>>>(a, st->reduce_partials());
+    const uint64_t want = ((st->cfg.n + 3) / 4 + 255) / 256;               // a thread takes groups of 4 coordinates
+    const uint32_t blocks = (uint32_t)(want < 4096 ? want : 4096);          // 3 doubles each in the partials area (32 x 1024 doubles)
+    if (a.replicas <= 8) am::k_diag_partial<8><<<blocks, 256, 0, st->stream>>>(a, st->reduce_partials());
+    else if (a.replicas <= 16) am::k_diag_partial<16><<<blocks, 256, 0, st->stream>>>(a, st->reduce_partials());
+    else am::k_diag_partial<32><<<blocks, 256, 0, st->stream>>>(a, st->reduce_partials());
     AM_HIP(hipGetLastError());
     am::k_diag_final<<<1, 256, 0, st->stream>>>(st->reduce_partials(), blocks, st->cfg.n, dev_out3);
     AM_HIP(hipGetLastError());

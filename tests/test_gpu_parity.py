@@ -302,17 +302,23 @@ def test_delay_changed_at_run_time(amlib):
         st.set_delay(4)
 
 
-def test_diagnostics(amlib):
-    n, R = 123_457, 5
-    st, orc = make_pair(amlib, n, R, delay=1, fraction=0.3, seed=12)
+@pytest.mark.parametrize("n,R", [(123_457, 5), (1003, 1), (70_001, 2), (70_002, 3), (33_333, 12), (33_331, 20), (10_007, 32)])
+@both_layouts
+def test_diagnostics(amlib, n, R, d_layout):
+    st, orc = make_pair(amlib, n, R, delay=1, fraction=0.3, seed=12, d_layout=d_layout)
     for t in range(1, 6):
         g, gd = grads_for(n, R, t, 12, False)
         st.step(t, gd, 1e-3, 0.5); orc.step(t, g, 1e-3, 0.5)
     cons, vmean, vmax = st.diagnostics()
     ovm, ovx = orc.ema_variance()
-    assert abs(cons - orc.consensus_error()) < 1e-9 * orc.consensus_error()
-    assert abs(vmean - ovm) < 1e-9 * ovm and abs(vmax - ovx) < 1e-9 * ovx
+    assert abs(cons - orc.consensus_error()) <= 1e-9 * orc.consensus_error()
+    assert abs(vmean - ovm) <= 1e-9 * ovm and abs(vmax - ovx) <= 1e-9 * ovx
     assert st.diagnostics() == (cons, vmean, vmax)                 # fixed reduction order
+    if R == 1:
+        assert (cons, vmean, vmax) == (0.0, 0.0, 0.0)              # one replica: nothing to disagree with
+
+
+def test_diagnostics_without_a_correction_vector(amlib):
     st2, orc2 = make_pair(amlib, 1000, 2, delay=1, fraction=0.3, seed=12, correction=O.CORR_NONE)
     assert st2.diagnostics() == (0.0, 0.0, 0.0)                    # identical replicas, no correction vector
 
