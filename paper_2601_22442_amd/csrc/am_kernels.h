@@ -710,7 +710,8 @@ k_step(const StepArgs a)
 }
 
 // =============================================================================================
-// Averaging alone, tau > 0 (am_sparse_average): steps a3-a8 on weights the caller has already stepped.
+// Averaging alone, tau > 0 (am_sparse_average): subset, send, replica mean, EMA correction and scatter
+// (asynchronous sparse averaging equations) on weights the caller has already stepped.
 //
 // Only lines that hold a selected coordinate move, so the call lives on how many of those lines are
 // in flight, not on bytes.  The fused kernel's shape (a wave per replica, staging in LDS, four
