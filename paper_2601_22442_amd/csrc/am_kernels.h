@@ -133,7 +133,7 @@ k_subset_write(SubsetKey key, uint64_t n, uint32_t ntiles, const uint32_t *__res
 // =============================================================================================
 // Fused step kernel
 // =============================================================================================
-enum : int { kOptSgdPlain = 0, kOptSgdMomentum = 1, kOptAdam = 2, kOptNone = 3 };   // kOptNone: w^ = w (averaging only)
+enum : int { kOptSgdPlain = 0, kOptSgdMomentum = 1, kOptAdam = 2 };
 enum : int { kFwdNone = 0, kFwdF32 = 1, kFwdBf16 = 2 };
 
 // What one replica's wave needs to know about its replica: 64 bytes, one scalar load.  The record
@@ -224,18 +224,14 @@ __device__ __forceinline__ void local_step(const StepArgs &a, const ReplicaArgs 
 {
     // A replica that is idle in this tick goes through the same arithmetic with the coefficients of
     // the identity (m' = m, v' = v, w^ = w exactly); its gradient was not loaded.
-    const bool idle = OPT != kOptNone && r.g == nullptr;
-    const double rs = (OPT != kOptNone && a.replica_scale && !idle) ? (double)a.replica_scale[i] : 1.0;
+    const bool idle = r.g == nullptr;
+    const double rs = (a.replica_scale && !idle) ? (double)a.replica_scale[i] : 1.0;
     const double a_m = idle ? 1.0 : a.a_m, b_m = idle ? 0.0 : a.b_m;
     const double a_v = idle ? 1.0 : a.a_v, b_v = idle ? 0.0 : a.b_v;
     const double c_wd = idle ? 0.0 : a.c_wd;
     const double c_g = r.c_g, c_m = r.c_m, c_v = r.c_v;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        if (OPT == kOptNone) {                                 // averaging only: the caller's w is w^
-            w_hat.v[j] = in.w.v[j];
-            continue;
-        }
         const double gj = idle ? 0.0 : rs * (double)in.g.v[j]; // grad_scale is folded into b_m, b_v, c_g; idle: what was loaded is not a gradient
         const double wo = (double)in.w.v[j];
         double step;                                           // what is subtracted besides the decay
@@ -297,15 +293,13 @@ __device__ __forceinline__ void load_group(const ReplicaArgs &r, uint64_t tbase,
     if (OPT == kOptAdam) in.v = load_f32x4(r.v + tbase, loff, nvalid);
 }
 
-// What the averaging alone touches in the per-replica arrays: the EMA entries of a line that
-// receives (per-replica layout of d), and (when there is no optimizer pass that reads w anyway) the
-// weights of a group that sends or whose line receives.
-template <int OPT, bool DIL>
+// What the averaging touches in the per-replica arrays besides the dense operands: the EMA entries of
+// a line that receives (per-replica layout of d).
+template <bool DIL>
 __device__ __forceinline__ void load_group_sparse(const StepArgs &a, uint32_t i, uint64_t tbase, uint32_t loff, int nvalid,
                                                   const GroupSubsets &s, GroupIn &in)
 {
     if (!DIL && a.ema && s.line_recv) in.d = load_f32x4(a.d[i] + tbase, loff, nvalid);
-    if (OPT == kOptNone && (s.mask_send != 0u || s.line_recv)) in.w = load_f32x4(a.rep[8u * (i >> a.rb_shift) + (i & (a.rb - 1u))].w + tbase, loff, nvalid);
 }
 
 // Replica i (slot `slot` of its block) of one group, from loaded operands to stored results.
@@ -316,7 +310,7 @@ __device__ __forceinline__ void step_replica(const StepArgs &a, const ReplicaArg
                                              F4 &w_hat, F4 &m_new, F4 &v_new, const float *recv_block, const TileLds &L)
 {
     const uint32_t rb = a.rb;
-    if (TAU0 || !DIL || OPT == kOptNone) local_step<OPT>(a, r, i, in, w_hat, m_new, v_new);      // (else: done by the caller while it waited)
+    if (TAU0 || !DIL) local_step<OPT>(a, r, i, in, w_hat, m_new, v_new);      // (else: done by the caller while it waited)
     if (TAU0 || !DIL) {                                    // the moments are final: out they go, before the averaging needs registers
         if (OPT == kOptSgdMomentum || OPT == kOptAdam) store_f32x4(r.m + tbase, loff, nvalid, m_new);
         if (OPT == kOptAdam) store_f32x4(r.v + tbase, loff, nvalid, v_new);
@@ -364,10 +358,6 @@ __device__ __forceinline__ void step_replica(const StepArgs &a, const ReplicaArg
     }
     if (!DIL && a.ema && s.line_recv) store_f32x4(a.d[i] + tbase, loff, nvalid, in.d);
 
-    if (OPT == kOptNone) {                                 // averaging only: rewrite just the lines that receive
-        if (s.line_recv) store_f32x4(r.w + tbase, loff, nvalid, w_new);
-        return;
-    }
     store_f32x4(r.w + tbase, loff, nvalid, w_new);
     if (FWD != kFwdNone) {
         // fwd = w + gamma (w^ - w_before): product and sum rounded separately in fp64, then ONE
@@ -458,11 +448,8 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint32_t tile
 {
     // One wave hashes the sent subset for all; so it is with the received subset, unless its masks steer
     // loads of per-replica arrays that should leave before the barrier (per-replica layout of d in the
-    // fused step).  Without an optimizer pass (averaging alone with tau = 0; tau > 0 is k_average's)
-    // there are no dense loads to wait for: the waves share the masks and load what the masks name.
-    static_assert(OPT != kOptNone || TAU0, "averaging alone runs here only with tau = 0");
-    constexpr bool kEarlyMasks = OPT == kOptNone;
-    constexpr bool kShareRecv = DIL || kEarlyMasks;
+    // fused step).
+    constexpr bool kShareRecv = DIL;
     constexpr bool kShareSend = true;
     const uint32_t R = a.replicas, rb = a.rb, sh = a.rb_shift;
     const uint32_t flat = wave * 64u + lane;                               // 64 rb threads; thread f owns 16-byte chunk f
@@ -483,7 +470,7 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint32_t tile
     // (no condition on i < R: the record of an absent replica names the arrays of the block's first
     // replica, whose values its wave loads and never uses -- with a condition the compiler parks
     // the conversions of the loaded values, and with them a wait for memory, right behind the loads)
-    if (OPT != kOptNone) load_group<OPT, GRAD_BF16>(rep, tbase, loff, nvalid, in);
+    load_group<OPT, GRAD_BF16>(rep, tbase, loff, nvalid, in);
     __builtin_amdgcn_sched_barrier(0);
 
     // ---- subsets: bit j of a lane's mask = coordinate 4 group + j is received / sent now.
@@ -586,7 +573,7 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint32_t tile
     if (!kShareRecv) {                                     // loads of per-replica arrays that the masks steer
         const uint64_t any_recv = __ballot(s.mask_recv != 0u);
         s.line_recv = ((any_recv >> (lane & ~7u)) & 0xFFull) != 0ull;
-        if (i < R) load_group_sparse<OPT, DIL>(a, i, tbase, loff, nvalid, s, in);
+        if (i < R) load_group_sparse<DIL>(a, i, tbase, loff, nvalid, s, in);
     }
 
     // ---- staging lines of the send start at zero: line tails and the slots of absent replicas stay zero
@@ -596,7 +583,6 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint32_t tile
     if (recv_is_send) {
         if (kShareRecv) __syncthreads();                   // the masks are in LDS
         finish_subsets();
-        if (kEarlyMasks && i < R) load_group_sparse<OPT, DIL>(a, i, tbase, loff, nvalid, s, in);
         if (count_recv) {
             for (uint32_t b = 0; b < a.nblocks; ++b) {
                 const uint32_t ib = b * rb + wave;
@@ -606,8 +592,8 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint32_t tile
                 if (b == b0) {
                     pre = in;
                 } else {
-                    if (OPT != kOptNone) load_group<OPT, GRAD_BF16>(a.rep[8u * b + wave], tbase, loff, nvalid, pre);
-                    load_group_sparse<OPT, DIL>(a, ib, tbase, loff, nvalid, s, pre);
+                    load_group<OPT, GRAD_BF16>(a.rep[8u * b + wave], tbase, loff, nvalid, pre);
+                    load_group_sparse<DIL>(a, ib, tbase, loff, nvalid, s, pre);
                 }
                 local_step<OPT>(a, a.rep[8u * b + wave], ib, pre, w_hat, m_new, v_new);
                 uint32_t c = s.rank_recv;
@@ -620,10 +606,10 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint32_t tile
     // the local optimizer step needs nothing but the wave's own operands: it runs while the lines
     // for LDS and the other waves' operands are still on their way
     F4 w_hat, m_new, v_new;
-    if (!TAU0 && DIL && OPT != kOptNone) local_step<OPT>(a, rep, i, in, w_hat, m_new, v_new);      // (per-replica d: its entries are in registers too)
+    if (!TAU0 && DIL) local_step<OPT>(a, rep, i, in, w_hat, m_new, v_new);      // (per-replica d: its entries are in registers too)
     lds_dma_wait();
     __syncthreads();
-    constexpr bool kEarlyLocal = !TAU0 && DIL && OPT != kOptNone;
+    constexpr bool kEarlyLocal = !TAU0 && DIL;
     if (kEarlyLocal && i < R) {                            // the moments are final: out they go at once
         if (OPT == kOptSgdMomentum || OPT == kOptAdam) store_f32x4(rep.m + tbase, loff, nvalid, m_new);
         if (OPT == kOptAdam) store_f32x4(rep.v + tbase, loff, nvalid, v_new);
@@ -659,8 +645,8 @@ __device__ __forceinline__ void step_tile(const StepArgs &a, const uint32_t tile
                 lds_dma_16(a.d[b] + (uint64_t)tile * tile_floats + d_chunk_off, L.d + wave * 256u);
             if (i < R) {
                 rep = a.rep[8u * b + wave];
-                if (OPT != kOptNone) load_group<OPT, GRAD_BF16>(rep, tbase, loff, nvalid, in);
-                load_group_sparse<OPT, DIL>(a, i, tbase, loff, nvalid, s, in);
+                load_group<OPT, GRAD_BF16>(rep, tbase, loff, nvalid, in);
+                load_group_sparse<DIL>(a, i, tbase, loff, nvalid, s, in);
             }
             lds_dma_wait();
             __syncthreads();
@@ -710,7 +696,7 @@ k_step(const StepArgs a)
 }
 
 // =============================================================================================
-// Averaging alone, tau > 0 (am_sparse_average): subset, send, replica mean, EMA correction and scatter
+// Averaging alone (am_sparse_average): subset, send, replica mean, EMA correction and scatter
 // (asynchronous sparse averaging equations) on weights the caller has already stepped.
 //
 // Only lines that hold a selected coordinate move, so the call lives on how many of those lines are
@@ -757,16 +743,73 @@ __device__ __forceinline__ void store_block_values(float *p, const float (&x)[RB
     }
 }
 
-// grid = (ceil(tiles / 4), blocks); blockDim = 256: four waves, each with a tile of its own (no LDS).
-// DIL: the EMA vectors are interleaved ([coordinate][RB] per block); else one flat array per replica.
+// The values block `b` of the replicas sends for the tile: the RB values of a selected coordinate side
+// by side at the coordinate's rank; the rest of the tile's last line is zero.
+template <int RB>
+__device__ __forceinline__ void average_send_block(float *slot, const F4 (&w)[RB], uint32_t mask_send, uint32_t rank_send,
+                                                   uint32_t count_send, uint32_t room, uint32_t lane)
+{
+    uint32_t c = rank_send;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        if (((mask_send >> j) & 1u) && c < room) {             // (the rank is below that by construction of the table)
+            float x[RB];
+#pragma unroll
+            for (int k = 0; k < RB; ++k) x[k] = w[k].v[j];
+            store_block_values<RB>(slot + (uint64_t)c * RB, x);
+            ++c;
+        }
+    }
+    if (count_send + lane < room) {                            // fewer than 32 / RB <= 32 lanes
+        float x[RB];
+#pragma unroll
+        for (int k = 0; k < RB; ++k) x[k] = 0.f;
+        store_block_values<RB>(slot + (uint64_t)(count_send + lane) * RB, x);
+    }
+}
+
+// Coordinate j of the group receives the old average abar: EMA of the staleness of each replica of the
+// block (own[k] = what replica k itself sent), corrected weight.  dp: the coordinate's RB entries of the
+// interleaved EMA vector (DIL), else the entries are in dv.
 template <bool DIL, int RB>
-__global__ void __launch_bounds__(256)
+__device__ __forceinline__ void average_receive(const StepArgs &a, int j, float abar, const float (&own)[RB], float *dp,
+                                                F4 (&w)[RB], F4 (&dv)[RB])
+{
+    if (a.ema) {
+        float d_new[RB];
+        if (DIL) {
+            load_block_values<RB>(dp, d_new);
+        } else {
+#pragma unroll
+            for (int k = 0; k < RB; ++k) d_new[k] = dv[k].v[j];
+        }
+#pragma unroll
+        for (int k = 0; k < RB; ++k) {
+            d_new[k] = (float)fma(a.coef_d, (double)d_new[k], a.coef_s * ((double)w[k].v[j] - (double)own[k]));
+            w[k].v[j] = (float)((double)abar + (double)d_new[k]);
+            if (!DIL) dv[k].v[j] = d_new[k];
+        }
+        if (DIL) store_block_values<RB>(dp, d_new);
+    } else {
+#pragma unroll
+        for (int k = 0; k < RB; ++k) w[k].v[j] = abar;
+    }
+}
+
+// grid = (ceil(tiles / 4), blocks) (TAU0: (ceil(tiles / 4), 1)); blockDim = 256: four waves, each with
+// a tile of its own (no LDS).
+// DIL: the EMA vectors are interleaved ([coordinate][RB] per block); else one flat array per replica.
+// TAU0: the average is of this very call's values (tau = 0): the wave walks all blocks of its tile,
+// once for the sums and the send, once more for the update (another wave must not rewrite a block's
+// weights while this one still needs them for the mean).
+template <bool DIL, int RB, bool TAU0>
+__global__ void __launch_bounds__(256, (DIL && !TAU0) ? 6 : 4)     // at most 80 (else 128) registers: 24 (16) tiles per compute unit in flight
 k_average(const StepArgs a)
 {
     constexpr uint32_t kPerLine = kLineFloats / RB;                        // coordinates a ring line holds
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const uint32_t tile = blockIdx.x * 4u + wave, b0 = blockIdx.y;
+    const uint32_t tile = blockIdx.x * 4u + wave, b0 = TAU0 ? 0u : blockIdx.y;
     if (tile >= a.ntiles) return;
     const uint32_t R = a.replicas;
     const uint64_t group = (uint64_t)tile * 64u + lane;
@@ -779,7 +822,7 @@ k_average(const StepArgs a)
     // ---- the subsets: bit j of a lane's mask = coordinate 4 group + j is received / sent now
     uint32_t mask_recv = 0, mask_send = 0;
     SubsetKey key = a.key;
-    if (a.do_recv) {
+    if (a.do_recv && !TAU0) {
         key.step_lo = a.step_lo[0]; key.step_hi = a.step_hi[0];
         mask_recv = member_mask(key, group, nvalid);
     }
@@ -798,109 +841,122 @@ k_average(const StepArgs a)
     //      capacity is left out, at send and at receive alike
     uint32_t word_s = 0, base_s = 0, word_r = 0, base_r = 0;
     if (a.do_send) { word_s = uniform_load(a.send_meta, tile); base_s = uniform_load(a.send_sb_base, tile / kTilesPerSuperblock); }
-    if (a.do_recv) { word_r = uniform_load(a.recv_meta, tile); base_r = uniform_load(a.recv_sb_base, tile / kTilesPerSuperblock); }
+    if (a.do_recv && !TAU0) { word_r = uniform_load(a.recv_meta, tile); base_r = uniform_load(a.recv_sb_base, tile / kTilesPerSuperblock); }
     const uint32_t first_s = base_s + (word_s & 0xFFFFFFu), first_r = base_r + (word_r & 0xFFFFFFu);
     uint32_t lines_s = word_s >> 24, lines_r = word_r >> 24;
     if ((uint64_t)first_s + lines_s > a.cap_lines) { lines_s = 0; mask_send = 0u; }
     if ((uint64_t)first_r + lines_r > a.cap_lines) { lines_r = 0; mask_recv = 0u; }
+    if (TAU0) mask_recv = mask_send;                                       // what is sent now is received now
 
     uint32_t count_send, count_recv;
     const uint32_t rank_send = wave_prefix_mask4(mask_send, count_send);
-    const uint32_t rank_recv = wave_prefix_mask4(mask_recv, count_recv);
+    const uint32_t rank_recv = TAU0 ? rank_send : wave_prefix_mask4(mask_recv, count_recv);
+    if (TAU0) count_recv = count_send;
     const uint64_t any_recv = __ballot(mask_recv != 0u);
     const bool line_recv = ((any_recv >> (lane & ~7u)) & 0xFFull) != 0ull;    // my 128-byte line of a per-replica array receives
     const bool need_w = mask_send != 0u || line_recv;
+    const double inv_replicas = 1.0 / (double)R;
 
-    // ---- the weights (and, per-replica layout, the EMA entries) of the block's replicas
     F4 w[RB], dv[RB];
-#pragma unroll
-    for (int k = 0; k < RB; ++k) {
-        const uint32_t i = b0 * RB + k;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) w[k].v[j] = dv[k].v[j] = 0.f;         // (an absent replica sends zeros)
-        if (i < R && need_w) w[k] = load_f32x4(a.rep[8u * b0 + k].w + tbase, loff, nvalid);
-        if (!DIL && a.ema && i < R && line_recv) dv[k] = load_f32x4(a.d[i] + tbase, loff, nvalid);
-    }
-
-    // ---- send: the RB values of a selected coordinate, side by side, at the coordinate's rank;
-    //      the rest of the tile's last line is zero
-    if (a.do_send && lines_s != 0u) {
-        float *slot = a.ring_send + b0 * block_floats + (uint64_t)first_s * kLineFloats;
-        uint32_t c = rank_send;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            if (((mask_send >> j) & 1u) && c < lines_s * kPerLine) {       // (the rank is below that by construction of the table)
-                float x[RB];
-#pragma unroll
-                for (int k = 0; k < RB; ++k) x[k] = w[k].v[j];
-                store_block_values<RB>(slot + (uint64_t)c * RB, x);
-                ++c;
-            }
-        }
-        if (count_send + lane < lines_s * kPerLine) {                      // fewer than kPerLine <= 32 lanes
-            float x[RB];
-#pragma unroll
-            for (int k = 0; k < RB; ++k) x[k] = 0.f;
-            store_block_values<RB>(slot + (uint64_t)(count_send + lane) * RB, x);
-        }
-    }
-
-    // ---- receive: old average of what every replica sent (+ EMA of staleness)
-    if (count_recv != 0u) {                                                // same for the whole wave
-        const float *slot = a.ring_recv + (uint64_t)first_r * kLineFloats;
-        const double inv_replicas = 1.0 / (double)R;
-        uint32_t c = rank_recv;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            if (((mask_recv >> j) & 1u) && c < lines_r * kPerLine) {       // (as above)
-                double sum = 0.;
-                float own[RB];
-                for (uint32_t b = 0; b < a.nblocks; ++b) {
-                    float x[RB];
-                    load_block_values<RB>(slot + b * block_floats + (uint64_t)c * RB, x);
-                    const uint32_t nrep = R - b * RB;                      // replicas present in this block (>= RB: all)
-#pragma unroll
-                    for (int k = 0; k < RB; ++k) {
-                        if (b == b0) own[k] = x[k];                        // my own staleness term takes the exact value
-                        const float q = a.msg_dtype != 0u ? quantize_message(x[k], a.msg_dtype) : x[k];
-                        if ((uint32_t)k < nrep) sum += (double)q;
-                    }
-                }
-                const float abar = (float)(sum * inv_replicas);
-                if (a.ema) {
-                    float d_new[RB];
-                    float *dp = nullptr;
-                    if (DIL) {
-                        dp = a.d[b0] + (tbase + loff + (uint32_t)j) * RB;
-                        load_block_values<RB>(dp, d_new);
-                    } else {
-#pragma unroll
-                        for (int k = 0; k < RB; ++k) d_new[k] = dv[k].v[j];
-                    }
-#pragma unroll
-                    for (int k = 0; k < RB; ++k) {
-                        d_new[k] = (float)fma(a.coef_d, (double)d_new[k], a.coef_s * ((double)w[k].v[j] - (double)own[k]));
-                        w[k].v[j] = (float)((double)abar + (double)d_new[k]);
-                        if (!DIL) dv[k].v[j] = d_new[k];
-                    }
-                    if (DIL) store_block_values<RB>(dp, d_new);
-                } else {
-#pragma unroll
-                    for (int k = 0; k < RB; ++k) w[k].v[j] = abar;
-                }
-                ++c;
-            }
-        }
-    }
-
-    // ---- only lines that received are rewritten
-    if (line_recv) {
+    // the weights (and, per-replica layout, the EMA entries) of block b's replicas; an absent replica counts as zeros
+    auto load_block = [&](const uint32_t b, const bool with_w, const bool with_d) {
 #pragma unroll
         for (int k = 0; k < RB; ++k) {
-            const uint32_t i = b0 * RB + k;
+            const uint32_t i = b * RB + k;
+            if (with_w) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) w[k].v[j] = 0.f;
+                if (i < R && need_w) w[k] = load_f32x4(a.rep[8u * b + k].w + tbase, loff, nvalid);
+            }
+            if (with_d) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) dv[k].v[j] = 0.f;
+                if (!DIL && a.ema && i < R && line_recv) dv[k] = load_f32x4(a.d[i] + tbase, loff, nvalid);
+            }
+        }
+    };
+    // only lines that received are rewritten
+    auto store_block = [&](const uint32_t b) {
+        if (!line_recv) return;
+#pragma unroll
+        for (int k = 0; k < RB; ++k) {
+            const uint32_t i = b * RB + k;
             if (i >= R) continue;
-            store_f32x4(a.rep[8u * b0 + k].w + tbase, loff, nvalid, w[k]);
+            store_f32x4(a.rep[8u * b + k].w + tbase, loff, nvalid, w[k]);
             if (!DIL && a.ema) store_f32x4(a.d[i] + tbase, loff, nvalid, dv[k]);
+        }
+    };
+
+    if constexpr (!TAU0) {
+        load_block(b0, true, true);
+        if (a.do_send && lines_s != 0u)
+            average_send_block<RB>(a.ring_send + b0 * block_floats + (uint64_t)first_s * kLineFloats, w, mask_send, rank_send,
+                                   count_send, lines_s * kPerLine, lane);
+        // ---- receive: old average of what every replica sent (+ EMA of staleness)
+        if (count_recv != 0u) {                                            // same for the whole wave
+            const float *slot = a.ring_recv + (uint64_t)first_r * kLineFloats;
+            uint32_t c = rank_recv;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (((mask_recv >> j) & 1u) && c < lines_r * kPerLine) {   // (as at the send)
+                    double sum = 0.;
+                    float own[RB];
+                    for (uint32_t b = 0; b < a.nblocks; ++b) {
+                        float x[RB];
+                        load_block_values<RB>(slot + b * block_floats + (uint64_t)c * RB, x);
+                        const uint32_t nrep = R - b * RB;                  // replicas present in this block (>= RB: all)
+#pragma unroll
+                        for (int k = 0; k < RB; ++k) {
+                            if (b == b0) own[k] = x[k];                    // my own staleness term takes the exact value
+                            const float q = a.msg_dtype != 0u ? quantize_message(x[k], a.msg_dtype) : x[k];
+                            if ((uint32_t)k < nrep) sum += (double)q;
+                        }
+                    }
+                    average_receive<DIL, RB>(a, j, (float)(sum * inv_replicas), own,
+                                             DIL ? a.d[b0] + (tbase + loff + (uint32_t)j) * RB : nullptr, w, dv);
+                    ++c;
+                }
+            }
+        }
+        store_block(b0);
+    } else {
+        // ---- first walk: every block sends, and the sums over all replicas (in replica order) build up
+        double sum[4] = {0., 0., 0., 0.};
+        for (uint32_t b = 0; b < a.nblocks; ++b) {
+            load_block(b, true, false);
+            if (lines_s != 0u)
+                average_send_block<RB>(a.ring_send + b * block_floats + (uint64_t)first_s * kLineFloats, w, mask_send, rank_send,
+                                       count_send, lines_s * kPerLine, lane);
+            const uint32_t nrep = R - b * RB;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (!((mask_recv >> j) & 1u)) continue;
+#pragma unroll
+                for (int k = 0; k < RB; ++k) {
+                    const float q = a.msg_dtype != 0u ? quantize_message(w[k].v[j], a.msg_dtype) : w[k].v[j];
+                    if ((uint32_t)k < nrep) sum[j] += (double)q;
+                }
+            }
+        }
+        // ---- second walk: the update of every block (one block: its weights are still in registers)
+        if (count_recv != 0u) {
+            for (uint32_t b = 0; b < a.nblocks; ++b) {
+                if (a.nblocks > 1u) load_block(b, true, false);
+                load_block(b, false, true);
+                uint32_t c = rank_recv;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    if (((mask_recv >> j) & 1u) && c < lines_s * kPerLine) {
+                        float own[RB];
+#pragma unroll
+                        for (int k = 0; k < RB; ++k) own[k] = w[k].v[j];   // no delay: what was sent is this very value
+                        average_receive<DIL, RB>(a, j, (float)(sum[j] * inv_replicas), own,
+                                                 DIL ? a.d[b] + (tbase + loff + (uint32_t)j) * RB : nullptr, w, dv);
+                        ++c;
+                    }
+                }
+                store_block(b);
+            }
         }
     }
 }

@@ -220,13 +220,8 @@ am_status launch_step_tau(am_state *st, const am::StepArgs &a)
     const bool tau0 = a.do_recv && a.same_slot;
     const dim3 grid(st->lay.ntiles, tau0 ? 1u : B.nblocks), block(64u * B.rb);
     const size_t lds = (size_t)am::step_lds_floats(B.rb, B.nblocks, DIL) * sizeof(float);
-    if constexpr (OPT == am::kOptNone) {                   // averaging alone: only tau = 0 runs here (else k_average)
-        if (!tau0) return fail(AM_EINVAL, "internal: averaging-only launch of the fused kernel with tau > 0");
-        am::k_step<OPT, GBF, FWD, DIL, true><<<grid, block, lds, st->stream>>>(a);
-    } else {
-        if (tau0) am::k_step<OPT, GBF, FWD, DIL, true><<<grid, block, lds, st->stream>>>(a);
-        else am::k_step<OPT, GBF, FWD, DIL, false><<<grid, block, lds, st->stream>>>(a);
-    }
+    if (tau0) am::k_step<OPT, GBF, FWD, DIL, true><<<grid, block, lds, st->stream>>>(a);
+    else am::k_step<OPT, GBF, FWD, DIL, false><<<grid, block, lds, st->stream>>>(a);
     AM_HIP(hipGetLastError());
     return AM_OK;
 }
@@ -252,17 +247,18 @@ am_status launch_step_grad(am_state *st, const am::StepArgs &a)
     return st->cfg.grad_dtype == AM_BF16 ? launch_step_fwd<OPT, true>(st, a) : launch_step_fwd<OPT, false>(st, a);
 }
 
-// The averaging-only kernel (tau > 0): one wave per (tile, block of replicas).
-template <bool DIL>
+// The averaging-only kernel: one wave per (tile, block of replicas); with tau = 0 (the average is of this
+// call's own values) one wave per tile, which walks the blocks.
+template <bool DIL, bool TAU0>
 am_status launch_average(am_state *st, const am::StepArgs &a)
 {
     const am_host::Blocks &B = st->lay.blocks;
-    const dim3 grid((st->lay.ntiles + 3u) / 4u, B.nblocks), block(256);
+    const dim3 grid((st->lay.ntiles + 3u) / 4u, TAU0 ? 1u : B.nblocks), block(256);
     switch (B.rb) {
-    case 8: am::k_average<DIL, 8><<<grid, block, 0, st->stream>>>(a); break;
-    case 4: am::k_average<DIL, 4><<<grid, block, 0, st->stream>>>(a); break;
-    case 2: am::k_average<DIL, 2><<<grid, block, 0, st->stream>>>(a); break;
-    default: am::k_average<DIL, 1><<<grid, block, 0, st->stream>>>(a); break;
+    case 8: am::k_average<DIL, 8, TAU0><<<grid, block, 0, st->stream>>>(a); break;
+    case 4: am::k_average<DIL, 4, TAU0><<<grid, block, 0, st->stream>>>(a); break;
+    case 2: am::k_average<DIL, 2, TAU0><<<grid, block, 0, st->stream>>>(a); break;
+    default: am::k_average<DIL, 1, TAU0><<<grid, block, 0, st->stream>>>(a); break;
     }
     AM_HIP(hipGetLastError());
     return AM_OK;
@@ -662,13 +658,9 @@ am_status am_sparse_average(am_state *st, uint64_t t, float lambda_t)
             a.next_lines = st->next_lines();
         }
         const bool dil = st->cfg.d_layout == AM_D_INTERLEAVED && a.ema;
-        if (r.recv && r.same_slot) {
-            // tau = 0, the average is of this call's own values: the fused kernel with the optimizer pass
-            // left out (w^ = w), whose workgroups see every replica of a tile
-            if (am_status s = launch_step_layout<am::kOptNone, false, am::kFwdNone>(st, a)) return s;
-        } else {
-            if (am_status s = dil ? launch_average<true>(st, a) : launch_average<false>(st, a)) return s;
-        }
+        const bool tau0 = r.recv && r.same_slot;           // the average is of this call's own values
+        if (am_status s = dil ? (tau0 ? launch_average<true, true>(st, a) : launch_average<true, false>(st, a))
+                              : (tau0 ? launch_average<false, true>(st, a) : launch_average<false, false>(st, a))) return s;
         if (do_next) st->next_lines_step = t + 1;
     }
     st->last_t = t;
