@@ -562,6 +562,7 @@ def run_average(am, n, R, steps, seed=17, lam=0.5, **kw):
     (50_000, 16, 1, 1, 1.0, O.CORR_EMA), (50_000, 32, 2, 1, 0.01, O.CORR_EMA), (50_000, 7, 1, 1, EMPTY_P, O.CORR_EMA),
     (1, 1, 1, 1, 1.0, O.CORR_EMA), (1003, 1, 2, 1, 0.3, O.CORR_EMA), (1003, 8, 2, 1, 0.3, O.CORR_EMA),
     (40_001, 12, 1, 3, 0.3, O.CORR_EMA), (40_001, 20, 3, 1, 0.1, O.CORR_NONE), (40_001, 9, 0, 2, 0.1, O.CORR_EMA),
+    (20_001, 32, 0, 1, 0.2, O.CORR_EMA), (20_001, 16, 0, 1, 1.0, O.CORR_NONE), (20_003, 6, 0, 1, 0.05, O.CORR_EMA),
 ])
 @both_layouts
 def test_sparse_average_alone(amlib, n, R, tau, K, p, corr, d_layout):
@@ -576,6 +577,7 @@ def test_sparse_average_quantised_exchange(amlib, msg, d_layout):
     """The mean takes the rounded messages, a replica's own staleness term its exact value."""
     run_average(amlib, 30_011, 5, 8, delay=2, fraction=0.2, msg_dtype=msg, d_layout=d_layout)
     run_average(amlib, 30_011, 11, 5, delay=1, fraction=0.2, msg_dtype=msg, d_layout=d_layout)
+    run_average(amlib, 30_011, 11, 4, delay=0, fraction=0.2, msg_dtype=msg, d_layout=d_layout)
 
 
 @both_layouts
